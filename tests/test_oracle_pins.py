@@ -1,0 +1,240 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, written out
+independently of the oracle's own code.  None of these tests touches the GPU."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import F32, F64, C64, C128
+
+REAL = {F32: np.float32, F64: np.float64, C64: np.float32, C128: np.float64}
+COMPS = {F32: 1, F64: 1, C64: 2, C128: 2}
+
+
+def prod(xs):
+    n = 1
+    for x in xs:
+        n *= x
+    return n
+
+
+def rand(dtype, n, seed):
+    return np.random.default_rng(seed).uniform(-1, 1, n * COMPS[dtype]).astype(REAL[dtype])
+
+
+def run(dtype, sizes, perm, alpha, beta, A, B0=None, nthreads=1):
+    B = np.full(prod(sizes) * COMPS[dtype], np.nan, REAL[dtype]) if B0 is None else B0.copy()
+    return oracle.transpose(dtype, sizes, perm, alpha, beta, A, B, nthreads)
+
+
+def ulp(x, real):
+    return float(np.spacing(np.abs(real(x))))
+
+
+# -- pin 1: closed-form address map printed in the paper's parallel-code listing (Section 3.5):
+#    permutation (i3,i2,i1) reads A[i1 + i2*lda1 + i3*lda2] and writes B[i1*ldb2 + i2*ldb1 + i3].
+@pytest.mark.parametrize("sizes", [(2, 3, 4), (5, 1, 3), (7, 6, 5)])
+def test_listing_address_map_reversal_3d(sizes):
+    s0, s1, s2 = sizes
+    lda1, lda2 = s0, s0 * s1          # dense A
+    ldb1, ldb2 = s2, s2 * s1          # dense B with extents (s2, s1, s0)
+    A = np.arange(prod(sizes), dtype=np.float32)
+    B = run(F32, sizes, (2, 1, 0), 1.0, 0.0, A)
+    for i3 in range(s2):
+        for i2 in range(s1):
+            for i1 in range(s0):
+                assert B[i1 * ldb2 + i2 * ldb1 + i3] == A[i1 + i2 * lda1 + i3 * lda2]
+
+
+# -- pin 2: the 2-D case with alpha=1, beta=0 is the ordinary matrix transpose (Section 1).
+@pytest.mark.parametrize("m,n", [(1, 1), (3, 5), (8, 2), (17, 13)])
+def test_2d_is_textbook_transpose(m, n):
+    A = rand(F64, m * n, 1)
+    B = run(F64, (m, n), (1, 0), 1.0, 0.0, A)
+    for i in range(m):
+        for j in range(n):
+            assert B[j + i * n] == A[i + j * m]
+
+
+# -- pin 3: the identity permutation is axpby on the flat arrays (Eq. 1 with Pi = id).
+@pytest.mark.parametrize("dtype", [F32, F64])
+def test_identity_is_axpby(dtype):
+    sizes = (3, 4, 5)
+    A, B0 = rand(dtype, 60, 2), rand(dtype, 60, 3)
+    B = run(dtype, sizes, (0, 1, 2), 2.0, -1.0, A, B0)       # 2a - b is exact in one rounding
+    want = (2.0 * A.astype(np.float64) - B0.astype(np.float64)).astype(REAL[dtype])
+    assert np.array_equal(B, want)
+    B = run(dtype, sizes, (0, 1, 2), 1.0, 0.0, A, B0)
+    assert np.array_equal(B, A)
+
+
+# -- pin 4: Pi followed by its inverse reproduces A bit for bit.
+@pytest.mark.parametrize("seed", range(6))
+def test_round_trip_with_inverse(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(2, 7))
+    sizes = tuple(int(x) for x in rng.integers(1, 6, n))
+    perm = tuple(int(x) for x in rng.permutation(n))
+    inv = [0] * n
+    for j, k in enumerate(perm):
+        inv[k] = j
+    A = rand(F32, prod(sizes), seed)
+    B = run(F32, sizes, perm, 1.0, 0.0, A)
+    sizes_b = tuple(sizes[perm[j]] for j in range(n))
+    back = run(F32, sizes_b, tuple(inv), 1.0, 0.0, B)
+    assert np.array_equal(back, A)
+
+
+# -- pin 5: applying p then q equals applying the composed permutation once.
+@pytest.mark.parametrize("seed", range(6))
+def test_composition(seed):
+    rng = np.random.default_rng(200 + seed)
+    n = int(rng.integers(2, 6))
+    sizes = tuple(int(x) for x in rng.integers(1, 6, n))
+    p = tuple(int(x) for x in rng.permutation(n))
+    q = tuple(int(x) for x in rng.permutation(n))
+    A = rand(F64, prod(sizes), seed)
+    B = run(F64, sizes, p, 1.0, 0.0, A)
+    sizes_b = tuple(sizes[p[j]] for j in range(n))
+    C = run(F64, sizes_b, q, 1.0, 0.0, B)
+    # index j of C is index q[j] of B, which is index p[q[j]] of A
+    pq = tuple(p[q[j]] for j in range(n))
+    assert np.array_equal(C, run(F64, sizes, pq, 1.0, 0.0, A))
+
+
+# -- pin 6: merged-index invariant, the paper's own example (Section 3, stage (1)):
+#    Pi(i1,i2,i3) = (i2,i3,i1) is the 2-D transposition (i~2, i1) with size(i~2) = size(i2)*size(i3).
+@pytest.mark.parametrize("sizes", [(2, 3, 4), (5, 2, 7), (1, 4, 3)])
+def test_merge_example(sizes):
+    s0, s1, s2 = sizes
+    A, B0 = rand(F32, prod(sizes), 5), rand(F32, prod(sizes), 6)
+    B3 = run(F32, sizes, (1, 2, 0), 1.5, 0.5, A, B0)
+    B2 = run(F32, (s0, s1 * s2), (1, 0), 1.5, 0.5, A, B0)
+    assert np.array_equal(B3, B2)
+
+
+# -- pin 7: C walker vs the definition written out element by element, every permutation
+#    of up to 4 indices on tiny extents (includes non-involutions, where perm and its
+#    inverse differ).
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_walker_vs_element_map_all_perms(n):
+    extents = [1, 2, 3, 5]
+    for perm in itertools.permutations(range(n)):
+        for shift in range(2):
+            sizes = tuple(extents[(k + shift + perm[0]) % 4] for k in range(n))
+            A = np.arange(1, prod(sizes) + 1, dtype=np.float64)
+            B = run(F64, sizes, perm, 1.0, 0.0, A)
+            emap = oracle.element_map(sizes, perm)
+            assert sorted(emap) == list(range(prod(sizes)))       # a bijection
+            for off_a, off_b in enumerate(emap):
+                assert B[off_b] == A[off_a], (sizes, perm, off_a)
+
+
+def test_element_map_by_hand():
+    # sizes (2,3), perm (1,0): A[i + 2j] -> B[j + 3i]
+    assert oracle.element_map((2, 3), (1, 0)) == [0, 3, 1, 4, 2, 5]
+    # sizes (2,2,2), perm (1,2,0): B index order (i1,i2,i0): off_b = i1 + 2*i2 + 4*i0
+    assert oracle.element_map((2, 2, 2), (1, 2, 0)) == [0, 4, 1, 5, 2, 6, 3, 7]
+
+
+# -- pin 8: numpy.transpose on Fortran-ordered arrays is an independent implementation of
+#    the same definition (B.shape[j] = A.shape[perm[j]]).
+@pytest.mark.parametrize("seed", range(8))
+def test_matches_numpy_fortran_transpose(seed):
+    rng = np.random.default_rng(300 + seed)
+    n = int(rng.integers(2, 7))
+    sizes = tuple(int(x) for x in rng.integers(1, 7, n))
+    perm = tuple(int(x) for x in rng.permutation(n))
+    A = rand(F32, prod(sizes), seed)
+    B = run(F32, sizes, perm, 1.0, 0.0, A, nthreads=1 + seed % 3)
+    want = np.transpose(A.reshape(sizes, order="F"), perm).reshape(-1, order="F")
+    assert np.array_equal(B, want)
+
+
+def test_complex_permutation_moves_pairs():
+    sizes, perm = (3, 4, 2), (2, 0, 1)
+    A = rand(C64, prod(sizes), 9)
+    B = run(C64, sizes, perm, 1.0, 0.0, A)
+    z = A.view(np.complex64)
+    want = np.transpose(z.reshape(sizes, order="F"), perm).reshape(-1, order="F")
+    assert np.array_equal(B.view(np.complex64), want)
+
+
+# -- pin 9: the alpha/beta arithmetic against exact rational arithmetic.
+@pytest.mark.parametrize("dtype,alpha,beta", [
+    (F32, 1.5, 0.0), (F32, 0.75, 1.25), (F32, 2.0, -1.0), (F32, -0.3, 0.7),
+    (F64, 0.75, 1.25), (F64, 1.5, 0.0), (F64, 1.0 / 3.0, -2.0 / 7.0),
+    (C64, 0.5 + 0.5j, 1.0 + 0.0j), (C64, 0.3 - 0.2j, 0.0), (C64, -1.25 + 2j, 0.5 - 0.75j),
+    (C128, 0.5 + 0.5j, 1.0 + 0.0j), (C128, 0.1 + 0.7j, -0.3 + 0.9j),
+])
+def test_alpha_beta_against_exact_rationals(dtype, alpha, beta):
+    sizes, perm = (3, 2, 4), (2, 0, 1)
+    real = REAL[dtype]
+    A, B0 = rand(dtype, prod(sizes), 11), rand(dtype, prod(sizes), 12)
+    B = run(dtype, sizes, perm, alpha, beta, A, B0)
+    exact = oracle.exact_expected(dtype, sizes, perm, alpha, beta, A, B0)
+    # error budget of the fixed evaluation order: every rounded intermediate contributes
+    # half an ulp of its own magnitude; all magnitudes here are below 8.
+    eps = float(np.finfo(real).eps)
+    for got, want in zip(B, exact):
+        err = abs(Fraction(float(got)) - want)
+        if COMPS[dtype] == 1 and beta == 0:
+            assert err <= Fraction(ulp(got, real)) / 2                 # one rounding
+        elif COMPS[dtype] == 1:
+            # t = round(beta*b); r = round(alpha*a + t)
+            assert err <= Fraction(ulp(got, real)) / 2 + Fraction(eps) * 2
+        else:
+            assert err <= Fraction(eps) * 16
+
+
+def test_exact_one_rounding_case_is_bit_exact():
+    # alpha=2, beta=-1: 2a - b has one rounding under any evaluation order
+    sizes, perm = (4, 3, 5), (1, 2, 0)
+    A, B0 = rand(F32, 60, 21), rand(F32, 60, 22)
+    B = run(F32, sizes, perm, 2.0, -1.0, A, B0)
+    want_lin = (2.0 * A.astype(np.float64))
+    emap = oracle.element_map(sizes, perm)
+    for off_a, off_b in enumerate(emap):
+        assert B[off_b] == np.float32(want_lin[off_a] - np.float64(B0[off_b]))
+
+
+def test_beta_zero_never_reads_b():
+    sizes, perm = (3, 5, 2), (1, 0, 2)
+    A = rand(F32, 30, 31)
+    for alpha in (1.0, 1.5):
+        B = run(F32, sizes, perm, alpha, 0.0, A, np.full(30, np.nan, np.float32))
+        assert not np.isnan(B).any()
+    Bc = run(C64, sizes, perm, 0.5 + 0.5j, 0.0, rand(C64, 30, 32), np.full(60, np.nan, np.float32))
+    assert not np.isnan(Bc).any()
+
+
+def test_alpha_zero_is_not_special():
+    A = np.array([np.nan, 1.0], dtype=np.float32)
+    B = run(F32, (2,), (0,), 0.0, 0.0, A)
+    assert np.isnan(B[0]) and B[1] == 0.0
+
+
+def test_size_one_extents_change_nothing():
+    A = rand(F64, 24, 41)
+    B1 = run(F64, (2, 1, 3, 1, 4), (4, 1, 0, 3, 2), 1.0, 0.0, A)
+    B2 = run(F64, (2, 3, 4), (2, 0, 1), 1.0, 0.0, A)
+    assert np.array_equal(B1, B2)
+
+
+def test_threads_give_identical_results():
+    sizes, perm = (7, 5, 6, 3), (2, 0, 3, 1)
+    A, B0 = rand(F32, prod(sizes), 51), rand(F32, prod(sizes), 52)
+    ref = run(F32, sizes, perm, 0.75, 1.25, A, B0, nthreads=1)
+    for t in (2, 3, 8):
+        assert np.array_equal(ref, run(F32, sizes, perm, 0.75, 1.25, A, B0, nthreads=t))
+
+
+def test_rejects_what_the_definition_does_not_cover():
+    A = np.zeros(6, np.float32)
+    for sizes, perm in [((2, 3), (0, 0)), ((2, 3), (0, 2))]:
+        with pytest.raises(ValueError):
+            oracle.transpose(F32, sizes, perm, 1.0, 0.0, A, np.zeros(6, np.float32))
+    with pytest.raises(ValueError):
+        oracle.transpose(F32, (2, 3), (1, 0), 1.0, 0.0, A, A)
