@@ -1,0 +1,171 @@
+/*
+ * ttc.h -- C ABI of the MI355X tensor-transposition library.
+ *
+ * The operation (paper Eq. 1), out of place, on dense column-major tensors
+ * (leftmost index has stride 1; paper Section 1):
+ *
+ *     B[Pi(i_0..i_{N-1})]  <-  alpha * A[i_0..i_{N-1}]  +  beta * B[Pi(i_0..i_{N-1})]
+ *
+ * perm[j] is the index of A that becomes index j of B (the capital-Pi list of Eq. 1:
+ * Pi(i1,i2,i3) = (i2,i3,i1) is perm = {1,2,0}); B's extents are sizes[perm[j]].
+ *
+ * All functions return integer status codes; nothing throws or aborts across this
+ * boundary.  Plan objects live in host memory and are owned by the library.  Tensor
+ * pointers are DEVICE pointers owned by the caller.  No function here synchronises
+ * the device unless its comment says so.
+ */
+#ifndef TTC_H_
+#define TTC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TTC_MAX_DIM 6
+
+typedef struct ttc_plan_s* ttc_plan_t;
+
+/* Element types (paper Table 1, --dataType s/d/c; z is not built yet). */
+enum { TTC_F32 = 0, TTC_F64 = 1, TTC_C64 = 2 /* interleaved re,im fp32 */, TTC_C128 = 3 /* rejected */ };
+
+enum {
+    TTC_OK = 0,
+    TTC_ERR_INVALID_VALUE = 1,     /* ndim outside 1..6, an extent < 1, bad candidate index, ... */
+    TTC_ERR_INVALID_PERM = 2,      /* perm is not a permutation of 0..ndim-1 */
+    TTC_ERR_UNSUPPORTED_DTYPE = 3,
+    TTC_ERR_NULL_POINTER = 4,
+    TTC_ERR_ALIAS = 5,             /* A and B overlap: the operation is out of place */
+    TTC_ERR_OVERFLOW = 6,          /* element or byte count does not fit */
+    TTC_ERR_HIP = 7,               /* a HIP runtime call failed */
+    TTC_ERR_ALLOC = 8,
+    TTC_ERR_MISALIGNED = 9,        /* pointer not aligned to the element size */
+    TTC_ERR_INTERNAL = 10          /* a candidate failed the host-side bounds check */
+};
+
+/* Kernel families (paper Section 3.1: the stride-1 index keeps its place, or not). */
+enum { TTC_KERNEL_DIRECT = 0 /* no staging: stride-1 index fixed */, TTC_KERNEL_LDS = 1 /* tile staged through LDS */ };
+/* Epilogues chosen from alpha, beta. */
+enum { TTC_EPI_COPY = 0 /* alpha=1, beta=0 */, TTC_EPI_SCALE = 1 /* beta=0: B never read */, TTC_EPI_AXPBY = 2 };
+
+/*
+ * What a plan decided.  "Fused" quantities are after size-1 extents were dropped and
+ * adjacent indices that stay adjacent and in order in B were merged (paper Section 3,
+ * stage (1)).  Arrays are indexed by fused index of A, entries past ndim are 0.
+ */
+typedef struct {
+    int     dtype;
+    int     ndim;                          /* fused number of indices, >= 1 */
+    int64_t sizes[TTC_MAX_DIM];            /* fused extents of A */
+    int     perm[TTC_MAX_DIM];             /* fused permutation */
+    int     stride1_fixed;                 /* 1: paper's case pi(i1)=i1 (or 1-D axpby), 0: stride-1 index changes */
+    int     kernel_class;                  /* TTC_KERNEL_* of the selected candidate */
+    int     epilogue;                      /* TTC_EPI_* */
+    int     tile[TTC_MAX_DIM];             /* extent of the tile (box) along each fused index; 1 = not blocked */
+    int     lane_a[TTC_MAX_DIM];           /* sub-box one wavefront instruction covers on the load side */
+    int     lane_b[TTC_MAX_DIM];           /* ... on the store side */
+    int     tile_order[TTC_MAX_DIM];       /* fused indices from fastest to slowest in the workgroup-id -> tile map */
+    int     lds_stride[TTC_MAX_DIM];       /* element stride of each fused index inside the LDS tile (0 = unused) */
+    int     vec_a, vec_b;                  /* elements per lane per global access on the A side / B side */
+    int     threads;                       /* workgroup size */
+    int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
+    int     lds_bytes;                     /* dynamic LDS per workgroup */
+    int     lds_conflict_a, lds_conflict_b;/* modelled worst bank multiplicity of the LDS write / read instructions */
+    int64_t num_tiles;                     /* = workgroups launched */
+    int64_t elements;                      /* prod(sizes) */
+    int64_t bytes_moved;                   /* 2 or 3 x tensor bytes: read A, write B, read B iff beta != 0 (paper Eq. 2) */
+    int     candidate_index;               /* which candidate is selected */
+    int     candidate_count;               /* how many the plan holds (ranked by the heuristic, best first) */
+    float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
+    double  heuristic_cost;                /* the ranking key: modelled relative cost, smaller is better */
+} ttc_plan_info_t;
+
+/*
+ * Create a plan for one transposition (paper Eq. 1; defaults of Table 1).
+ *   dtype       TTC_F32 / TTC_F64 / TTC_C64.
+ *   ndim        1..TTC_MAX_DIM.
+ *   sizes, perm HOST arrays of length ndim, copied; every extent >= 1.
+ *   alpha, beta HOST pointers to one scalar of dtype (float, double, float[2]);
+ *               NULL means alpha = 1, beta = 0.  Copied.
+ * Touches no device.  Returns NULL on error; ttc_last_status() says why.
+ * The plan holds a ranked list of candidate launch configurations (tile shape, vector
+ * widths, lane mapping, tile order); candidate 0, the heuristic's choice, is selected.
+ */
+ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int* perm,
+                           const void* alpha, const void* beta);
+
+/*
+ * Run the plan: B <- alpha * permute(A) + beta * B (paper Eq. 1).
+ *   A, B    DEVICE pointers to prod(sizes) elements each, dense, column-major, aligned to
+ *           the element size; 16-byte alignment enables the vector paths (else the plan's
+ *           scalar fallback runs).  They must not overlap (TTC_ERR_ALIAS).
+ *   stream  hipStream_t passed as void*; NULL is the default stream.
+ * Asynchronous: enqueues one kernel on `stream`, allocates nothing, never synchronises.
+ * With beta == 0, B is never read.  Returns the launch status.
+ */
+int ttc_execute(ttc_plan_t plan, const void* A, void* B, void* stream);
+
+/* Free a plan.  NULL is a no-op.  Returns TTC_OK. */
+int ttc_plan_destroy(ttc_plan_t plan);
+
+/* Why the last ttc_plan_create on this thread returned NULL (TTC_OK if it did not). */
+int ttc_last_status(void);
+const char* ttc_status_string(int status);
+
+/* Fill *out with the decisions of the selected candidate.  Host only. */
+int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out);
+
+/* Number of candidates the plan holds, or a negative status. */
+int ttc_plan_candidate_count(ttc_plan_t plan);
+/* Select candidate `index` (0 = heuristic best) for later ttc_execute calls.  Host only. */
+int ttc_plan_select_candidate(ttc_plan_t plan, int index);
+
+/*
+ * Search (paper Section 3: candidates are timed and the fastest becomes the solution;
+ * Table 1 --maxImplementations).  Times at most max_candidates candidates, in heuristic
+ * rank order, on the caller's buffers and stream (HIP events, a few launches each) and
+ * selects the fastest.  max_candidates: 0 = environment TTC_MAX_CANDIDATES or 200,
+ * 1 = keep the heuristic choice without timing, -1 = all candidates.
+ * A_scratch / B_scratch are DEVICE buffers of prod(sizes) elements; B_scratch is
+ * overwritten.  SYNCHRONISES the stream.
+ */
+int ttc_plan_tune(ttc_plan_t plan, const void* A_scratch, void* B_scratch, void* stream,
+                  int max_candidates);
+
+/*
+ * Measurement helper: enqueue `warmup` untimed and `iters` timed ttc_execute calls on
+ * `stream`, launch i using the buffer pair (A_list[i % npairs], B_list[i % npairs])
+ * (HOST arrays of DEVICE pointers; rotating pairs keeps the last-level cache from holding
+ * the working set), bracket the timed launches with HIP events recorded on `stream`, wait
+ * for them, and return the mean milliseconds per launch in *ms_per_launch.  SYNCHRONISES.
+ */
+int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                     void* stream, int warmup, int iters, float* ms_per_launch);
+
+/*
+ * Bandwidth ceilings measured the same way (the role of the STREAM/SAXPY lines in the
+ * paper's Section 4).  kind 0: dst <- src with a 128-bit-per-lane copy kernel (1 read, 1
+ * write); kind 1: hipMemcpyAsync device-to-device; kind 2: dst <- 0.75*src + 1.25*dst as
+ * fp32 (2 reads, 1 write).  `bytes` must be a multiple of 16 and the pointers 16-byte
+ * aligned.  Buffer pairs rotate as in ttc_time_execute.  SYNCHRONISES.
+ */
+int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src_list,
+                     void* const* dst_list, void* stream, int warmup, int iters,
+                     float* ms_per_launch);
+
+/*
+ * Host-side bounds checker for the planner and the kernels' index arithmetic; it is a test
+ * aid, never part of ttc_execute.  Replays the walk of the selected candidate lane by lane on
+ * the host, with the index code the kernels are compiled from, and writes to b_from_a[o]
+ * (HOST array of prod(sizes) entries) the element offset of A that the candidate moves to
+ * element offset o of B (the element map of paper Eq. 1).  Returns TTC_ERR_INTERNAL if any
+ * access would leave the tensors or the LDS tile, a vector access would be misaligned, or an
+ * element of B would be written twice or not at all.  Cost grows with prod(sizes).
+ */
+int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TTC_H_ */

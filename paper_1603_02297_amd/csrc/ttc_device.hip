@@ -1,0 +1,449 @@
+// Device side of the library for gfx950 (MI355X): the tile ("box") kernels, their launch,
+// the timed search over candidates and the measurement helpers.
+//
+// One kernel template serves both cases of the paper's Section 3.1.
+//   * staged (stride-1 index changes):  a workgroup owns one box of the tensor that spans the
+//     leading indices of A *and* of B.  Wavefronts walk the box in A order with vector loads
+//     (lanes along A's stride-1 index), park it in LDS, and after one barrier walk it again in B
+//     order (lanes along B's stride-1 index), apply the alpha/beta epilogue and store vectors.
+//   * direct (stride-1 index fixed, or 1-D):  the same walk, but every lane stores what it
+//     loaded; no LDS, no barrier.
+// A walk is factorised CDNA-style: the 64 lanes of a wavefront cover a fixed sub-box (lane
+// offsets are computed once and live in VGPRs), and the position of that sub-box inside the
+// tile is wave-uniform, so the per-instruction index arithmetic runs on the scalar unit.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "ttc_internal.h"
+#include "ttc_walk.h"
+
+namespace ttc {
+
+// ---------------------------------------------------------------------------------
+// Element types and the alpha/beta epilogue (fixed evaluation order; built with
+// -ffp-contract=off so the only fused operations are the ones written here).
+//   real:    copy: r = a | scale: r = alpha*a | axpby: t = beta*b, r = fma(alpha, a, t)
+//   complex: product z = s*x as z.re = fma(s.re, x.re, -(s.im*x.im)), z.im = fma(s.re, x.im, s.im*x.re);
+//            scale: r = alpha*a | axpby: r = alpha*a + beta*b componentwise
+// ---------------------------------------------------------------------------------
+struct alignas(8) cfloat { float re, im; };
+
+template <typename T, int V> struct alignas(sizeof(T) * V) Pack { T v[V]; };
+
+template <typename T, int MODE> struct Epilogue;
+
+template <int MODE> struct Epilogue<float, MODE> {
+    float al, be;
+    __device__ explicit Epilogue(const KernelParams& p) : al((float)p.alpha[0]), be((float)p.beta[0]) {}
+    __device__ __forceinline__ float operator()(float a, float b) const
+    {
+        if (MODE == TTC_EPI_COPY) return a;
+        if (MODE == TTC_EPI_SCALE) return al * a;
+        const float t = be * b;
+        return __builtin_fmaf(al, a, t);
+    }
+};
+
+template <int MODE> struct Epilogue<double, MODE> {
+    double al, be;
+    __device__ explicit Epilogue(const KernelParams& p) : al(p.alpha[0]), be(p.beta[0]) {}
+    __device__ __forceinline__ double operator()(double a, double b) const
+    {
+        if (MODE == TTC_EPI_COPY) return a;
+        if (MODE == TTC_EPI_SCALE) return al * a;
+        const double t = be * b;
+        return __builtin_fma(al, a, t);
+    }
+};
+
+template <int MODE> struct Epilogue<cfloat, MODE> {
+    float ar, ai, br, bi;
+    __device__ explicit Epilogue(const KernelParams& p)
+        : ar((float)p.alpha[0]), ai((float)p.alpha[1]), br((float)p.beta[0]), bi((float)p.beta[1]) {}
+    __device__ __forceinline__ cfloat operator()(cfloat a, cfloat b) const
+    {
+        if (MODE == TTC_EPI_COPY) return a;
+        cfloat p;
+        p.re = __builtin_fmaf(ar, a.re, -(ai * a.im));
+        p.im = __builtin_fmaf(ar, a.im, ai * a.re);
+        if (MODE == TTC_EPI_SCALE) return p;
+        cfloat q;
+        q.re = __builtin_fmaf(br, b.re, -(bi * b.im));
+        q.im = __builtin_fmaf(br, b.im, bi * b.re);
+        cfloat r;
+        r.re = p.re + q.re;
+        r.im = p.im + q.im;
+        return r;
+    }
+};
+
+// ---------------------------------------------------------------------------------
+// The kernel
+// ---------------------------------------------------------------------------------
+constexpr int kUnroll = 4;     // memory instructions a wavefront keeps in flight per walk step
+
+template <typename T, int MODE, int VA, int VB, bool DIRECT>
+__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const T* __restrict__ A,
+                                                          T* __restrict__ B)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    T* lds = reinterpret_cast<T*>(smem_raw);
+
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t nwave = blockDim.x >> 6;
+
+    const TilePos tp = tile_pos(p, tile_of_workgroup(p, blockIdx.x));
+    const int32_t* lim = tp.lim;
+    const int64_t base_a = tp.base_a, base_b = tp.base_b;
+    const T* __restrict__ At = A + base_a;
+    T* __restrict__ Bt = B + base_b;
+    const Epilogue<T, MODE> epi(p);
+
+    if (DIRECT) {
+        const LaneState L = lane_setup<true>(p, p.a, p.stride_a, lane);
+        const uint32_t n_it = (uint32_t)p.a.n_iter;
+        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
+            Pack<T, VA> ra[kUnroll], rb[kUnroll];
+            bool ok[kUnroll];
+            int64_t ob[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t it = it0 + u * nwave;
+                ok[u] = false;
+                if (it < n_it) {
+                    const IterPos q = iter_pos<true>(p, p.a, p.stride_a, lim, L, it);
+                    ok[u] = q.valid;
+                    ob[u] = q.g2 + L.g2;
+                    if (q.valid) {
+                        ra[u] = *reinterpret_cast<const Pack<T, VA>*>(At + (q.g + L.g));
+                        if (MODE == TTC_EPI_AXPBY) rb[u] = *reinterpret_cast<const Pack<T, VA>*>(Bt + ob[u]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (ok[u]) {
+                    Pack<T, VA> out;
+#pragma unroll
+                    for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
+                    *reinterpret_cast<Pack<T, VA>*>(Bt + ob[u]) = out;
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- walk 1: A order, global -> LDS
+    {
+        const LaneState L = lane_setup<false>(p, p.a, p.stride_a, lane);
+        const uint32_t n_it = (uint32_t)p.a.n_iter;
+        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
+            Pack<T, VA> ra[kUnroll];
+            bool ok[kUnroll];
+            int32_t lo[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t it = it0 + u * nwave;
+                ok[u] = false;
+                if (it < n_it) {
+                    const IterPos q = iter_pos<false>(p, p.a, p.stride_a, lim, L, it);
+                    ok[u] = q.valid;
+                    lo[u] = q.l + L.l;
+                    if (q.valid) ra[u] = *reinterpret_cast<const Pack<T, VA>*>(At + (q.g + L.g));
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (ok[u]) {
+#pragma unroll
+                    for (int j = 0; j < VA; ++j) lds[lo[u] + j] = ra[u].v[j];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // ---- walk 2: B order, LDS -> epilogue -> global
+    {
+        const LaneState L = lane_setup<false>(p, p.b, p.stride_b, lane);
+        const uint32_t n_it = (uint32_t)p.b.n_iter;
+        const int32_t vs = p.b.vec_lds_stride;
+        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
+            Pack<T, VB> rb[kUnroll];
+            bool ok[kUnroll];
+            int32_t lo[kUnroll];
+            int64_t ob[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t it = it0 + u * nwave;
+                ok[u] = false;
+                if (it < n_it) {
+                    const IterPos q = iter_pos<false>(p, p.b, p.stride_b, lim, L, it);
+                    ok[u] = q.valid;
+                    lo[u] = q.l + L.l;
+                    ob[u] = q.g + L.g;
+                    if (MODE == TTC_EPI_AXPBY) {
+                        if (q.valid) rb[u] = *reinterpret_cast<const Pack<T, VB>*>(Bt + ob[u]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (ok[u]) {
+                    Pack<T, VB> out;
+#pragma unroll
+                    for (int j = 0; j < VB; ++j) {
+                        const T a = lds[lo[u] + j * vs];
+                        out.v[j] = epi(a, MODE == TTC_EPI_AXPBY ? rb[u].v[j] : a);
+                    }
+                    *reinterpret_cast<Pack<T, VB>*>(Bt + ob[u]) = out;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Dispatch
+// ---------------------------------------------------------------------------------
+using KernelFn = void (*)(const KernelParams, const void*, void*);
+
+template <typename T, int MODE, int VA, int VB, bool DIRECT>
+static hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uint32_t grid, int threads,
+                             int lds_bytes, hipStream_t stream)
+{
+    hipLaunchKernelGGL((box_kernel<T, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
+                       kp, static_cast<const T*>(A), static_cast<T*>(B));
+    return hipGetLastError();
+}
+
+template <typename T, int MODE, int VMAX>
+static hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
+{
+    const KernelParams& kp = c.kp;
+    const uint32_t grid = kp.num_tiles;
+    const int va = kp.a.vec, vb = kp.b.vec;
+    if (c.kernel_class == TTC_KERNEL_DIRECT) {
+        if (va == 1) return launch_one<T, MODE, 1, 1, true>(kp, A, B, grid, c.threads, 0, s);
+        if (va == 2) return launch_one<T, MODE, 2, 2, true>(kp, A, B, grid, c.threads, 0, s);
+        if (va == 4 && VMAX >= 4) return launch_one<T, MODE, (VMAX >= 4 ? 4 : 1), (VMAX >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, 0, s);
+        return hipErrorInvalidValue;
+    }
+#define TTC_CASE(VA_, VB_)                                                                                   \
+    if (va == VA_ && vb == VB_)                                                                              \
+        return launch_one<T, MODE, (VA_ <= VMAX ? VA_ : 1), (VB_ <= VMAX ? VB_ : 1), false>(kp, A, B, grid,    \
+                                                                                            c.threads, c.lds_bytes, s);
+    TTC_CASE(1, 1) TTC_CASE(1, 2) TTC_CASE(2, 1) TTC_CASE(2, 2)
+    if (VMAX >= 4) { TTC_CASE(1, 4) TTC_CASE(2, 4) TTC_CASE(4, 1) TTC_CASE(4, 2) TTC_CASE(4, 4) }
+#undef TTC_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename T, int VMAX>
+static hipError_t launch_mode(const Problem& P, const Candidate& c, const void* A, void* B, hipStream_t s)
+{
+    switch (P.epilogue) {
+    case TTC_EPI_COPY:  return launch_vec<T, TTC_EPI_COPY, VMAX>(c, A, B, s);
+    case TTC_EPI_SCALE: return launch_vec<T, TTC_EPI_SCALE, VMAX>(c, A, B, s);
+    default:            return launch_vec<T, TTC_EPI_AXPBY, VMAX>(c, A, B, s);
+    }
+}
+
+static hipError_t launch(const Problem& P, const Candidate& c, const void* A, void* B, hipStream_t s)
+{
+    if (c.threads < kWave || c.threads > kMaxThreads || (c.threads % kWave) != 0) return hipErrorInvalidValue;
+    if (c.lds_bytes > kMaxLdsBytes) return hipErrorInvalidValue;
+    switch (P.dtype) {
+    case TTC_F32: return launch_mode<float, 4>(P, c, A, B, s);
+    case TTC_F64: return launch_mode<double, 2>(P, c, A, B, s);
+    case TTC_C64: return launch_mode<cfloat, 2>(P, c, A, B, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+static int check_buffers(const ttc_plan_s* plan, const void* A, const void* B)
+{
+    if (!plan || !A || !B) return TTC_ERR_NULL_POINTER;
+    const Problem& P = plan->prob;
+    const uintptr_t a = (uintptr_t)A, b = (uintptr_t)B;
+    const int align = (P.dtype == TTC_F32) ? 4 : (P.dtype == TTC_F64 ? 8 : 4);   // complex64: its real type
+    if (a % align || b % align) return TTC_ERR_MISALIGNED;
+    if (P.dtype == TTC_C64 && (a % 8 || b % 8)) return TTC_ERR_MISALIGNED;       // pairs are moved as 8-byte units
+    const uintptr_t bytes = (uintptr_t)P.elements * P.elem_bytes;
+    if (a < b + bytes && b < a + bytes) return TTC_ERR_ALIAS;
+    return TTC_OK;
+}
+
+static const Candidate& pick_candidate(const ttc_plan_s* plan, const void* A, const void* B)
+{
+    const Candidate& c = plan->cands[plan->selected];
+    const bool aligned16 = (((uintptr_t)A | (uintptr_t)B) % 16) == 0;
+    if (!aligned16 && (c.kp.a.vec > 1 || c.kp.b.vec > 1)) return plan->cands[plan->fallback];
+    return c;
+}
+
+// ---------------------------------------------------------------------------------
+// Ceiling kernels
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n)
+{
+    const int64_t base = (int64_t)blockIdx.x * (256 * 4) + threadIdx.x;
+    uint4 r[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (base + u * 256 < n) r[u] = src[base + u * 256];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (base + u * 256 < n) dst[base + u * 256] = r[u];
+}
+
+__global__ __launch_bounds__(256) void axpby_kernel(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n)
+{
+    const int64_t base = (int64_t)blockIdx.x * (256 * 4) + threadIdx.x;
+    float4 r[4], w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (base + u * 256 < n) { r[u] = src[base + u * 256]; w[u] = dst[base + u * 256]; }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (base + u * 256 < n) {
+        float4 o;
+        o.x = __builtin_fmaf(0.75f, r[u].x, 1.25f * w[u].x);
+        o.y = __builtin_fmaf(0.75f, r[u].y, 1.25f * w[u].y);
+        o.z = __builtin_fmaf(0.75f, r[u].z, 1.25f * w[u].z);
+        o.w = __builtin_fmaf(0.75f, r[u].w, 1.25f * w[u].w);
+        dst[base + u * 256] = o;
+    }
+}
+
+struct EventPair {
+    hipEvent_t start = nullptr, stop = nullptr;
+    bool ok = false;
+    EventPair() { ok = hipEventCreate(&start) == hipSuccess && hipEventCreate(&stop) == hipSuccess; }
+    ~EventPair() { if (start) (void)hipEventDestroy(start); if (stop) (void)hipEventDestroy(stop); }
+};
+
+}  // namespace ttc
+
+// ---------------------------------------------------------------------------------
+// Device part of the C ABI
+// ---------------------------------------------------------------------------------
+extern "C" {
+
+int ttc_execute(ttc_plan_t plan, const void* A, void* B, void* stream)
+{
+    const int st = ttc::check_buffers(plan, A, B);
+    if (st != TTC_OK) return st;
+    const ttc::Candidate& c = ttc::pick_candidate(plan, A, B);
+    return ttc::launch(plan->prob, c, A, B, (hipStream_t)stream) == hipSuccess ? TTC_OK : TTC_ERR_HIP;
+}
+
+int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max_candidates)
+{
+    const int st = ttc::check_buffers(plan, A, B);
+    if (st != TTC_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    int cap = max_candidates;
+    if (cap == 0) {
+        const char* e = std::getenv("TTC_MAX_CANDIDATES");
+        cap = e ? std::atoi(e) : 200;
+        if (cap == 0) cap = 200;
+    }
+    const int total = (int)plan->cands.size();
+    if (cap < 0 || cap > total) cap = total;
+    if (cap == 1) { plan->selected = 0; return TTC_OK; }
+    const bool aligned16 = (((uintptr_t)A | (uintptr_t)B) % 16) == 0;
+    ttc::EventPair ev;
+    if (!ev.ok) return TTC_ERR_HIP;
+    int best = -1;
+    float best_ms = 0.f;
+    for (int i = 0; i < cap; ++i) {
+        ttc::Candidate& c = plan->cands[i];
+        if (!aligned16 && (c.kp.a.vec > 1 || c.kp.b.vec > 1)) continue;
+        const int reps = 3;
+        if (ttc::launch(plan->prob, c, A, B, s) != hipSuccess) return TTC_ERR_HIP;      // warm-up
+        if (hipEventRecord(ev.start, s) != hipSuccess) return TTC_ERR_HIP;
+        for (int r = 0; r < reps; ++r)
+            if (ttc::launch(plan->prob, c, A, B, s) != hipSuccess) return TTC_ERR_HIP;
+        if (hipEventRecord(ev.stop, s) != hipSuccess) return TTC_ERR_HIP;
+        if (hipEventSynchronize(ev.stop) != hipSuccess) return TTC_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev.start, ev.stop) != hipSuccess) return TTC_ERR_HIP;
+        c.tuned_ms = ms / reps;
+        if (best < 0 || c.tuned_ms < best_ms) { best = i; best_ms = c.tuned_ms; }
+    }
+    if (best >= 0) plan->selected = best;
+    return TTC_OK;
+}
+
+int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                     void* stream, int warmup, int iters, float* ms_per_launch)
+{
+    if (!plan || !A_list || !B_list || !ms_per_launch) return TTC_ERR_NULL_POINTER;
+    if (npairs < 1 || warmup < 0 || iters < 1) return TTC_ERR_INVALID_VALUE;
+    for (int i = 0; i < npairs; ++i) {
+        const int st = ttc::check_buffers(plan, A_list[i], B_list[i]);
+        if (st != TTC_OK) return st;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    ttc::EventPair ev;
+    if (!ev.ok) return TTC_ERR_HIP;
+    for (int i = 0; i < warmup; ++i) {
+        const int st = ttc_execute(plan, A_list[i % npairs], B_list[i % npairs], stream);
+        if (st != TTC_OK) return st;
+    }
+    if (hipEventRecord(ev.start, s) != hipSuccess) return TTC_ERR_HIP;
+    for (int i = 0; i < iters; ++i) {
+        const int st = ttc_execute(plan, A_list[(warmup + i) % npairs], B_list[(warmup + i) % npairs], stream);
+        if (st != TTC_OK) return st;
+    }
+    if (hipEventRecord(ev.stop, s) != hipSuccess) return TTC_ERR_HIP;
+    if (hipEventSynchronize(ev.stop) != hipSuccess) return TTC_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev.start, ev.stop) != hipSuccess) return TTC_ERR_HIP;
+    *ms_per_launch = ms / iters;
+    return TTC_OK;
+}
+
+int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src_list, void* const* dst_list,
+                     void* stream, int warmup, int iters, float* ms_per_launch)
+{
+    if (!src_list || !dst_list || !ms_per_launch) return TTC_ERR_NULL_POINTER;
+    if (kind < 0 || kind > 2 || bytes < 16 || (bytes % 16) != 0 || npairs < 1 || warmup < 0 || iters < 1)
+        return TTC_ERR_INVALID_VALUE;
+    for (int i = 0; i < npairs; ++i) {
+        if (!src_list[i] || !dst_list[i]) return TTC_ERR_NULL_POINTER;
+        const uintptr_t a = (uintptr_t)src_list[i], b = (uintptr_t)dst_list[i];
+        if (a % 16 || b % 16) return TTC_ERR_MISALIGNED;
+        if (a < b + (uintptr_t)bytes && b < a + (uintptr_t)bytes) return TTC_ERR_ALIAS;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    ttc::EventPair ev;
+    if (!ev.ok) return TTC_ERR_HIP;
+    const int64_t n = bytes / 16;
+    const int64_t grid64 = (n + 1023) / 1024;
+    if (grid64 > INT32_MAX) return TTC_ERR_OVERFLOW;
+    const uint32_t grid = (uint32_t)grid64;
+    auto one = [&](int i) -> hipError_t {
+        const void* src = src_list[i % npairs];
+        void* dst = dst_list[i % npairs];
+        if (kind == 0) {
+            hipLaunchKernelGGL(ttc::copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n);
+            return hipGetLastError();
+        }
+        if (kind == 1) return hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyDeviceToDevice, s);
+        hipLaunchKernelGGL(ttc::axpby_kernel, dim3(grid), dim3(256), 0, s, (const float4*)src, (float4*)dst, n);
+        return hipGetLastError();
+    };
+    for (int i = 0; i < warmup; ++i) if (one(i) != hipSuccess) return TTC_ERR_HIP;
+    if (hipEventRecord(ev.start, s) != hipSuccess) return TTC_ERR_HIP;
+    for (int i = 0; i < iters; ++i) if (one(warmup + i) != hipSuccess) return TTC_ERR_HIP;
+    if (hipEventRecord(ev.stop, s) != hipSuccess) return TTC_ERR_HIP;
+    if (hipEventSynchronize(ev.stop) != hipSuccess) return TTC_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ev.start, ev.stop) != hipSuccess) return TTC_ERR_HIP;
+    *ms_per_launch = ms / iters;
+    return TTC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,739 @@
+// Host planner: validation, size-1 removal, index fusion (paper Section 3, stage (1)),
+// case split (Section 3.1), candidate enumeration with a heuristic ranking (Sections 3.2,
+// 3.3 and the candidate queue of Section 3).  Pure host C++: no device is touched here.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "ttc_internal.h"
+#include "ttc_walk.h"
+
+namespace ttc {
+
+static thread_local int g_last_status = TTC_OK;
+void set_last_status(int status) { g_last_status = status; }
+
+FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    if (d < 1) d = 1;
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    f.div = d;
+    f.shift = s;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << s) - d)) / d + 1);
+    return f;
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
+
+// ---------------------------------------------------------------------------------
+// Normalisation: drop extents of 1, merge indices that stay adjacent and in order.
+// ---------------------------------------------------------------------------------
+static int normalise(int dtype, int ndim, const int64_t* sizes, const int* perm,
+                     const void* alpha, const void* beta, Problem* P)
+{
+    if (!sizes || !perm) return TTC_ERR_NULL_POINTER;
+    if (dtype == TTC_C128) return TTC_ERR_UNSUPPORTED_DTYPE;
+    if (dtype != TTC_F32 && dtype != TTC_F64 && dtype != TTC_C64) return TTC_ERR_UNSUPPORTED_DTYPE;
+    if (ndim < 1 || ndim > kMaxDim) return TTC_ERR_INVALID_VALUE;
+    bool seen[kMaxDim] = {false};
+    for (int j = 0; j < ndim; ++j) {
+        if (perm[j] < 0 || perm[j] >= ndim || seen[perm[j]]) return TTC_ERR_INVALID_PERM;
+        seen[perm[j]] = true;
+    }
+    const int elem = (dtype == TTC_F32) ? 4 : 8;
+    int64_t total = 1;
+    for (int k = 0; k < ndim; ++k) {
+        if (sizes[k] < 1) return TTC_ERR_INVALID_VALUE;
+        if (total > (INT64_MAX / 16) / sizes[k]) return TTC_ERR_OVERFLOW;
+        total *= sizes[k];
+    }
+
+    // 1. drop size-1 extents (they contribute offset 0 on both sides)
+    int newidx[kMaxDim], m = 0;
+    int64_t s1[kMaxDim];
+    for (int k = 0; k < ndim; ++k) {
+        newidx[k] = -1;
+        if (sizes[k] > 1) { newidx[k] = m; s1[m] = sizes[k]; ++m; }
+    }
+    int p1[kMaxDim], mp = 0;
+    for (int j = 0; j < ndim; ++j)
+        if (sizes[perm[j]] > 1) p1[mp++] = newidx[perm[j]];
+    if (m == 0) { m = 1; s1[0] = 1; p1[0] = 0; }
+
+    // 2. merge: B positions j, j+1 holding A indices a, a+1 form one index (dense tensors
+    //    always satisfy the leading-dimension condition of the paper's footnote).
+    int group_start[kMaxDim], group_len[kMaxDim], ng = 0;     // groups in B order
+    for (int j = 0; j < m;) {
+        int len = 1;
+        while (j + len < m && p1[j + len] == p1[j + len - 1] + 1) ++len;
+        group_start[ng] = p1[j];
+        group_len[ng] = len;
+        ++ng;
+        j += len;
+    }
+    // fused index of A = rank of the group's first A index
+    int rank_of_group[kMaxDim];
+    for (int g = 0; g < ng; ++g) {
+        int r = 0;
+        for (int h = 0; h < ng; ++h) if (group_start[h] < group_start[g]) ++r;
+        rank_of_group[g] = r;
+    }
+    P->dtype = dtype;
+    P->elem_bytes = elem;
+    P->ndim = ng;
+    P->elements = total;
+    for (int k = 0; k < kMaxDim; ++k) { P->size[k] = 0; P->perm[k] = 0; P->stride_a[k] = 0; P->stride_b[k] = 0; }
+    for (int g = 0; g < ng; ++g) {
+        int64_t sz = 1;
+        for (int i = 0; i < group_len[g]; ++i) sz *= s1[group_start[g] + i];
+        P->size[rank_of_group[g]] = sz;
+        P->perm[g] = rank_of_group[g];
+    }
+    int64_t st = 1;
+    for (int k = 0; k < ng; ++k) { P->stride_a[k] = st; st *= P->size[k]; }
+    st = 1;
+    for (int j = 0; j < ng; ++j) { P->stride_b[P->perm[j]] = st; st *= P->size[P->perm[j]]; }
+
+    // scalars (defaults of the paper's Table 1: alpha = 1, beta = 0)
+    P->alpha[0] = 1.0; P->alpha[1] = 0.0; P->beta[0] = 0.0; P->beta[1] = 0.0;
+    if (alpha) {
+        if (dtype == TTC_F32) P->alpha[0] = *(const float*)alpha;
+        else if (dtype == TTC_F64) P->alpha[0] = *(const double*)alpha;
+        else { P->alpha[0] = ((const float*)alpha)[0]; P->alpha[1] = ((const float*)alpha)[1]; }
+    }
+    if (beta) {
+        if (dtype == TTC_F32) P->beta[0] = *(const float*)beta;
+        else if (dtype == TTC_F64) P->beta[0] = *(const double*)beta;
+        else { P->beta[0] = ((const float*)beta)[0]; P->beta[1] = ((const float*)beta)[1]; }
+    }
+    const bool beta0 = (P->beta[0] == 0.0 && P->beta[1] == 0.0);
+    const bool alpha1 = (P->alpha[0] == 1.0 && P->alpha[1] == 0.0);
+    P->epilogue = beta0 ? (alpha1 ? TTC_EPI_COPY : TTC_EPI_SCALE) : TTC_EPI_AXPBY;
+    return TTC_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Tile (box) construction
+// ---------------------------------------------------------------------------------
+
+// Extent near `want` along an index of size s, a multiple of mult (s % mult == 0).
+// Divisors of s are preferred (no remainder tiles: the second rule of the paper's blocking
+// heuristic, Section 3.2); otherwise the index is cut into equal pieces.
+static int pick_extent(int64_t s, int64_t want, int mult)
+{
+    if (want < mult) want = mult;
+    if (want >= s) return (int)s;
+    for (int64_t t = round_up(want, mult); t <= std::min<int64_t>(s, 2 * want); t += mult)
+        if (s % t == 0) return (int)t;
+    for (int64_t t = (want / mult) * mult; t >= mult && 4 * t >= 3 * want; t -= mult)
+        if (s % t == 0) return (int)t;
+    const int64_t parts = ceil_div(s, want);
+    int64_t t = round_up(ceil_div(s, parts), mult);
+    return (int)std::min<int64_t>(t, s);
+}
+
+// Leading indices of one tensor, in that tensor's order, until the contiguous run they
+// span reaches `target` elements.  All but the last are taken whole.
+static void build_group(const Problem& P, const int* order, int64_t target, int vec, int* t)
+{
+    for (int k = 0; k < kMaxDim; ++k) t[k] = 1;
+    int64_t run = 1;
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = order[i];
+        const int64_t need = ceil_div(target, run);
+        if (need <= 1) break;
+        const int mult = (i == 0) ? vec : 1;
+        int ext;
+        if (P.size[k] <= need + need / 2) ext = (int)P.size[k];
+        else ext = pick_extent(P.size[k], need, mult);
+        t[k] = ext;
+        run *= ext;
+        if (ext < P.size[k]) break;
+    }
+}
+
+// Contiguous run (elements) the box spans in a tensor whose index order is `order`.
+static int64_t box_run(const Problem& P, const int* order, const int* t)
+{
+    int64_t run = 1;
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = order[i];
+        run *= t[k];
+        if (t[k] < P.size[k]) break;
+    }
+    return run;
+}
+
+// ---------------------------------------------------------------------------------
+// Lane mapping: which sub-box of the tile one wavefront instruction covers.
+// ---------------------------------------------------------------------------------
+struct LaneChoice { int lane[kMaxDim]; int n_iter; int lanes; };
+
+static LaneChoice choose_lanes(const Problem& P, const int* order, const int* t, int vec)
+{
+    LaneChoice best;
+    best.n_iter = INT32_MAX;
+    best.lanes = 0;
+    int64_t best_cost = INT64_MAX;
+    for (int k = 0; k < kMaxDim; ++k) best.lane[k] = 1;
+    const int first = order[0];
+    const int t0 = t[first];
+    // candidate extents along the vector index: divisors of t0 that are multiples of vec, and
+    // the largest extent 64 lanes can cover
+    std::vector<int> opts;
+    const int cap = std::min(t0, kWave * vec);
+    for (int l = vec; l <= cap; l += vec)
+        if (t0 % l == 0 || l == cap) opts.push_back(l);
+    if (opts.empty()) opts.push_back(std::max(vec, std::min(t0, vec)));
+    for (int l0 : opts) {
+        LaneChoice c;
+        for (int k = 0; k < kMaxDim; ++k) c.lane[k] = 1;
+        c.lane[first] = l0;
+        int lanes = l0 / vec;
+        int rem = kWave / lanes;
+        int64_t iters = ceil_div(t0, l0);
+        for (int i = 1; i < P.ndim; ++i) {
+            const int k = order[i];
+            if (t[k] <= 1) continue;
+            int l = 1;
+            if (rem > 1) {
+                l = std::min(rem, t[k]);
+                l = (int)ceil_div(t[k], ceil_div(t[k], l));      // same count, less ragged
+                rem /= l;
+                lanes *= l;
+            }
+            c.lane[k] = l;
+            iters *= ceil_div(t[k], l);
+        }
+        c.n_iter = (int)std::min<int64_t>(iters, INT32_MAX);
+        c.lanes = lanes;
+        // short segments along the stride-1 index cost coalescing: require 64 B unless the tile is shorter
+        const bool short_seg = (l0 < t0) && (l0 * P.elem_bytes < 64);
+        const int64_t cost = (int64_t)c.n_iter * (short_seg ? 2 : 1);
+        if (cost < best_cost || (cost == best_cost && l0 > best.lane[first])) { best = c; best_cost = cost; }
+    }
+    return best;
+}
+
+static void fill_side(const Problem& P, const int* order, const int* t, int vec, const LaneChoice& lc,
+                      const int* lds_stride, Side* s)
+{
+    std::memset(s, 0, sizeof(*s));
+    s->vec = vec;
+    const int vdim = order[0];
+    uint32_t lane_below = 1, iter_below = 1;
+    int64_t n_iter = 1;
+    for (int k = 0; k < kMaxDim; ++k) {
+        s->lane[k] = 1; s->lane_mul[k] = 1;
+        s->lane_below[k] = make_fastdiv(1); s->lane_cnt[k] = make_fastdiv(1);
+        s->iter_below[k] = make_fastdiv(1); s->iters[k] = make_fastdiv(1);
+    }
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = order[i];
+        const int mul = (k == vdim) ? vec : 1;
+        const int cnt = lc.lane[k] / mul;
+        const int its = (int)ceil_div(t[k], lc.lane[k]);
+        s->lane[k] = lc.lane[k];
+        s->lane_mul[k] = mul;
+        s->lane_below[k] = make_fastdiv(lane_below);
+        s->lane_cnt[k] = make_fastdiv((uint32_t)cnt);
+        s->iter_below[k] = make_fastdiv(iter_below);
+        s->iters[k] = make_fastdiv((uint32_t)its);
+        lane_below *= (uint32_t)cnt;
+        iter_below *= (uint32_t)its;
+        n_iter *= its;
+    }
+    s->lanes = (int)lane_below;
+    s->n_iter = (int)n_iter;
+    s->vec_lds_stride = lds_stride ? lds_stride[vdim] : 0;
+}
+
+// ---------------------------------------------------------------------------------
+// LDS layout: A order with small pads on the strides, chosen by simulating which banks the
+// 64 lanes of one instruction touch.
+// ---------------------------------------------------------------------------------
+static int bank_multiplicity(const Problem& P, const Side& s, const int* lds_stride, int vec_stride, int banks)
+{
+    const int words = P.elem_bytes / 4;
+    int worst = 1;
+    std::vector<int64_t> addr(kWave);
+    for (int j = 0; j < s.vec; ++j) {
+        int n = 0;
+        for (int lane = 0; lane < s.lanes; ++lane) {
+            int64_t a = (int64_t)j * vec_stride;
+            for (int k = 0; k < P.ndim; ++k) {
+                const uint32_t c = (lane / s.lane_below[k].div) % s.lane_cnt[k].div;
+                a += (int64_t)c * s.lane_mul[k] * lds_stride[k];
+            }
+            addr[n++] = a * words;
+        }
+        // distinct word addresses per bank (same address = broadcast, no conflict)
+        std::sort(addr.begin(), addr.begin() + n);
+        n = (int)(std::unique(addr.begin(), addr.begin() + n) - addr.begin());
+        std::vector<int> cnt(banks, 0);
+        for (int i = 0; i < n; ++i)
+            for (int w = 0; w < words; ++w) cnt[(addr[i] + w) % banks]++;
+        const int ideal = (int)ceil_div((int64_t)n * words, banks);
+        int mx = 0;
+        for (int b = 0; b < banks; ++b) mx = std::max(mx, cnt[b]);
+        worst = std::max(worst, (int)ceil_div(mx, std::max(ideal, 1)));
+    }
+    return worst;
+}
+
+struct LdsLayout { int stride[kMaxDim]; int elems; int conflict_a, conflict_b; };
+
+static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* order_b, int va, int vb,
+                                   const LaneChoice& la, const LaneChoice& lb)
+{
+    int order_a[kMaxDim];
+    for (int k = 0; k < kMaxDim; ++k) order_a[k] = k;
+    int box_dims[kMaxDim], nb = 0;
+    for (int k = 0; k < P.ndim; ++k) if (t[k] > 1) box_dims[nb++] = k;
+    const int npad = std::max(0, std::min(nb - 1, 3));          // strides of the 2nd..4th box index get a pad
+    LdsLayout best;
+    best.elems = 0; best.conflict_a = best.conflict_b = 1 << 20;
+    int64_t best_cost = INT64_MAX;
+    const int combos = 1 << (2 * npad);                          // pad in 0..3 each
+    for (int c = 0; c < combos; ++c) {
+        LdsLayout L;
+        for (int k = 0; k < kMaxDim; ++k) L.stride[k] = 0;
+        int64_t run = 1;
+        for (int i = 0; i < nb; ++i) {
+            const int k = box_dims[i];
+            if (i >= 1 && i - 1 < npad) run += (c >> (2 * (i - 1))) & 3;
+            L.stride[k] = (int)run;
+            run *= t[k];
+        }
+        if (nb == 0) run = 1;
+        L.elems = (int)run;
+        if ((int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
+        Side sa, sb;
+        fill_side(P, order_a, t, va, la, L.stride, &sa);
+        fill_side(P, order_b, t, vb, lb, L.stride, &sb);
+        L.conflict_a = bank_multiplicity(P, sa, L.stride, sa.vec_lds_stride, 32) +
+                       bank_multiplicity(P, sa, L.stride, sa.vec_lds_stride, 64);
+        L.conflict_b = bank_multiplicity(P, sb, L.stride, sb.vec_lds_stride, 32) +
+                       bank_multiplicity(P, sb, L.stride, sb.vec_lds_stride, 64);
+        const int64_t cost = ((int64_t)(L.conflict_a + L.conflict_b) << 24) + L.elems;
+        if (cost < best_cost) { best_cost = cost; best = L; }
+        if (L.conflict_a + L.conflict_b == 4) break;             // conflict-free under both bank counts
+    }
+    return best;
+}
+
+// ---------------------------------------------------------------------------------
+// Candidate assembly
+// ---------------------------------------------------------------------------------
+static int max_vec(const Problem& P, int64_t extent)
+{
+    int v = 16 / P.elem_bytes;
+    while (v > 1 && extent % v != 0) v /= 2;
+    return v;
+}
+
+static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bool direct, int threads,
+                           const int* tile_order, int xcd_remap, Candidate* out)
+{
+    Candidate C;
+    std::memset(&C, 0, sizeof(C));
+    int t[kMaxDim];
+    for (int k = 0; k < kMaxDim; ++k) t[k] = (k < P.ndim) ? t_in[k] : 1;
+    int order_a[kMaxDim], order_b[kMaxDim];
+    for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < P.ndim) ? P.perm[k] : k; }
+
+    KernelParams& kp = C.kp;
+    kp.n = P.ndim;
+    kp.xcd_remap = xcd_remap;
+    int64_t ntiles = 1;
+    for (int k = 0; k < kMaxDim; ++k) {
+        kp.size[k] = (k < P.ndim) ? P.size[k] : 1;
+        kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
+        kp.stride_b[k] = (k < P.ndim) ? P.stride_b[k] : 0;
+        kp.tile[k] = t[k];
+        kp.tile_below[k] = make_fastdiv(1);
+        kp.tile_cnt[k] = make_fastdiv(1);
+    }
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = tile_order[i];
+        const int64_t cnt = ceil_div(P.size[k], t[k]);
+        if (ntiles > INT32_MAX / 2 || cnt > INT32_MAX / 2) return false;
+        kp.tile_below[k] = make_fastdiv((uint32_t)ntiles);
+        kp.tile_cnt[k] = make_fastdiv((uint32_t)cnt);
+        ntiles *= cnt;
+        if (ntiles > INT32_MAX / 2) return false;
+        C.tile_order[i] = k;
+    }
+    kp.num_tiles = (uint32_t)ntiles;
+    kp.tiles_per_xcd = kp.num_tiles / 8;
+    kp.tiles_rem_xcd = kp.num_tiles % 8;
+    kp.alpha[0] = P.alpha[0]; kp.alpha[1] = P.alpha[1];
+    kp.beta[0] = P.beta[0];   kp.beta[1] = P.beta[1];
+
+    const LaneChoice la = choose_lanes(P, order_a, t, va);
+    if (direct) {
+        fill_side(P, order_a, t, va, la, nullptr, &kp.a);
+        kp.b = kp.a;
+        C.kernel_class = TTC_KERNEL_DIRECT;
+        C.lds_bytes = 0;
+        C.lds_conflict_a = C.lds_conflict_b = 0;
+    } else {
+        const LaneChoice lb = choose_lanes(P, order_b, t, vb);
+        const LdsLayout L = choose_lds_layout(P, t, order_b, va, vb, la, lb);
+        if (L.elems == 0) return false;
+        for (int k = 0; k < kMaxDim; ++k) kp.lds_stride[k] = L.stride[k];
+        fill_side(P, order_a, t, va, la, L.stride, &kp.a);
+        fill_side(P, order_b, t, vb, lb, L.stride, &kp.b);
+        C.kernel_class = TTC_KERNEL_LDS;
+        C.lds_bytes = L.elems * P.elem_bytes;
+        C.lds_conflict_a = L.conflict_a;
+        C.lds_conflict_b = L.conflict_b;
+    }
+    C.threads = threads;
+    C.tuned_ms = 0.f;
+    *out = C;
+    return true;
+}
+
+// Heuristic cost of a candidate (smaller is better).  It plays the role of the paper's cost
+// estimate that admits candidates to the bounded queue; the paper does not define one, this
+// one prices coalescing (length and alignment of the contiguous runs on both sides),
+// remainder tiles, tile size, lane use and vector width.
+static double heuristic_cost(const Problem& P, const Candidate& C)
+{
+    const KernelParams& kp = C.kp;
+    int order_a[kMaxDim], order_b[kMaxDim];
+    for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < P.ndim) ? P.perm[k] : k; }
+    const double eb = P.elem_bytes;
+    auto run_eff = [&](const int* order, int vec) {
+        const double run = (double)box_run(P, order, kp.tile) * eb;
+        // a run that is not a whole number of 128-byte lines shares its end lines with a neighbour
+        const bool aligned = std::fmod(run, 128.0) == 0.0;
+        double e = aligned ? 1.0 : run / (run + 48.0);
+        if (run < 256.0) e *= 0.5 + run / 512.0;
+        const double vbytes = vec * eb;
+        e *= (vbytes >= 16 ? 1.0 : (vbytes >= 8 ? 0.95 : 0.85));
+        return e;
+    };
+    double volume = 1, padded = 1;
+    for (int k = 0; k < P.ndim; ++k) {
+        volume *= kp.tile[k];
+        padded *= (double)ceil_div(P.size[k], kp.tile[k]) * kp.tile[k] / (double)P.size[k];
+    }
+    const double tile_bytes = volume * eb;
+    double cost = 0.5 / run_eff(order_a, kp.a.vec) + 0.5 / run_eff(order_b, C.kernel_class == TTC_KERNEL_DIRECT ? kp.a.vec : kp.b.vec);
+    cost *= padded;
+    cost *= 1.0 + 1536.0 / tile_bytes;                               // per-workgroup overhead
+    if (C.kernel_class == TTC_KERNEL_LDS) {
+        if (C.lds_bytes > 40 * 1024) cost *= 1.0 + (C.lds_bytes - 40 * 1024) / (96.0 * 1024);   // occupancy
+        const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
+        const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
+        cost *= 1.0 + 0.15 * (lane_a - 1.0) + 0.15 * (lane_b - 1.0);
+        cost *= 1.0 + 0.02 * (C.lds_conflict_a + C.lds_conflict_b - 4);
+        cost *= 1.08;                                                 // staging costs a barrier and LDS traffic
+    } else {
+        const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
+        cost *= 1.0 + 0.15 * (lane_a - 1.0);
+        if (tile_bytes > 64 * 1024) cost *= 1.05;
+    }
+    if (C.threads != 256) cost *= 1.03;
+    if (kp.num_tiles < 1024) cost *= 1.0 + 256.0 / (kp.num_tiles + 1.0) * 0.25;   // fewer tiles than the chip has slots
+    return cost;
+}
+
+static bool same_config(const Candidate& x, const Candidate& y)
+{
+    if (x.kernel_class != y.kernel_class || x.threads != y.threads) return false;
+    if (x.kp.a.vec != y.kp.a.vec || x.kp.b.vec != y.kp.b.vec) return false;
+    for (int k = 0; k < kMaxDim; ++k) {
+        if (x.kp.tile[k] != y.kp.tile[k]) return false;
+        if (x.kp.tile_below[k].div != y.kp.tile_below[k].div) return false;
+        if (x.kp.a.lane[k] != y.kp.a.lane[k] || x.kp.b.lane[k] != y.kp.b.lane[k]) return false;
+    }
+    return true;
+}
+
+static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Candidate& c)
+{
+    for (const Candidate& o : v) if (same_config(o, c)) return;
+    v.push_back(c);
+    v.back().score = heuristic_cost(P, c);
+}
+
+static void enumerate(const Problem& P, std::vector<Candidate>& out)
+{
+    const int n = P.ndim;
+    const int eb = P.elem_bytes;
+    int order_a[kMaxDim], order_b[kMaxDim];
+    for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < n) ? P.perm[k] : k; }
+    const bool stride1_fixed = (P.perm[0] == 0);
+    const int threads_opts[3] = {256, 512, 128};
+    const int* orders[2] = {order_b, order_a};
+
+    // -- direct candidates: only when the stride-1 index keeps its place
+    if (stride1_fixed) {
+        const int vfull = max_vec(P, P.size[0]);
+        for (int v = vfull; v >= 1; v /= 2) {
+            const int64_t tile_bytes_opts[4] = {16384, 32768, 8192, 65536};
+            for (int64_t tb : tile_bytes_opts) {
+                int t[kMaxDim];
+                build_group(P, order_a, tb / eb, v, t);
+                for (int o = 0; o < 2; ++o)
+                    for (int th : threads_opts) {
+                        Candidate c;
+                        if (make_candidate(P, t, v, v, true, th, orders[o], 1, &c)) add_candidate(P, out, c);
+                    }
+            }
+        }
+    }
+
+    // -- staged candidates: a box spanning the leading indices of A and of B
+    if (n >= 2) {
+        const int p0 = P.perm[0];
+        const int va_full = max_vec(P, P.size[0]);
+        const int vb_full = max_vec(P, P.size[p0]);
+        const int64_t run_bytes[8] = {256, 512, 128, 1024, 64, 2048, 4096, 8192};
+        for (int vsel = 0; vsel < 2; ++vsel) {
+            const int va = vsel == 0 ? va_full : 1;
+            const int vb = vsel == 0 ? vb_full : 1;
+            if (vsel == 1 && va_full == 1 && vb_full == 1) break;
+            for (int64_t ra : run_bytes)
+                for (int64_t rb : run_bytes) {
+                    int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
+                    build_group(P, order_a, ra / eb, va, ta);
+                    build_group(P, order_b, rb / eb, vb, tb);
+                    int64_t vol = 1;
+                    for (int k = 0; k < kMaxDim; ++k) { t[k] = std::max(ta[k], tb[k]); }
+                    t[0] = (int)std::min<int64_t>(round_up(t[0], va), P.size[0]);
+                    t[p0] = (int)std::min<int64_t>(round_up(t[p0], (p0 == 0) ? std::max(va, vb) : vb), P.size[p0]);
+                    for (int k = 0; k < n; ++k) vol *= t[k];
+                    if (vol * eb > kMaxLdsBytes - 2048 || vol * eb < 2048) continue;
+                    for (int o = 0; o < 2; ++o)
+                        for (int th : threads_opts) {
+                            Candidate c;
+                            if (make_candidate(P, t, va, vb, false, th, orders[o], 1, &c)) add_candidate(P, out, c);
+                        }
+                }
+        }
+    }
+
+    // -- last resort so that every problem has a candidate: scalar direct walk in A order
+    if (out.empty() || n == 1) {
+        int t[kMaxDim];
+        build_group(P, order_a, 16384 / eb, 1, t);
+        Candidate c;
+        if (make_candidate(P, t, 1, 1, true, 256, order_a, 1, &c)) add_candidate(P, out, c);
+    }
+}
+
+int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
+               const void* alpha, const void* beta, ttc_plan_s* plan)
+{
+    Problem& P = plan->prob;
+    int st = normalise(dtype, ndim, sizes, perm, alpha, beta, &P);
+    if (st != TTC_OK) return st;
+    plan->cands.clear();
+    enumerate(P, plan->cands);
+    if (plan->cands.empty()) return TTC_ERR_OVERFLOW;
+    std::stable_sort(plan->cands.begin(), plan->cands.end(),
+                     [](const Candidate& x, const Candidate& y) { return x.score < y.score; });
+    plan->selected = 0;
+    plan->fallback = -1;
+    for (size_t i = 0; i < plan->cands.size(); ++i)
+        if (plan->cands[i].kp.a.vec == 1 && plan->cands[i].kp.b.vec == 1) { plan->fallback = (int)i; break; }
+    if (plan->fallback < 0) {
+        // every candidate is vectorised: add the scalar variant of the best one
+        const Candidate& b = plan->cands[0];
+        Candidate c;
+        if (!make_candidate(P, b.kp.tile, 1, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.tile_order, 1, &c))
+            return TTC_ERR_OVERFLOW;
+        c.score = heuristic_cost(P, c);
+        plan->cands.push_back(c);
+        plan->fallback = (int)plan->cands.size() - 1;
+    }
+    return TTC_OK;
+}
+
+}  // namespace ttc
+
+// ---------------------------------------------------------------------------------
+// Host-only part of the C ABI
+// ---------------------------------------------------------------------------------
+extern "C" {
+
+ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int* perm,
+                           const void* alpha, const void* beta)
+{
+    ttc_plan_s* plan = new (std::nothrow) ttc_plan_s();
+    if (!plan) { ttc::set_last_status(TTC_ERR_ALLOC); return nullptr; }
+    int st;
+    try {
+        st = ttc::build_plan(dtype, ndim, sizes, perm, alpha, beta, plan);
+    } catch (const std::bad_alloc&) {
+        st = TTC_ERR_ALLOC;
+    } catch (...) {
+        st = TTC_ERR_INVALID_VALUE;
+    }
+    ttc::set_last_status(st);
+    if (st != TTC_OK) { delete plan; return nullptr; }
+    return plan;
+}
+
+int ttc_plan_destroy(ttc_plan_t plan)
+{
+    delete plan;
+    return TTC_OK;
+}
+
+int ttc_last_status(void) { return ttc::g_last_status; }
+
+const char* ttc_status_string(int status)
+{
+    switch (status) {
+    case TTC_OK: return "ok";
+    case TTC_ERR_INVALID_VALUE: return "invalid value";
+    case TTC_ERR_INVALID_PERM: return "perm is not a permutation";
+    case TTC_ERR_UNSUPPORTED_DTYPE: return "unsupported data type";
+    case TTC_ERR_NULL_POINTER: return "null pointer";
+    case TTC_ERR_ALIAS: return "A and B overlap";
+    case TTC_ERR_OVERFLOW: return "size overflow";
+    case TTC_ERR_HIP: return "HIP runtime error";
+    case TTC_ERR_ALLOC: return "allocation failed";
+    case TTC_ERR_MISALIGNED: return "pointer not aligned to the element size";
+    case TTC_ERR_INTERNAL: return "internal error: a candidate's walk is not a bijection in bounds";
+    default: return "unknown status";
+    }
+}
+
+int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
+{
+    if (!plan || !out) return TTC_ERR_NULL_POINTER;
+    const ttc::Problem& P = plan->prob;
+    const ttc::Candidate& C = plan->cands[plan->selected];
+    std::memset(out, 0, sizeof(*out));
+    out->dtype = P.dtype;
+    out->ndim = P.ndim;
+    for (int k = 0; k < P.ndim; ++k) {
+        out->sizes[k] = P.size[k];
+        out->perm[k] = P.perm[k];
+        out->tile[k] = C.kp.tile[k];
+        out->lane_a[k] = C.kp.a.lane[k];
+        out->lane_b[k] = C.kp.b.lane[k];
+        out->tile_order[k] = C.tile_order[k];
+        out->lds_stride[k] = C.kp.lds_stride[k];
+    }
+    out->stride1_fixed = (P.perm[0] == 0) ? 1 : 0;
+    out->kernel_class = C.kernel_class;
+    out->epilogue = P.epilogue;
+    out->vec_a = C.kp.a.vec;
+    out->vec_b = C.kp.b.vec;
+    out->threads = C.threads;
+    out->xcd_remap = C.kp.xcd_remap;
+    out->lds_bytes = C.lds_bytes;
+    out->lds_conflict_a = C.lds_conflict_a;
+    out->lds_conflict_b = C.lds_conflict_b;
+    out->num_tiles = C.kp.num_tiles;
+    out->elements = P.elements;
+    out->bytes_moved = (P.epilogue == TTC_EPI_AXPBY ? 3 : 2) * P.elements * P.elem_bytes;
+    out->candidate_index = plan->selected;
+    out->candidate_count = (int)plan->cands.size();
+    out->tuned_ms = C.tuned_ms;
+    out->heuristic_cost = C.score;
+    return TTC_OK;
+}
+
+int ttc_plan_candidate_count(ttc_plan_t plan)
+{
+    if (!plan) return -TTC_ERR_NULL_POINTER;
+    return (int)plan->cands.size();
+}
+
+int ttc_plan_select_candidate(ttc_plan_t plan, int index)
+{
+    if (!plan) return TTC_ERR_NULL_POINTER;
+    if (index < 0 || index >= (int)plan->cands.size()) return TTC_ERR_INVALID_VALUE;
+    plan->selected = index;
+    return TTC_OK;
+}
+
+// Host-side bounds checker: replays the selected candidate's walk (the same index code the
+// kernels run) lane by lane and records, for every offset of B, the offset of A that lands
+// there.  Fails on any access outside the tensors or the LDS tile, any misaligned vector, any
+// element of B written twice or never, and any LDS slot read before it was written.
+int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
+{
+    using namespace ttc;
+    if (!plan || !b_from_a) return TTC_ERR_NULL_POINTER;
+    const Problem& P = plan->prob;
+    const Candidate& C = plan->cands[plan->selected];
+    const KernelParams& p = C.kp;
+    const int64_t total = P.elements;
+    for (int64_t i = 0; i < total; ++i) b_from_a[i] = -1;
+    const uint32_t nwave = (uint32_t)C.threads / kWave;
+    if (nwave < 1 || C.threads % kWave) return TTC_ERR_INTERNAL;
+    const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
+    const int64_t lds_elems = C.lds_bytes / P.elem_bytes;
+    std::vector<int64_t> lds((size_t)lds_elems);
+    std::vector<char> seen(p.num_tiles, 0);
+    for (uint32_t wg = 0; wg < p.num_tiles; ++wg) {
+        const uint32_t tile = tile_of_workgroup(p, wg);
+        if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
+        seen[tile] = 1;
+        const TilePos tp = tile_pos(p, tile);
+        if (direct) {
+            for (uint32_t it = 0; it < (uint32_t)p.a.n_iter; ++it)
+                for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                    const LaneState L = lane_setup<true>(p, p.a, p.stride_a, lane);
+                    const IterPos q = iter_pos<true>(p, p.a, p.stride_a, tp.lim, L, it);
+                    if (!q.valid) continue;
+                    const int64_t oa = tp.base_a + q.g + L.g, ob = tp.base_b + q.g2 + L.g2;
+                    if (oa % p.a.vec || ob % p.a.vec) return TTC_ERR_INTERNAL;
+                    for (int j = 0; j < p.a.vec; ++j) {
+                        if (oa + j < 0 || oa + j >= total || ob + j < 0 || ob + j >= total) return TTC_ERR_INTERNAL;
+                        if (b_from_a[ob + j] != -1) return TTC_ERR_INTERNAL;
+                        b_from_a[ob + j] = oa + j;
+                    }
+                }
+            continue;
+        }
+        std::fill(lds.begin(), lds.end(), (int64_t)-1);
+        for (uint32_t it = 0; it < (uint32_t)p.a.n_iter; ++it)
+            for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                const LaneState L = lane_setup<false>(p, p.a, p.stride_a, lane);
+                const IterPos q = iter_pos<false>(p, p.a, p.stride_a, tp.lim, L, it);
+                if (!q.valid) continue;
+                const int64_t oa = tp.base_a + q.g + L.g;
+                const int64_t lo = (int64_t)q.l + L.l;
+                if (oa % p.a.vec) return TTC_ERR_INTERNAL;
+                for (int j = 0; j < p.a.vec; ++j) {
+                    if (oa + j < 0 || oa + j >= total || lo + j < 0 || lo + j >= lds_elems) return TTC_ERR_INTERNAL;
+                    if (lds[lo + j] != -1) return TTC_ERR_INTERNAL;
+                    lds[lo + j] = oa + j;
+                }
+            }
+        for (uint32_t it = 0; it < (uint32_t)p.b.n_iter; ++it)
+            for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                const LaneState L = lane_setup<false>(p, p.b, p.stride_b, lane);
+                const IterPos q = iter_pos<false>(p, p.b, p.stride_b, tp.lim, L, it);
+                if (!q.valid) continue;
+                const int64_t ob = tp.base_b + q.g + L.g;
+                const int64_t lo = (int64_t)q.l + L.l;
+                if (ob % p.b.vec) return TTC_ERR_INTERNAL;
+                for (int j = 0; j < p.b.vec; ++j) {
+                    const int64_t li = lo + (int64_t)j * p.b.vec_lds_stride;
+                    if (ob + j < 0 || ob + j >= total || li < 0 || li >= lds_elems) return TTC_ERR_INTERNAL;
+                    if (lds[li] == -1 || b_from_a[ob + j] != -1) return TTC_ERR_INTERNAL;
+                    b_from_a[ob + j] = lds[li];
+                }
+            }
+    }
+    for (int64_t i = 0; i < total; ++i) if (b_from_a[i] < 0) return TTC_ERR_INTERNAL;
+    return TTC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,200 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bar: bit-exact for alpha=1, beta=0 (a pure permutation); at most 1 ulp otherwise (both sides
+follow one evaluation order with the same fused multiply-adds, so 0 is what is expected).
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+import paper_1603_02297_amd as ttc
+from paper_1603_02297_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REAL = wl.REAL_DTYPE
+COMPS = wl.COMPONENTS
+INT_OF = {np.dtype(np.float32): np.int32, np.dtype(np.float64): np.int64}
+
+
+def ulp_distance(x: np.ndarray, y: np.ndarray) -> int:
+    """Largest distance in units in the last place between two float arrays of one dtype."""
+    if np.array_equal(x, y):
+        return 0
+    it = INT_OF[x.dtype]
+    xi, yi = x.view(it).astype(np.int64), y.view(it).astype(np.int64)
+    lowest = np.int64(np.iinfo(it).min)
+    xi = np.where(xi < 0, lowest - xi, xi)          # map sign-magnitude to a monotone integer line
+    yi = np.where(yi < 0, lowest - yi, yi)
+    return int(np.abs(xi - yi).max())
+
+
+def gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate=None, tune=False):
+    """One ttc_execute on the GPU; returns the resulting B as a numpy array."""
+    dev = torch.device("cuda:0")
+    dA = torch.from_numpy(A).to(dev)
+    dB = torch.from_numpy(B0).to(dev)
+    plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+    try:
+        if candidate is not None:
+            ttc.ttc_plan_select_candidate(plan, candidate)
+        if tune:
+            scratch = torch.empty_like(dB)
+            ttc.ttc_plan_tune(plan, dA.data_ptr(), scratch.data_ptr(), torch.cuda.current_stream().cuda_stream, 0)
+        ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        info = ttc.ttc_plan_get_info(plan)
+    finally:
+        ttc.ttc_plan_destroy(plan)
+    return dB.cpu().numpy(), info
+
+
+def check(dtype, sizes, perm, alpha, beta, seed=0, candidate=None, nan_b=False, threads=8, tune=False):
+    n = int(np.prod(sizes))
+    A = wl.uniform_tensor(dtype, n, 1000 + seed)
+    B0 = wl.uniform_tensor(dtype, n, 2000 + seed)
+    if nan_b:
+        B0[:] = np.nan
+    want = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy(), threads)
+    got, info = gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate, tune)
+    pure = (complex(alpha) == 1 and complex(beta) == 0)
+    d = ulp_distance(got, want)
+    assert d <= (0 if pure else 1), (sizes, perm, alpha, beta, candidate, d, info)
+    return d, info
+
+
+SCALARS = {
+    wl.F32: [(1.0, 0.0), (1.5, 0.0), (0.75, 1.25), (2.0, -1.0)],
+    wl.F64: [(1.0, 0.0), (1.5, 0.0), (0.75, 1.25)],
+    wl.C64: [(1.0, 0.0), (0.5 + 0.5j, 0.0), (0.5 + 0.5j, 1.0 + 0.0j), (-1.25 + 2j, 0.5 - 0.75j)],
+}
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F64, wl.C64])
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_all_perms_small_odd_extents(dtype, n):
+    ext = [37, 5, 19, 6]
+    for pi, perm in enumerate(itertools.permutations(range(n))):
+        sizes = tuple(ext[(k + perm[0]) % 4] for k in range(n))
+        al, be = SCALARS[dtype][pi % len(SCALARS[dtype])]
+        check(dtype, sizes, perm, al, be, seed=pi)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F64, wl.C64])
+@pytest.mark.parametrize("sizes,perm", [
+    ((200, 150), (1, 0)),
+    ((129, 3, 67), (2, 1, 0)),
+    ((96, 50, 31), (0, 2, 1)),
+    ((4, 50, 30), (0, 2, 1)),
+    ((6, 5, 4, 7, 3, 5), (5, 3, 1, 0, 4, 2)),
+    ((12, 10, 9, 11), (1, 0, 3, 2)),
+    ((8, 16, 6, 5, 10), (4, 1, 3, 0, 2)),
+    ((5000,), (0,)),
+    ((2, 3, 5, 7, 11, 13), (5, 4, 3, 2, 1, 0)),
+])
+def test_every_candidate_every_epilogue(dtype, sizes, perm):
+    """Ragged shapes spanning several tiles; every candidate configuration of the plan."""
+    p = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, None, None)
+    ncand = ttc.ttc_plan_candidate_count(p)
+    ttc.ttc_plan_destroy(p)
+    for k in range(ncand):
+        al, be = SCALARS[dtype][k % len(SCALARS[dtype])]
+        check(dtype, sizes, perm, al, be, seed=k, candidate=k)
+
+
+def test_random_5d_6d():
+    rng = np.random.default_rng(5)
+    for i in range(20):
+        n = int(rng.integers(5, 7))
+        sizes, perm = wl.random_problem(rng, n, 300000, 14)
+        dtype = (wl.F32, wl.F64, wl.C64)[i % 3]
+        al, be = SCALARS[dtype][i % len(SCALARS[dtype])]
+        check(dtype, sizes, perm, al, be, seed=i)
+
+
+def test_beta_zero_never_reads_b():
+    for dtype in (wl.F32, wl.F64, wl.C64):
+        for al in (1.0, 1.5):
+            check(dtype, (70, 33, 9), (2, 0, 1), al, 0.0, nan_b=True)
+            check(dtype, (70, 33, 9), (0, 2, 1), al, 0.0, nan_b=True)
+
+
+def test_size_one_and_degenerate_shapes():
+    check(wl.F32, (1,), (0,), 1.0, 0.0)
+    check(wl.F32, (1, 1, 1), (2, 0, 1), 2.0, -1.0)
+    check(wl.F64, (1, 77, 1, 5), (3, 2, 1, 0), 0.75, 1.25)
+    check(wl.F32, (2, 1, 3, 1, 4, 1), (5, 4, 3, 2, 1, 0), 1.0, 0.0)
+    check(wl.C64, (3, 2), (1, 0), 0.5 + 0.5j, 1.0)
+
+
+def test_rejects_alias_null_and_misaligned():
+    dev = torch.device("cuda:0")
+    buf = torch.zeros(4096, dtype=torch.float32, device=dev)
+    plan = ttc.ttc_plan_create(wl.F32, 2, (32, 32), (1, 0), None, None)
+    s = torch.cuda.current_stream().cuda_stream
+    for a, b, status in [(buf.data_ptr(), buf.data_ptr(), ttc.TTC_ERR_ALIAS),
+                         (buf.data_ptr(), buf.data_ptr() + 4 * 512, ttc.TTC_ERR_ALIAS),
+                         (0, buf.data_ptr(), ttc.TTC_ERR_NULL_POINTER),
+                         (buf.data_ptr() + 2, buf.data_ptr() + 8192, ttc.TTC_ERR_MISALIGNED)]:
+        with pytest.raises(ttc.TtcError) as e:
+            ttc.ttc_execute(plan, a, b, s)
+        assert e.value.status == status
+    ttc.ttc_plan_destroy(plan)
+
+
+def test_unaligned_pointers_take_the_scalar_fallback():
+    """Pointers aligned to the element but not to 16 bytes still give the exact result."""
+    dev = torch.device("cuda:0")
+    sizes, perm = (64, 48, 5), (1, 0, 2)
+    n = int(np.prod(sizes))
+    A = wl.uniform_tensor(wl.F32, n, 77)
+    want = oracle.transpose(wl.F32, sizes, perm, 1.0, 0.0, A, np.zeros(n, np.float32))
+    dA = torch.zeros(n + 8, dtype=torch.float32, device=dev)
+    dB = torch.zeros(n + 8, dtype=torch.float32, device=dev)
+    dA[1:n + 1] = torch.from_numpy(A).to(dev)
+    plan = ttc.ttc_plan_create(wl.F32, 3, sizes, perm, None, None)
+    assert ttc.ttc_plan_get_info(plan)["vec_a"] == 4
+    ttc.ttc_execute(plan, dA.data_ptr() + 4, dB.data_ptr() + 12, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ttc.ttc_plan_destroy(plan)
+    got = dB.cpu().numpy()
+    assert np.array_equal(got[3:n + 3], want)
+    assert not got[:3].any() and not got[n + 3:].any()          # nothing written outside B
+
+
+def test_tuned_plan_is_still_exact():
+    d, info = check(wl.F32, (96, 40, 24), (2, 0, 1), 1.5, 0.0, tune=True)
+    assert info["tuned_ms"] > 0
+
+
+def test_non_default_stream():
+    dev = torch.device("cuda:0")
+    sizes, perm = (80, 60), (1, 0)
+    A = wl.uniform_tensor(wl.F64, 4800, 5)
+    want = oracle.transpose(wl.F64, sizes, perm, 1.0, 0.0, A, np.zeros(4800))
+    dA = torch.from_numpy(A).to(dev)
+    dB = torch.zeros(4800, dtype=torch.float64, device=dev)
+    st = torch.cuda.Stream()                      # default priority
+    torch.cuda.synchronize()
+    plan = ttc.ttc_plan_create(wl.F64, 2, sizes, perm, None, None)
+    ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), st.cuda_stream)
+    st.synchronize()
+    ttc.ttc_plan_destroy(plan)
+    assert np.array_equal(dB.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("case", wl.CASES, ids=[c.name for c in wl.CASES])
+def test_benchmark_cases_full_size(case):
+    """The 15 headline cases at full size, in the launch configuration the benchmark times
+    (the tuned plan), every element compared."""
+    A, B0 = wl.case_inputs(case)
+    want = oracle.transpose(case.dtype, case.sizes, case.perm, case.alpha, case.beta, A, B0.copy(), 16)
+    for tune in (False, True):
+        got, info = gpu_run(case.dtype, case.sizes, case.perm, case.alpha, case.beta, A, B0, tune=tune)
+        pure = (complex(case.alpha) == 1 and complex(case.beta) == 0)
+        d = ulp_distance(got, want)
+        assert d <= (0 if pure else 1), (case.name, tune, d, info)

@@ -1,0 +1,183 @@
+"""Host logic of the library (no GPU): validation, size-1 removal, index fusion, case split,
+candidate list, and -- through the library's host-side replay of its own index arithmetic --
+that every candidate's walk stays in bounds and realises the element map of Eq. 1."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1603_02297_amd as ttc
+from paper_1603_02297_amd import workloads as wl
+
+
+def plan(dtype, sizes, perm, alpha=None, beta=None):
+    return ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+
+
+def info_of(dtype, sizes, perm, alpha=None, beta=None):
+    p = plan(dtype, sizes, perm, alpha, beta)
+    try:
+        return ttc.ttc_plan_get_info(p)
+    finally:
+        ttc.ttc_plan_destroy(p)
+
+
+# ---- validation -------------------------------------------------------------------
+@pytest.mark.parametrize("args,status", [
+    ((ttc.TTC_F32, 0, (), ()), ttc.TTC_ERR_INVALID_VALUE),
+    ((ttc.TTC_F32, 7, (2,) * 7, tuple(range(7))), ttc.TTC_ERR_INVALID_VALUE),
+    ((ttc.TTC_F32, 2, (4, 0), (1, 0)), ttc.TTC_ERR_INVALID_VALUE),
+    ((ttc.TTC_F32, 2, (4, -3), (1, 0)), ttc.TTC_ERR_INVALID_VALUE),
+    ((ttc.TTC_F32, 2, (4, 4), (1, 1)), ttc.TTC_ERR_INVALID_PERM),
+    ((ttc.TTC_F32, 2, (4, 4), (0, 2)), ttc.TTC_ERR_INVALID_PERM),
+    ((ttc.TTC_F32, 2, (4, 4), (-1, 0)), ttc.TTC_ERR_INVALID_PERM),
+    ((ttc.TTC_C128, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
+    ((17, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
+    ((ttc.TTC_F64, 3, (2 ** 31, 2 ** 31, 2 ** 10), (2, 1, 0)), ttc.TTC_ERR_OVERFLOW),
+])
+def test_create_rejects(args, status):
+    with pytest.raises(ttc.TtcError) as e:
+        ttc.ttc_plan_create(*args)
+    assert e.value.status == status
+    assert ttc.ttc_last_status() == status
+
+
+def test_destroy_null_is_noop():
+    ttc.ttc_plan_destroy(None)
+
+
+def test_defaults_are_alpha_one_beta_zero():
+    # defaults of the paper's Table 1
+    assert info_of(ttc.TTC_F32, (8, 8), (1, 0))["epilogue"] == ttc.TTC_EPI_COPY
+    assert info_of(ttc.TTC_F32, (8, 8), (1, 0), 1.5, 0.0)["epilogue"] == ttc.TTC_EPI_SCALE
+    assert info_of(ttc.TTC_F32, (8, 8), (1, 0), 1.0, 1.0)["epilogue"] == ttc.TTC_EPI_AXPBY
+    assert info_of(ttc.TTC_C64, (8, 8), (1, 0), 1.0 + 0j, 0.0)["epilogue"] == ttc.TTC_EPI_COPY
+    assert info_of(ttc.TTC_C64, (8, 8), (1, 0), 1.0 + 1j, 0.0)["epilogue"] == ttc.TTC_EPI_SCALE
+
+
+# ---- index fusion (paper Section 3, stage (1)) ---------------------------------------
+def test_paper_merge_example():
+    # Pi(i1,i2,i3) = (i2,i3,i1) becomes the 2-D (i~2, i1) with size(i~2) = size(i2)*size(i3)
+    i = info_of(ttc.TTC_F32, (5, 6, 7), (1, 2, 0))
+    assert i["ndim"] == 2 and i["sizes"] == [5, 42] and i["perm"] == [1, 0]
+
+
+def test_config_fusions():
+    i = info_of(ttc.TTC_F64, (72,) * 4, (2, 3, 0, 1))
+    assert i["ndim"] == 2 and i["sizes"] == [5184, 5184] and i["perm"] == [1, 0]
+    i = info_of(ttc.TTC_F32, (24, 20, 16, 18, 22, 17), (1, 0, 2, 3, 5, 4))
+    assert i["ndim"] == 5 and i["sizes"] == [24, 20, 288, 22, 17] and i["perm"] == [1, 0, 2, 4, 3]
+    i = info_of(ttc.TTC_F32, (4, 5, 6), (0, 1, 2))
+    assert i["ndim"] == 1 and i["sizes"] == [120] and i["perm"] == [0] and i["stride1_fixed"] == 1
+    for perm in [(5, 3, 1, 0, 4, 2), (5, 4, 3, 2, 1, 0)]:
+        assert info_of(ttc.TTC_F32, (24, 20, 16, 18, 22, 17), perm)["ndim"] == 6      # nothing merges
+
+
+def test_size_one_extents_are_dropped_then_fused():
+    i = info_of(ttc.TTC_F32, (4, 1, 5, 1, 6), (2, 1, 4, 3, 0))     # without the 1s: (4,5,6) perm (1,2,0)
+    assert i["ndim"] == 2 and i["sizes"] == [4, 30] and i["perm"] == [1, 0]
+    i = info_of(ttc.TTC_F32, (1, 1, 1), (2, 0, 1))
+    assert i["ndim"] == 1 and i["sizes"] == [1] and i["elements"] == 1
+
+
+def test_fusion_is_maximal_and_consistent():
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        n = int(rng.integers(1, 7))
+        sizes = tuple(int(x) for x in rng.integers(1, 5, n))
+        perm = tuple(int(x) for x in rng.permutation(n))
+        i = info_of(ttc.TTC_F32, sizes, perm)
+        m, fs, fp = i["ndim"], i["sizes"], i["perm"]
+        assert sorted(fp) == list(range(m))
+        assert int(np.prod(fs)) == int(np.prod(sizes)) == i["elements"]
+        for j in range(m - 1):
+            assert fp[j + 1] != fp[j] + 1          # nothing left to merge
+        if m > 1:
+            assert all(s > 1 for s in fs)
+        # the fused problem has the same element map as the original one
+        if i["elements"] <= 400:
+            assert oracle.element_map(sizes, perm) == oracle.element_map(tuple(fs), tuple(fp))
+
+
+# ---- case split (paper Section 3.1) ------------------------------------------------------
+def test_case_split_on_the_benchmark_cases():
+    for c in wl.CASES:
+        i = info_of(c.dtype, c.sizes, c.perm, c.alpha, c.beta)
+        fixed = (i["perm"][0] == 0)
+        assert i["stride1_fixed"] == int(fixed)
+        assert fixed == (c.perm == (0, 2, 1))
+        if not fixed:
+            assert i["kernel_class"] == ttc.TTC_KERNEL_LDS
+        assert i["bytes_moved"] == c.traffic_bytes
+        assert i["lds_bytes"] <= 64 * 1024
+        assert 0 < i["candidate_count"]
+
+
+def test_candidates_are_ranked_and_have_a_scalar_fallback():
+    p = plan(ttc.TTC_F32, (48, 36, 20), (2, 0, 1))
+    n = ttc.ttc_plan_candidate_count(p)
+    costs, scalar = [], False
+    for k in range(n):
+        ttc.ttc_plan_select_candidate(p, k)
+        i = ttc.ttc_plan_get_info(p)
+        costs.append(i["heuristic_cost"])
+        scalar |= (i["vec_a"] == 1 and i["vec_b"] == 1)
+        assert i["tile"][0] % i["vec_a"] == 0 and i["tile"][i["perm"][0]] % i["vec_b"] == 0
+    assert scalar
+    assert costs[:-1] == sorted(costs[:-1])       # the appended fallback may sit out of order
+    with pytest.raises(ttc.TtcError):
+        ttc.ttc_plan_select_candidate(p, n)
+    ttc.ttc_plan_destroy(p)
+
+
+# ---- every candidate's walk, replayed on the host, is the element map of Eq. 1 ----------------
+def check_all_candidates(dtype, sizes, perm, max_candidates=None):
+    p = plan(dtype, sizes, perm)
+    total = int(np.prod(sizes))
+    emap = oracle.element_map(sizes, perm)
+    want = [0] * total
+    for off_a, off_b in enumerate(emap):
+        want[off_b] = off_a
+    n = ttc.ttc_plan_candidate_count(p)
+    idx = range(n) if max_candidates is None or n <= max_candidates else \
+        sorted(set(np.linspace(0, n - 1, max_candidates).astype(int).tolist()))
+    for k in idx:
+        ttc.ttc_plan_select_candidate(p, k)
+        got = ttc.ttc_debug_emulate_map(p, total)
+        assert list(got) == want, (sizes, perm, k, ttc.ttc_plan_get_info(p))
+    ttc.ttc_plan_destroy(p)
+    return n
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_walks_all_perms_small_odd_extents(n):
+    ext = [3, 5, 7, 2]
+    for perm in itertools.permutations(range(n)):
+        sizes = tuple(ext[(k + perm[0]) % 4] for k in range(n))
+        check_all_candidates(ttc.TTC_F32, sizes, perm, max_candidates=12)
+
+
+@pytest.mark.parametrize("dtype", [ttc.TTC_F32, ttc.TTC_F64, ttc.TTC_C64])
+@pytest.mark.parametrize("sizes,perm", [
+    ((70, 66), (1, 0)),                 # several tiles, ragged tails on both indices
+    ((64, 64), (1, 0)),
+    ((129, 3, 67), (2, 1, 0)),
+    ((40, 36, 5), (0, 2, 1)),           # stride-1 index fixed, long rows
+    ((4, 50, 30), (0, 2, 1)),           # stride-1 index fixed, short rows
+    ((6, 5, 4, 7, 3, 5), (5, 3, 1, 0, 4, 2)),
+    ((12, 10, 9, 11), (1, 0, 3, 2)),
+    ((8, 16, 6, 5, 10), (4, 1, 3, 0, 2)),
+    ((1000,), (0,)),
+    ((2, 3, 5, 7, 11, 13), (5, 4, 3, 2, 1, 0)),
+])
+def test_walks_shapes_with_tails(dtype, sizes, perm):
+    check_all_candidates(dtype, sizes, perm, max_candidates=24)
+
+
+def test_walks_random_5d_6d():
+    rng = np.random.default_rng(11)
+    for _ in range(12):
+        n = int(rng.integers(5, 7))
+        sizes, perm = wl.random_problem(rng, n, 20000, 12)
+        check_all_candidates(ttc.TTC_F32, sizes, perm, max_candidates=6)
