@@ -69,10 +69,11 @@ typedef struct {
     int     lds_stride[TTC_MAX_DIM];       /* element stride of each fused index inside the LDS tile (0 = unused) */
     int     vec_a, vec_b;                  /* elements per lane per global access on the A side / B side */
     int     threads;                       /* workgroup size */
+    int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles */
     int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
-    int     lds_bytes;                     /* dynamic LDS per workgroup */
+    int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + two tile buffers */
     int     lds_conflict_a, lds_conflict_b;/* modelled worst bank multiplicity of the LDS write / read instructions */
-    int64_t num_tiles;                     /* = workgroups launched */
+    int64_t num_tiles;                     /* tiles the tensor is cut into */
     int64_t elements;                      /* prod(sizes) */
     int64_t bytes_moved;                   /* 2 or 3 x tensor bytes: read A, write B, read B iff beta != 0 (paper Eq. 2) */
     int     candidate_index;               /* which candidate is selected */

@@ -33,7 +33,7 @@ class ttc_plan_info_t(ctypes.Structure):
         ("tile", ctypes.c_int * TTC_MAX_DIM), ("lane_a", ctypes.c_int * TTC_MAX_DIM),
         ("lane_b", ctypes.c_int * TTC_MAX_DIM), ("tile_order", ctypes.c_int * TTC_MAX_DIM),
         ("lds_stride", ctypes.c_int * TTC_MAX_DIM),
-        ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int),
+        ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
         ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int),
         ("lds_conflict_a", ctypes.c_int), ("lds_conflict_b", ctypes.c_int),
         ("num_tiles", ctypes.c_int64), ("elements", ctypes.c_int64), ("bytes_moved", ctypes.c_int64),

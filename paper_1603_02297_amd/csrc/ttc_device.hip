@@ -82,129 +82,121 @@ template <int MODE> struct Epilogue<cfloat, MODE> {
 };
 
 // ---------------------------------------------------------------------------------
-// The kernel
+// The kernel.  Dynamic LDS: [position tables of both walks][tile buffer 0][tile buffer 1].
+// A workgroup walks several tiles; with two tile buffers one barrier per tile is enough: a
+// wavefront can only start filling buffer (t+1)%2 after it passed the barrier of tile t, and
+// every wavefront reached that barrier after it had finished reading that buffer for tile t-1.
 // ---------------------------------------------------------------------------------
 constexpr int kUnroll = 4;     // memory instructions a wavefront keeps in flight per walk step
+
+template <typename T, int V>
+__device__ __forceinline__ Pack<T, V> load_pack(const unsigned char* base, int64_t off)
+{
+    return *reinterpret_cast<const Pack<T, V>*>(base + off);
+}
 
 template <typename T, int MODE, int VA, int VB, bool DIRECT>
 __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const T* __restrict__ A,
                                                           T* __restrict__ B)
 {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    T* lds = reinterpret_cast<T*>(smem_raw);
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int32_t kScale = (int32_t)sizeof(T);
+    const uint32_t n_a = (uint32_t)p.a.n_iter, n_b = DIRECT ? 0u : (uint32_t)p.b.n_iter;
+    PosEntry* tab_a = reinterpret_cast<PosEntry*>(smem);
+    PosEntry* tab_b = tab_a + n_a;
+    PosCoord* tabc_a = reinterpret_cast<PosCoord*>(tab_b + n_b);
+    PosCoord* tabc_b = tabc_a + n_a;
 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t nwave = blockDim.x >> 6;
 
-    const TilePos tp = tile_pos(p, tile_of_workgroup(p, blockIdx.x));
-    const int32_t* lim = tp.lim;
-    const int64_t base_a = tp.base_a, base_b = tp.base_b;
-    const T* __restrict__ At = A + base_a;
-    T* __restrict__ Bt = B + base_b;
-    const Epilogue<T, MODE> epi(p);
-
-    if (DIRECT) {
-        const LaneState L = lane_setup<true>(p, p.a, p.stride_a, lane);
-        const uint32_t n_it = (uint32_t)p.a.n_iter;
-        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
-            Pack<T, VA> ra[kUnroll], rb[kUnroll];
-            bool ok[kUnroll];
-            int64_t ob[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint32_t it = it0 + u * nwave;
-                ok[u] = false;
-                if (it < n_it) {
-                    const IterPos q = iter_pos<true>(p, p.a, p.stride_a, lim, L, it);
-                    ok[u] = q.valid;
-                    ob[u] = q.g2 + L.g2;
-                    if (q.valid) {
-                        ra[u] = *reinterpret_cast<const Pack<T, VA>*>(At + (q.g + L.g));
-                        if (MODE == TTC_EPI_AXPBY) rb[u] = *reinterpret_cast<const Pack<T, VA>*>(Bt + ob[u]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (ok[u]) {
-                    Pack<T, VA> out;
-#pragma unroll
-                    for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
-                    *reinterpret_cast<Pack<T, VA>*>(Bt + ob[u]) = out;
-                }
-            }
-        }
-        return;
-    }
-
-    // ---- walk 1: A order, global -> LDS
-    {
-        const LaneState L = lane_setup<false>(p, p.a, p.stride_a, lane);
-        const uint32_t n_it = (uint32_t)p.a.n_iter;
-        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
-            Pack<T, VA> ra[kUnroll];
-            bool ok[kUnroll];
-            int32_t lo[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint32_t it = it0 + u * nwave;
-                ok[u] = false;
-                if (it < n_it) {
-                    const IterPos q = iter_pos<false>(p, p.a, p.stride_a, lim, L, it);
-                    ok[u] = q.valid;
-                    lo[u] = q.l + L.l;
-                    if (q.valid) ra[u] = *reinterpret_cast<const Pack<T, VA>*>(At + (q.g + L.g));
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (ok[u]) {
-#pragma unroll
-                    for (int j = 0; j < VA; ++j) lds[lo[u] + j] = ra[u].v[j];
-                }
-            }
-        }
-    }
+    for (uint32_t it = threadIdx.x; it < n_a; it += blockDim.x)
+        make_position<DIRECT>(p.a, it, kScale, &tab_a[it], &tabc_a[it]);
+    if (!DIRECT)
+        for (uint32_t it = threadIdx.x; it < n_b; it += blockDim.x)
+            make_position<false>(p.b, it, kScale, &tab_b[it], &tabc_b[it]);
+    const LaneState LA = lane_setup<DIRECT>(p.a, lane, kScale);
+    const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, kScale);
     __syncthreads();
-    // ---- walk 2: B order, LDS -> epilogue -> global
-    {
-        const LaneState L = lane_setup<false>(p, p.b, p.stride_b, lane);
-        const uint32_t n_it = (uint32_t)p.b.n_iter;
-        const int32_t vs = p.b.vec_lds_stride;
-        for (uint32_t it0 = wave; it0 < n_it; it0 += nwave * kUnroll) {
-            Pack<T, VB> rb[kUnroll];
-            bool ok[kUnroll];
-            int32_t lo[kUnroll];
-            int64_t ob[kUnroll];
+
+    const Epilogue<T, MODE> epi(p);
+    const TileSeq seq = tile_sequence(p, blockIdx.x);
+    uint32_t parity = 0;
+    for (uint32_t tile = seq.first; tile < seq.end; tile += seq.step) {
+        const TileBase tb = tile_base(p, tile);
+        const unsigned char* At = reinterpret_cast<const unsigned char*>(A + tb.a);
+        unsigned char* Bt = reinterpret_cast<unsigned char*>(B + tb.b);
+
+        if (DIRECT) {
+            const TileLim tl = tile_lim(p.a, tile);
+            Pack<T, VA> ra[kUnroll], rb[kUnroll];
+            auto load = [&](int u, const PosEntry& e) {
+                ra[u] = load_pack<T, VA>(At, e.g + LA.g);
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<T, VA>(Bt, e.l_or_g2 + LA.g2);
+            };
+            auto store = [&](int u, const PosEntry& e) {
+                Pack<T, VA> out;
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint32_t it = it0 + u * nwave;
-                ok[u] = false;
-                if (it < n_it) {
-                    const IterPos q = iter_pos<false>(p, p.b, p.stride_b, lim, L, it);
-                    ok[u] = q.valid;
-                    lo[u] = q.l + L.l;
-                    ob[u] = q.g + L.g;
-                    if (MODE == TTC_EPI_AXPBY) {
-                        if (q.valid) rb[u] = *reinterpret_cast<const Pack<T, VB>*>(Bt + ob[u]);
-                    }
-                }
-            }
+                for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
+                *reinterpret_cast<Pack<T, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
+            };
+            if (tl.full) walk<kUnroll, true>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, store);
+            else walk<kUnroll, false>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, store);
+            continue;
+        }
+
+        unsigned char* lds = smem + p.lds_data_off + parity * (uint32_t)(p.lds_tile_elems * kScale);
+        parity ^= 1u;
+        // ---- walk 1: A order, global -> LDS
+        {
+            const TileLim tl = tile_lim(p.a, tile);
+            Pack<T, VA> ra[kUnroll];
+            auto load = [&](int u, const PosEntry& e) { ra[u] = load_pack<T, VA>(At, e.g + LA.g); };
+            auto park = [&](int u, const PosEntry& e) {
+                T* dst = reinterpret_cast<T*>(lds + ((int32_t)e.l_or_g2 + LA.l));
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (ok[u]) {
-                    Pack<T, VB> out;
+                for (int j = 0; j < VA; ++j) dst[j] = ra[u].v[j];
+            };
+            if (tl.full) walk<kUnroll, true>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, park);
+            else walk<kUnroll, false>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, park);
+        }
+        __syncthreads();
+        // ---- walk 2: B order, LDS -> epilogue -> global
+        {
+            const TileLim tl = tile_lim(p.b, tile);
+            const int32_t vs = p.b.vec_lds_stride;
+            Pack<T, VB> rb[kUnroll], rl[kUnroll];
+            auto load = [&](int u, const PosEntry& e) {
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<T, VB>(Bt, e.g + LB.g);
+                const T* src = reinterpret_cast<const T*>(lds + ((int32_t)e.l_or_g2 + LB.l));
 #pragma unroll
-                    for (int j = 0; j < VB; ++j) {
-                        const T a = lds[lo[u] + j * vs];
-                        out.v[j] = epi(a, MODE == TTC_EPI_AXPBY ? rb[u].v[j] : a);
-                    }
-                    *reinterpret_cast<Pack<T, VB>*>(Bt + ob[u]) = out;
-                }
-            }
+                for (int j = 0; j < VB; ++j) rl[u].v[j] = src[j * vs];
+            };
+            auto store = [&](int u, const PosEntry& e) {
+                Pack<T, VB> out;
+#pragma unroll
+                for (int j = 0; j < VB; ++j) out.v[j] = epi(rl[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : rl[u].v[j]);
+                *reinterpret_cast<Pack<T, VB>*>(Bt + (e.g + LB.g)) = out;
+            };
+            if (tl.full) walk<kUnroll, true>(p.b, LB, tl.lim, tab_b, tabc_b, wave, nwave, load, store);
+            else walk<kUnroll, false>(p.b, LB, tl.lim, tab_b, tabc_b, wave, nwave, load, store);
         }
     }
+}
+
+// Compute units of the current device (256 on MI355X), asked once per process and device.
+static int device_cus()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 // ---------------------------------------------------------------------------------
@@ -216,6 +208,7 @@ template <typename T, int MODE, int VA, int VB, bool DIRECT>
 static hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uint32_t grid, int threads,
                              int lds_bytes, hipStream_t stream)
 {
+    if (grid != kp.grid || grid < 1 || grid > kp.num_tiles) return hipErrorInvalidValue;
     hipLaunchKernelGGL((box_kernel<T, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
                        kp, static_cast<const T*>(A), static_cast<T*>(B));
     return hipGetLastError();
@@ -224,13 +217,14 @@ static hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uin
 template <typename T, int MODE, int VMAX>
 static hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
 {
-    const KernelParams& kp = c.kp;
-    const uint32_t grid = kp.num_tiles;
+    KernelParams kp = c.kp;
+    const uint32_t grid = launch_grid(c, device_cus());
+    set_grid(&kp, grid);
     const int va = kp.a.vec, vb = kp.b.vec;
     if (c.kernel_class == TTC_KERNEL_DIRECT) {
-        if (va == 1) return launch_one<T, MODE, 1, 1, true>(kp, A, B, grid, c.threads, 0, s);
-        if (va == 2) return launch_one<T, MODE, 2, 2, true>(kp, A, B, grid, c.threads, 0, s);
-        if (va == 4 && VMAX >= 4) return launch_one<T, MODE, (VMAX >= 4 ? 4 : 1), (VMAX >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, 0, s);
+        if (va == 1) return launch_one<T, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 2) return launch_one<T, MODE, 2, 2, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 4 && VMAX >= 4) return launch_one<T, MODE, (VMAX >= 4 ? 4 : 1), (VMAX >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
         return hipErrorInvalidValue;
     }
 #define TTC_CASE(VA_, VB_)                                                                                   \

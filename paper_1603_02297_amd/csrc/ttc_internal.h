@@ -25,20 +25,34 @@ struct FastDiv {
 };
 FastDiv make_fastdiv(uint32_t d);
 
-// One way of walking the tile ("box"): which sub-box the 64 lanes of a wavefront cover
-// with one memory instruction, and how many such instructions cover the box.  All arrays
-// are indexed by fused index of A.  An index k outside the box has lane=1, iters=1.
+constexpr int kBoxDims = 4;               // a box spans at most this many indices
+constexpr int kMaxIters = 2048;           // sub-box positions per tile and walk (size of the position table)
+
+// One index of the box as one walk sees it.  A walk ("side") lists only the indices the box
+// really spans (extent > 1), in the order of the tensor it follows, stride-1 index first.
+struct Digit {
+    int32_t  tile;                   // box extent along the index
+    int32_t  lane;                   // extent of the sub-box the 64 lanes cover (elements)
+    int32_t  iters;                  // ceil(tile / lane): sub-box positions along the index
+    int32_t  lane_mul;               // elements per lane step: vec on the vector index, else 1
+    FastDiv  lane_below, lane_cnt;   // lane id  -> lane coordinate: (lane / below) % cnt
+    FastDiv  iter_below, iter_cnt;   // position id -> position digit
+    FastDiv  tile_below, tile_cnt;   // tile id -> tile coordinate along this index
+    int64_t  size;                   // extent of the index in the tensor
+    int64_t  gstride;                // element stride in the tensor the walk follows
+    int64_t  g2stride;               // direct kernel: element stride in B
+    int32_t  lstride;                // element stride inside the LDS tile
+    int32_t  pad;
+};
+
 struct Side {
-    int32_t  vec;                    // elements per lane per access along vec_dim
-    int32_t  lanes;                  // active lanes = prod(lane[k]) / vec
-    int32_t  n_iter;                 // prod(iters[k])
-    int32_t  vec_lds_stride;         // LDS stride (elements) between the vec elements of one lane
-    int32_t  lane[kMaxDim];          // lane sub-box extent (elements); multiple of vec on vec_dim
-    int32_t  lane_mul[kMaxDim];      // elements per lane step: vec on vec_dim, else 1
-    FastDiv  lane_below[kMaxDim];    // prod of lane counts of the digits below k in this side's order
-    FastDiv  lane_cnt[kMaxDim];      // lane count along k (lane[k] / lane_mul[k])
-    FastDiv  iter_below[kMaxDim];    // prod of iters of the digits below k in this side's order
-    FastDiv  iters[kMaxDim];         // ceil(tile[k] / lane[k])
+    int32_t  nd;                     // digits in use (<= kBoxDims)
+    int32_t  vec;                    // elements per lane per access, along digit 0
+    int32_t  lanes;                  // active lanes of a wavefront
+    int32_t  n_iter;                 // sub-box positions per tile = prod(iters)
+    int32_t  vec_lds_stride;         // LDS element stride between the vec elements of one lane
+    int32_t  exact;                  // 1: lane divides tile on every digit (no ragged sub-boxes)
+    Digit    d[kBoxDims];
 };
 
 // Everything a kernel launch needs; passed by value as the kernel argument.
@@ -48,15 +62,18 @@ struct KernelParams {
     uint32_t num_tiles;
     uint32_t tiles_per_xcd;          // num_tiles / 8
     uint32_t tiles_rem_xcd;          // num_tiles % 8
-    int64_t  size[kMaxDim];          // fused extents
-    int64_t  stride_a[kMaxDim];      // element stride of fused index k in A
-    int64_t  stride_b[kMaxDim];      // element stride of fused index k in B
-    int32_t  tile[kMaxDim];          // box extent (1 = index not blocked)
-    int32_t  lds_stride[kMaxDim];    // element stride of index k in the LDS tile
+    uint32_t grid;                   // workgroups launched (filled at launch; <= num_tiles)
+    uint32_t grid_per_xcd;           // grid / 8
+    uint32_t grid_rem_xcd;           // grid % 8
+    int32_t  lds_data_off;           // byte offset of the first data buffer in dynamic LDS
+    int32_t  lds_tile_elems;         // elements per LDS data buffer (padded tile)
+    int32_t  tile[kMaxDim];          // box extent per fused index of A (1 = index not blocked)
     FastDiv  tile_below[kMaxDim];    // prod of tile counts of the indices that vary faster in the tile order
     FastDiv  tile_cnt[kMaxDim];      // ceil(size[k] / tile[k])
-    Side     a;                      // load side (A order)
-    Side     b;                      // store side (B order); unused by the direct kernel
+    int64_t  stride_a[kMaxDim];      // element stride of fused index k in A
+    int64_t  stride_b[kMaxDim];      // element stride of fused index k in B
+    Side     a;                      // load walk (A order)
+    Side     b;                      // store walk (B order); unused by the direct kernel
     double   alpha[2];               // re, im (im = 0 for real types)
     double   beta[2];
 };
@@ -65,8 +82,10 @@ struct KernelParams {
 struct Candidate {
     int      kernel_class;           // TTC_KERNEL_*
     int      threads;
-    int      lds_bytes;
+    int      wg_per_cu;              // workgroups launched per compute unit (each walks several tiles)
+    int      lds_bytes;              // dynamic LDS per workgroup: position tables + two tile buffers
     int      tile_order[kMaxDim];
+    int      tile[kMaxDim], lane_a[kMaxDim], lane_b[kMaxDim], lds_stride[kMaxDim];   // by fused index of A
     int      lds_conflict_a, lds_conflict_b;
     double   score;                  // heuristic cost, smaller is better
     float    tuned_ms;
@@ -101,5 +120,8 @@ namespace ttc {
 int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
                const void* alpha, const void* beta, ttc_plan_s* out);
 void set_last_status(int status);
+// Workgroups to launch for a candidate on a device with `cus` compute units.
+uint32_t launch_grid(const Candidate& c, int cus);
+void set_grid(KernelParams* kp, uint32_t grid);
 
 }  // namespace ttc

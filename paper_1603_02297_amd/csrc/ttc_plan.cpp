@@ -139,11 +139,11 @@ static int pick_extent(int64_t s, int64_t want, int mult)
 
 // Leading indices of one tensor, in that tensor's order, until the contiguous run they
 // span reaches `target` elements.  All but the last are taken whole.
-static void build_group(const Problem& P, const int* order, int64_t target, int vec, int* t)
+static void build_group(const Problem& P, const int* order, int64_t target, int vec, int max_dims, int* t)
 {
     for (int k = 0; k < kMaxDim; ++k) t[k] = 1;
     int64_t run = 1;
-    for (int i = 0; i < P.ndim; ++i) {
+    for (int i = 0; i < P.ndim && i < max_dims; ++i) {
         const int k = order[i];
         const int64_t need = ceil_div(target, run);
         if (need <= 1) break;
@@ -220,44 +220,63 @@ static LaneChoice choose_lanes(const Problem& P, const int* order, const int* t,
     return best;
 }
 
-static void fill_side(const Problem& P, const int* order, const int* t, int vec, const LaneChoice& lc,
-                      const int* lds_stride, Side* s)
+// Lay one walk out digit by digit (only the indices the box spans, in the walk's order).
+// Returns false if the box spans more indices than a walk supports.
+static bool fill_side(const Problem& P, const KernelParams& kp, const int* order, const int* t, int vec,
+                      const LaneChoice& lc, const int* lds_stride, bool follows_b, Side* s)
 {
     std::memset(s, 0, sizeof(*s));
     s->vec = vec;
     const int vdim = order[0];
     uint32_t lane_below = 1, iter_below = 1;
     int64_t n_iter = 1;
-    for (int k = 0; k < kMaxDim; ++k) {
-        s->lane[k] = 1; s->lane_mul[k] = 1;
-        s->lane_below[k] = make_fastdiv(1); s->lane_cnt[k] = make_fastdiv(1);
-        s->iter_below[k] = make_fastdiv(1); s->iters[k] = make_fastdiv(1);
+    int nd = 0;
+    s->exact = 1;
+    for (int i = 0; i < kBoxDims; ++i) {
+        Digit& d = s->d[i];
+        d.tile = 1; d.lane = 1; d.iters = 1; d.lane_mul = 1; d.size = 1;
+        d.lane_below = d.lane_cnt = d.iter_below = d.iter_cnt = d.tile_below = d.tile_cnt = make_fastdiv(1);
     }
     for (int i = 0; i < P.ndim; ++i) {
         const int k = order[i];
+        if (t[k] <= 1) continue;
+        if (nd == kBoxDims || t[k] >= 65536) return false;
+        Digit& d = s->d[nd++];
         const int mul = (k == vdim) ? vec : 1;
         const int cnt = lc.lane[k] / mul;
         const int its = (int)ceil_div(t[k], lc.lane[k]);
-        s->lane[k] = lc.lane[k];
-        s->lane_mul[k] = mul;
-        s->lane_below[k] = make_fastdiv(lane_below);
-        s->lane_cnt[k] = make_fastdiv((uint32_t)cnt);
-        s->iter_below[k] = make_fastdiv(iter_below);
-        s->iters[k] = make_fastdiv((uint32_t)its);
+        d.tile = t[k];
+        d.lane = lc.lane[k];
+        d.iters = its;
+        d.lane_mul = mul;
+        d.lane_below = make_fastdiv(lane_below);
+        d.lane_cnt = make_fastdiv((uint32_t)cnt);
+        d.iter_below = make_fastdiv(iter_below);
+        d.iter_cnt = make_fastdiv((uint32_t)its);
+        d.tile_below = kp.tile_below[k];
+        d.tile_cnt = kp.tile_cnt[k];
+        d.size = P.size[k];
+        d.gstride = follows_b ? P.stride_b[k] : P.stride_a[k];
+        d.g2stride = P.stride_b[k];
+        d.lstride = lds_stride ? lds_stride[k] : 0;
+        if (t[k] % lc.lane[k] != 0) s->exact = 0;
         lane_below *= (uint32_t)cnt;
         iter_below *= (uint32_t)its;
         n_iter *= its;
+        if (n_iter > kMaxIters) return false;
     }
+    s->nd = nd;
     s->lanes = (int)lane_below;
     s->n_iter = (int)n_iter;
     s->vec_lds_stride = lds_stride ? lds_stride[vdim] : 0;
+    return true;
 }
 
 // ---------------------------------------------------------------------------------
 // LDS layout: A order with small pads on the strides, chosen by simulating which banks the
 // 64 lanes of one instruction touch.
 // ---------------------------------------------------------------------------------
-static int bank_multiplicity(const Problem& P, const Side& s, const int* lds_stride, int vec_stride, int banks)
+static int bank_multiplicity(const Problem& P, const Side& s, int banks)
 {
     const int words = P.elem_bytes / 4;
     int worst = 1;
@@ -265,10 +284,11 @@ static int bank_multiplicity(const Problem& P, const Side& s, const int* lds_str
     for (int j = 0; j < s.vec; ++j) {
         int n = 0;
         for (int lane = 0; lane < s.lanes; ++lane) {
-            int64_t a = (int64_t)j * vec_stride;
-            for (int k = 0; k < P.ndim; ++k) {
-                const uint32_t c = (lane / s.lane_below[k].div) % s.lane_cnt[k].div;
-                a += (int64_t)c * s.lane_mul[k] * lds_stride[k];
+            int64_t a = (int64_t)j * s.vec_lds_stride;
+            for (int i = 0; i < s.nd; ++i) {
+                const Digit& d = s.d[i];
+                const uint32_t c = (lane / d.lane_below.div) % d.lane_cnt.div;
+                a += (int64_t)c * d.lane_mul * d.lstride;
             }
             addr[n++] = a * words;
         }
@@ -288,8 +308,8 @@ static int bank_multiplicity(const Problem& P, const Side& s, const int* lds_str
 
 struct LdsLayout { int stride[kMaxDim]; int elems; int conflict_a, conflict_b; };
 
-static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* order_b, int va, int vb,
-                                   const LaneChoice& la, const LaneChoice& lb)
+static LdsLayout choose_lds_layout(const Problem& P, const KernelParams& kp, const int* t, const int* order_b,
+                                   int va, int vb, const LaneChoice& la, const LaneChoice& lb)
 {
     int order_a[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) order_a[k] = k;
@@ -312,14 +332,13 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* or
         }
         if (nb == 0) run = 1;
         L.elems = (int)run;
-        if ((int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
+        if (2 * (int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
         Side sa, sb;
-        fill_side(P, order_a, t, va, la, L.stride, &sa);
-        fill_side(P, order_b, t, vb, lb, L.stride, &sb);
-        L.conflict_a = bank_multiplicity(P, sa, L.stride, sa.vec_lds_stride, 32) +
-                       bank_multiplicity(P, sa, L.stride, sa.vec_lds_stride, 64);
-        L.conflict_b = bank_multiplicity(P, sb, L.stride, sb.vec_lds_stride, 32) +
-                       bank_multiplicity(P, sb, L.stride, sb.vec_lds_stride, 64);
+        if (!fill_side(P, kp, order_a, t, va, la, L.stride, false, &sa)) continue;
+        if (!fill_side(P, kp, order_b, t, vb, lb, L.stride, true, &sb)) continue;
+        sa.vec_lds_stride = 1;
+        L.conflict_a = bank_multiplicity(P, sa, 32) + bank_multiplicity(P, sa, 64);
+        L.conflict_b = bank_multiplicity(P, sb, 32) + bank_multiplicity(P, sb, 64);
         const int64_t cost = ((int64_t)(L.conflict_a + L.conflict_b) << 24) + L.elems;
         if (cost < best_cost) { best_cost = cost; best = L; }
         if (L.conflict_a + L.conflict_b == 4) break;             // conflict-free under both bank counts
@@ -338,7 +357,7 @@ static int max_vec(const Problem& P, int64_t extent)
 }
 
 static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bool direct, int threads,
-                           const int* tile_order, int xcd_remap, Candidate* out)
+                           int wg_per_cu, const int* tile_order, int xcd_remap, Candidate* out)
 {
     Candidate C;
     std::memset(&C, 0, sizeof(C));
@@ -352,7 +371,6 @@ static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bo
     kp.xcd_remap = xcd_remap;
     int64_t ntiles = 1;
     for (int k = 0; k < kMaxDim; ++k) {
-        kp.size[k] = (k < P.ndim) ? P.size[k] : 1;
         kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
         kp.stride_b[k] = (k < P.ndim) ? P.stride_b[k] : 0;
         kp.tile[k] = t[k];
@@ -376,28 +394,49 @@ static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bo
     kp.beta[0] = P.beta[0];   kp.beta[1] = P.beta[1];
 
     const LaneChoice la = choose_lanes(P, order_a, t, va);
+    for (int k = 0; k < kMaxDim; ++k) { C.tile[k] = t[k]; C.lane_a[k] = la.lane[k]; C.lane_b[k] = la.lane[k]; C.lds_stride[k] = 0; }
     if (direct) {
-        fill_side(P, order_a, t, va, la, nullptr, &kp.a);
+        if (!fill_side(P, kp, order_a, t, va, la, nullptr, false, &kp.a)) return false;
         kp.b = kp.a;
         C.kernel_class = TTC_KERNEL_DIRECT;
-        C.lds_bytes = 0;
+        C.lds_bytes = (int)round_up(24 * (int64_t)kp.a.n_iter, 16);
+        kp.lds_data_off = C.lds_bytes;
+        kp.lds_tile_elems = 0;
         C.lds_conflict_a = C.lds_conflict_b = 0;
     } else {
         const LaneChoice lb = choose_lanes(P, order_b, t, vb);
-        const LdsLayout L = choose_lds_layout(P, t, order_b, va, vb, la, lb);
+        const LdsLayout L = choose_lds_layout(P, kp, t, order_b, va, vb, la, lb);
         if (L.elems == 0) return false;
-        for (int k = 0; k < kMaxDim; ++k) kp.lds_stride[k] = L.stride[k];
-        fill_side(P, order_a, t, va, la, L.stride, &kp.a);
-        fill_side(P, order_b, t, vb, lb, L.stride, &kp.b);
+        for (int k = 0; k < kMaxDim; ++k) { C.lds_stride[k] = L.stride[k]; C.lane_b[k] = lb.lane[k]; }
+        if (!fill_side(P, kp, order_a, t, va, la, L.stride, false, &kp.a)) return false;
+        if (!fill_side(P, kp, order_b, t, vb, lb, L.stride, true, &kp.b)) return false;
         C.kernel_class = TTC_KERNEL_LDS;
-        C.lds_bytes = L.elems * P.elem_bytes;
+        kp.lds_data_off = (int)round_up(24 * (int64_t)(kp.a.n_iter + kp.b.n_iter), 16);
+        kp.lds_tile_elems = (int)round_up(L.elems, 16 / P.elem_bytes);
+        C.lds_bytes = kp.lds_data_off + 2 * kp.lds_tile_elems * P.elem_bytes;
+        if (C.lds_bytes > kMaxLdsBytes) return false;
         C.lds_conflict_a = L.conflict_a;
         C.lds_conflict_b = L.conflict_b;
     }
     C.threads = threads;
+    C.wg_per_cu = wg_per_cu;
+    set_grid(&kp, launch_grid(C, 256));
     C.tuned_ms = 0.f;
     *out = C;
     return true;
+}
+
+uint32_t launch_grid(const Candidate& c, int cus)
+{
+    const uint64_t want = (uint64_t)std::max(cus, 1) * (uint64_t)std::max(c.wg_per_cu, 1);
+    return (uint32_t)std::min<uint64_t>(want, c.kp.num_tiles);
+}
+
+void set_grid(KernelParams* kp, uint32_t grid)
+{
+    kp->grid = grid;
+    kp->grid_per_xcd = grid / 8;
+    kp->grid_rem_xcd = grid % 8;
 }
 
 // Heuristic cost of a candidate (smaller is better).  It plays the role of the paper's cost
@@ -441,19 +480,19 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
         cost *= 1.0 + 0.15 * (lane_a - 1.0);
         if (tile_bytes > 64 * 1024) cost *= 1.05;
     }
-    if (C.threads != 256) cost *= 1.03;
+    if (C.threads != 256 || C.wg_per_cu != 8) cost *= 1.03;
     if (kp.num_tiles < 1024) cost *= 1.0 + 256.0 / (kp.num_tiles + 1.0) * 0.25;   // fewer tiles than the chip has slots
     return cost;
 }
 
 static bool same_config(const Candidate& x, const Candidate& y)
 {
-    if (x.kernel_class != y.kernel_class || x.threads != y.threads) return false;
+    if (x.kernel_class != y.kernel_class || x.threads != y.threads || x.wg_per_cu != y.wg_per_cu) return false;
     if (x.kp.a.vec != y.kp.a.vec || x.kp.b.vec != y.kp.b.vec) return false;
     for (int k = 0; k < kMaxDim; ++k) {
-        if (x.kp.tile[k] != y.kp.tile[k]) return false;
+        if (x.tile[k] != y.tile[k]) return false;
         if (x.kp.tile_below[k].div != y.kp.tile_below[k].div) return false;
-        if (x.kp.a.lane[k] != y.kp.a.lane[k] || x.kp.b.lane[k] != y.kp.b.lane[k]) return false;
+        if (x.lane_a[k] != y.lane_a[k] || x.lane_b[k] != y.lane_b[k]) return false;
     }
     return true;
 }
@@ -465,6 +504,10 @@ static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Can
     v.back().score = heuristic_cost(P, c);
 }
 
+// Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
+struct LaunchShape { int threads, wg_per_cu; };
+static const LaunchShape kLaunchShapes[] = {{256, 8}, {128, 16}, {128, 8}, {256, 4}, {512, 4}, {256, 16}};
+
 static void enumerate(const Problem& P, std::vector<Candidate>& out)
 {
     const int n = P.ndim;
@@ -472,7 +515,6 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     int order_a[kMaxDim], order_b[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < n) ? P.perm[k] : k; }
     const bool stride1_fixed = (P.perm[0] == 0);
-    const int threads_opts[3] = {256, 512, 128};
     const int* orders[2] = {order_b, order_a};
 
     // -- direct candidates: only when the stride-1 index keeps its place
@@ -482,11 +524,12 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
             const int64_t tile_bytes_opts[4] = {16384, 32768, 8192, 65536};
             for (int64_t tb : tile_bytes_opts) {
                 int t[kMaxDim];
-                build_group(P, order_a, tb / eb, v, t);
+                build_group(P, order_a, tb / eb, v, kBoxDims, t);
                 for (int o = 0; o < 2; ++o)
-                    for (int th : threads_opts) {
+                    for (const LaunchShape& ls : kLaunchShapes) {
                         Candidate c;
-                        if (make_candidate(P, t, v, v, true, th, orders[o], 1, &c)) add_candidate(P, out, c);
+                        if (make_candidate(P, t, v, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                            add_candidate(P, out, c);
                     }
             }
         }
@@ -502,32 +545,37 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
             const int va = vsel == 0 ? va_full : 1;
             const int vb = vsel == 0 ? vb_full : 1;
             if (vsel == 1 && va_full == 1 && vb_full == 1) break;
-            for (int64_t ra : run_bytes)
-                for (int64_t rb : run_bytes) {
-                    int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                    build_group(P, order_a, ra / eb, va, ta);
-                    build_group(P, order_b, rb / eb, vb, tb);
-                    int64_t vol = 1;
-                    for (int k = 0; k < kMaxDim; ++k) { t[k] = std::max(ta[k], tb[k]); }
-                    t[0] = (int)std::min<int64_t>(round_up(t[0], va), P.size[0]);
-                    t[p0] = (int)std::min<int64_t>(round_up(t[p0], (p0 == 0) ? std::max(va, vb) : vb), P.size[p0]);
-                    for (int k = 0; k < n; ++k) vol *= t[k];
-                    if (vol * eb > kMaxLdsBytes - 2048 || vol * eb < 2048) continue;
-                    for (int o = 0; o < 2; ++o)
-                        for (int th : threads_opts) {
-                            Candidate c;
-                            if (make_candidate(P, t, va, vb, false, th, orders[o], 1, &c)) add_candidate(P, out, c);
-                        }
-                }
+            for (int md = 3; md >= 1; --md)
+                for (int64_t ra : run_bytes)
+                    for (int64_t rb : run_bytes) {
+                        int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
+                        build_group(P, order_a, ra / eb, va, md, ta);
+                        build_group(P, order_b, rb / eb, vb, md, tb);
+                        int64_t vol = 1;
+                        int spanned = 0;
+                        for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
+                        t[0] = (int)std::min<int64_t>(round_up(t[0], va), P.size[0]);
+                        t[p0] = (int)std::min<int64_t>(round_up(t[p0], (p0 == 0) ? std::max(va, vb) : vb), P.size[p0]);
+                        for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
+                        if (spanned > kBoxDims) continue;
+                        if (2 * vol * eb > kMaxLdsBytes - 1024) continue;
+                        if (vol * eb < 2048 && md > 1 && vol < P.elements) continue;
+                        for (int o = 0; o < 2; ++o)
+                            for (const LaunchShape& ls : kLaunchShapes) {
+                                Candidate c;
+                                if (make_candidate(P, t, va, vb, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                                    add_candidate(P, out, c);
+                            }
+                    }
         }
     }
 
     // -- last resort so that every problem has a candidate: scalar direct walk in A order
     if (out.empty() || n == 1) {
         int t[kMaxDim];
-        build_group(P, order_a, 16384 / eb, 1, t);
+        build_group(P, order_a, 16384 / eb, 1, kBoxDims, t);
         Candidate c;
-        if (make_candidate(P, t, 1, 1, true, 256, order_a, 1, &c)) add_candidate(P, out, c);
+        if (make_candidate(P, t, 1, 1, true, 256, 8, order_a, 1, &c)) add_candidate(P, out, c);
     }
 }
 
@@ -550,7 +598,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
         // every candidate is vectorised: add the scalar variant of the best one
         const Candidate& b = plan->cands[0];
         Candidate c;
-        if (!make_candidate(P, b.kp.tile, 1, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.tile_order, 1, &c))
+        if (!make_candidate(P, b.tile, 1, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c))
             return TTC_ERR_OVERFLOW;
         c.score = heuristic_cost(P, c);
         plan->cands.push_back(c);
@@ -621,11 +669,11 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     for (int k = 0; k < P.ndim; ++k) {
         out->sizes[k] = P.size[k];
         out->perm[k] = P.perm[k];
-        out->tile[k] = C.kp.tile[k];
-        out->lane_a[k] = C.kp.a.lane[k];
-        out->lane_b[k] = C.kp.b.lane[k];
+        out->tile[k] = C.tile[k];
+        out->lane_a[k] = C.lane_a[k];
+        out->lane_b[k] = C.lane_b[k];
         out->tile_order[k] = C.tile_order[k];
-        out->lds_stride[k] = C.kp.lds_stride[k];
+        out->lds_stride[k] = C.lds_stride[k];
     }
     out->stride1_fixed = (P.perm[0] == 0) ? 1 : 0;
     out->kernel_class = C.kernel_class;
@@ -633,6 +681,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->vec_a = C.kp.a.vec;
     out->vec_b = C.kp.b.vec;
     out->threads = C.threads;
+    out->wg_per_cu = C.wg_per_cu;
     out->xcd_remap = C.kp.xcd_remap;
     out->lds_bytes = C.lds_bytes;
     out->lds_conflict_a = C.lds_conflict_a;
@@ -671,67 +720,101 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     if (!plan || !b_from_a) return TTC_ERR_NULL_POINTER;
     const Problem& P = plan->prob;
     const Candidate& C = plan->cands[plan->selected];
-    const KernelParams& p = C.kp;
-    const int64_t total = P.elements;
+    KernelParams p = C.kp;
+    set_grid(&p, launch_grid(C, 256));
+    const int64_t total = P.elements, total_bytes = P.elements * P.elem_bytes;
+    const int32_t eb = P.elem_bytes;
     for (int64_t i = 0; i < total; ++i) b_from_a[i] = -1;
     const uint32_t nwave = (uint32_t)C.threads / kWave;
     if (nwave < 1 || C.threads % kWave) return TTC_ERR_INTERNAL;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
-    const int64_t lds_elems = C.lds_bytes / P.elem_bytes;
-    std::vector<int64_t> lds((size_t)lds_elems);
-    std::vector<char> seen(p.num_tiles, 0);
-    for (uint32_t wg = 0; wg < p.num_tiles; ++wg) {
-        const uint32_t tile = tile_of_workgroup(p, wg);
-        if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
-        seen[tile] = 1;
-        const TilePos tp = tile_pos(p, tile);
-        if (direct) {
-            for (uint32_t it = 0; it < (uint32_t)p.a.n_iter; ++it)
-                for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                    const LaneState L = lane_setup<true>(p, p.a, p.stride_a, lane);
-                    const IterPos q = iter_pos<true>(p, p.a, p.stride_a, tp.lim, L, it);
-                    if (!q.valid) continue;
-                    const int64_t oa = tp.base_a + q.g + L.g, ob = tp.base_b + q.g2 + L.g2;
-                    if (oa % p.a.vec || ob % p.a.vec) return TTC_ERR_INTERNAL;
-                    for (int j = 0; j < p.a.vec; ++j) {
-                        if (oa + j < 0 || oa + j >= total || ob + j < 0 || ob + j >= total) return TTC_ERR_INTERNAL;
-                        if (b_from_a[ob + j] != -1) return TTC_ERR_INTERNAL;
-                        b_from_a[ob + j] = oa + j;
-                    }
-                }
-            continue;
-        }
-        std::fill(lds.begin(), lds.end(), (int64_t)-1);
-        for (uint32_t it = 0; it < (uint32_t)p.a.n_iter; ++it)
-            for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                const LaneState L = lane_setup<false>(p, p.a, p.stride_a, lane);
-                const IterPos q = iter_pos<false>(p, p.a, p.stride_a, tp.lim, L, it);
-                if (!q.valid) continue;
-                const int64_t oa = tp.base_a + q.g + L.g;
-                const int64_t lo = (int64_t)q.l + L.l;
-                if (oa % p.a.vec) return TTC_ERR_INTERNAL;
-                for (int j = 0; j < p.a.vec; ++j) {
-                    if (oa + j < 0 || oa + j >= total || lo + j < 0 || lo + j >= lds_elems) return TTC_ERR_INTERNAL;
-                    if (lds[lo + j] != -1) return TTC_ERR_INTERNAL;
-                    lds[lo + j] = oa + j;
-                }
-            }
-        for (uint32_t it = 0; it < (uint32_t)p.b.n_iter; ++it)
-            for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                const LaneState L = lane_setup<false>(p, p.b, p.stride_b, lane);
-                const IterPos q = iter_pos<false>(p, p.b, p.stride_b, tp.lim, L, it);
-                if (!q.valid) continue;
-                const int64_t ob = tp.base_b + q.g + L.g;
-                const int64_t lo = (int64_t)q.l + L.l;
-                if (ob % p.b.vec) return TTC_ERR_INTERNAL;
-                for (int j = 0; j < p.b.vec; ++j) {
-                    const int64_t li = lo + (int64_t)j * p.b.vec_lds_stride;
-                    if (ob + j < 0 || ob + j >= total || li < 0 || li >= lds_elems) return TTC_ERR_INTERNAL;
-                    if (lds[li] == -1 || b_from_a[ob + j] != -1) return TTC_ERR_INTERNAL;
-                    b_from_a[ob + j] = lds[li];
-                }
-            }
+    const uint32_t n_a = (uint32_t)p.a.n_iter, n_b = direct ? 0u : (uint32_t)p.b.n_iter;
+    if ((int64_t)24 * (n_a + n_b) > p.lds_data_off) return TTC_ERR_INTERNAL;
+    if (p.lds_data_off + 2 * (int64_t)p.lds_tile_elems * eb != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
+        return TTC_ERR_INTERNAL;
+    // position tables, as a workgroup builds them
+    std::vector<PosEntry> tab_a(n_a), tab_b(n_b);
+    std::vector<PosCoord> tabc_a(n_a), tabc_b(n_b);
+    for (uint32_t it = 0; it < n_a; ++it) {
+        if (direct) make_position<true>(p.a, it, eb, &tab_a[it], &tabc_a[it]);
+        else make_position<false>(p.a, it, eb, &tab_a[it], &tabc_a[it]);
     }
+    for (uint32_t it = 0; it < n_b; ++it) make_position<false>(p.b, it, eb, &tab_b[it], &tabc_b[it]);
+
+    const int64_t lds_bytes = (int64_t)p.lds_tile_elems * eb;
+    std::vector<int64_t> lds((size_t)p.lds_tile_elems);          // which byte offset of A each slot holds
+    std::vector<char> seen(p.num_tiles, 0);
+    bool bad = false;
+    auto fail = [&]() { bad = true; };
+    auto nop = [](int, const PosEntry&) {};
+    for (uint32_t wg = 0; wg < p.grid && !bad; ++wg) {
+        const TileSeq seq = tile_sequence(p, wg);
+        for (uint32_t tile = seq.first; tile < seq.end && !bad; tile += seq.step) {
+            if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
+            seen[tile] = 1;
+            const TileBase tb = tile_base(p, tile);
+            const int64_t base_a = tb.a * eb, base_b = tb.b * eb;
+            const TileLim la = tile_lim(p.a, tile);
+            if (direct) {
+                for (uint32_t wave = 0; wave < nwave; ++wave)
+                    for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                        const LaneState L = lane_setup<true>(p.a, lane, eb);
+                        auto st = [&](int, const PosEntry& e) {
+                            const int64_t oa = base_a + e.g + L.g, ob = base_b + e.l_or_g2 + L.g2;
+                            const int64_t w = (int64_t)p.a.vec * eb;
+                            if (oa % w || ob % w) return fail();
+                            if (oa < 0 || oa + w > total_bytes || ob < 0 || ob + w > total_bytes) return fail();
+                            for (int j = 0; j < p.a.vec; ++j) {
+                                if (b_from_a[ob / eb + j] != -1) return fail();
+                                b_from_a[ob / eb + j] = oa / eb + j;
+                            }
+                        };
+                        if (la.full) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                        else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                    }
+                continue;
+            }
+            std::fill(lds.begin(), lds.end(), (int64_t)-1);
+            for (uint32_t wave = 0; wave < nwave; ++wave)
+                for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                    const LaneState L = lane_setup<false>(p.a, lane, eb);
+                    auto st = [&](int, const PosEntry& e) {
+                        const int64_t oa = base_a + e.g + L.g;
+                        const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
+                        const int64_t w = (int64_t)p.a.vec * eb;
+                        if (oa % w || lo % eb) return fail();
+                        if (oa < 0 || oa + w > total_bytes || lo < 0 || lo + w > lds_bytes) return fail();
+                        for (int j = 0; j < p.a.vec; ++j) {
+                            if (lds[lo / eb + j] != -1) return fail();
+                            lds[lo / eb + j] = oa / eb + j;
+                        }
+                    };
+                    if (la.full) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                    else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                }
+            const TileLim lb = tile_lim(p.b, tile);
+            for (uint32_t wave = 0; wave < nwave; ++wave)
+                for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
+                    const LaneState L = lane_setup<false>(p.b, lane, eb);
+                    auto st = [&](int, const PosEntry& e) {
+                        const int64_t ob = base_b + e.g + L.g;
+                        const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
+                        const int64_t w = (int64_t)p.b.vec * eb;
+                        if (ob % w || lo % eb) return fail();
+                        if (ob < 0 || ob + w > total_bytes) return fail();
+                        for (int j = 0; j < p.b.vec; ++j) {
+                            const int64_t li = lo / eb + (int64_t)j * p.b.vec_lds_stride;
+                            if (li < 0 || li >= p.lds_tile_elems) return fail();
+                            if (lds[li] == -1 || b_from_a[ob / eb + j] != -1) return fail();
+                            b_from_a[ob / eb + j] = lds[li];
+                        }
+                    };
+                    if (lb.full) walk<4, true>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
+                    else walk<4, false>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
+                }
+        }
+    }
+    if (bad) return TTC_ERR_INTERNAL;
     for (int64_t i = 0; i < total; ++i) if (b_from_a[i] < 0) return TTC_ERR_INTERNAL;
     return TTC_OK;
 }

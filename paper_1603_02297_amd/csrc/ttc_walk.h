@@ -1,6 +1,14 @@
-// Index arithmetic of a tile walk, shared by the device kernels and by the host-side
-// bounds checker (ttc_debug_emulate_map), so that what the checker proves in bounds is
-// the code the GPU runs.
+// Index arithmetic of a tile walk, shared by the device kernels and by the host-side bounds
+// checker (ttc_debug_emulate_map), so that what the checker proves in bounds is the code the
+// GPU runs.
+//
+// A walk covers the tile with copies of one fixed sub-box.  Two small tables make a step of
+// the walk cost a handful of instructions whatever the number of indices:
+//   * per lane (vector registers, built once per workgroup): where the lane sits inside the
+//     sub-box -- its offset in the tensor, its offset in the LDS tile, its coordinates;
+//   * per sub-box position (LDS, built once per workgroup, the same for every tile): where
+//     the sub-box sits inside the tile -- the same three things.
+// A memory access of the walk is then  tile base + position entry + lane entry.
 #pragma once
 
 #include "ttc_internal.h"
@@ -23,90 +31,168 @@ TTC_HD uint32_t fdigit(uint32_t x, const FastDiv& below, const FastDiv& cnt)
     return q - fdiv(q, cnt) * cnt.div;
 }
 
-// workgroup id -> tile id.  Consecutive workgroup ids land on consecutive XCDs; every XCD gets
-// one contiguous range of tiles so that neighbouring tiles share its L2.
-TTC_HD uint32_t tile_of_workgroup(const KernelParams& p, uint32_t wg)
+// ---- which tiles a workgroup walks ---------------------------------------------------------
+// Consecutive workgroup ids land on consecutive XCDs (8 of them, each with its own L2).  Every
+// XCD owns one contiguous range of tile ids; its workgroups take the tiles of that range round
+// robin, so tiles that are neighbours in memory are in flight on the same XCD at the same time.
+struct TileSeq { uint32_t first, end, step; };
+
+TTC_HD TileSeq tile_sequence(const KernelParams& p, uint32_t wg)
 {
-    if (!p.xcd_remap) return wg;
+    TileSeq s;
+    if (!p.xcd_remap || p.grid < 8u) {
+        s.first = wg; s.end = p.num_tiles; s.step = p.grid;
+        return s;
+    }
     const uint32_t x = wg & 7u, slot = wg >> 3;
-    return x * p.tiles_per_xcd + (x < p.tiles_rem_xcd ? x : p.tiles_rem_xcd) + slot;
+    const uint32_t lo = x * p.tiles_per_xcd + (x < p.tiles_rem_xcd ? x : p.tiles_rem_xcd);
+    s.first = lo + slot;
+    s.end = lo + p.tiles_per_xcd + (x < p.tiles_rem_xcd ? 1u : 0u);
+    s.step = p.grid_per_xcd + (x < p.grid_rem_xcd ? 1u : 0u);
+    return s;
 }
 
-// tile id -> base offsets of the box in A and B and the part of the box inside the tensor
-struct TilePos { int64_t base_a, base_b; int32_t lim[kMaxDim]; };
+// tile id -> element offsets of the box origin in A and in B
+struct TileBase { int64_t a, b; };
 
-TTC_HD TilePos tile_pos(const KernelParams& p, uint32_t tile)
+TTC_HD TileBase tile_base(const KernelParams& p, uint32_t tile)
 {
-    TilePos t;
-    t.base_a = 0; t.base_b = 0;
+    TileBase t;
+    t.a = 0; t.b = 0;
+    for (int k = 0; k < p.n; ++k) {
+        const int64_t origin = (int64_t)fdigit(tile, p.tile_below[k], p.tile_cnt[k]) * p.tile[k];
+        t.a += origin * p.stride_a[k];
+        t.b += origin * p.stride_b[k];
+    }
+    return t;
+}
+
+// How much of the box lies inside the tensor, per digit of one walk.  full: nothing is cut
+// off and the sub-box tiles the box exactly, so the walk needs no per-lane bounds test.
+struct TileLim { int32_t lim[kBoxDims]; bool full; };
+
+TTC_HD TileLim tile_lim(const Side& s, uint32_t tile)
+{
+    TileLim t;
+    t.full = (s.exact != 0);
 #pragma unroll
-    for (int k = 0; k < kMaxDim; ++k) {
-        t.lim[k] = 1;
-        if (k < p.n) {
-            const int64_t origin = (int64_t)fdigit(tile, p.tile_below[k], p.tile_cnt[k]) * p.tile[k];
-            t.base_a += origin * p.stride_a[k];
-            t.base_b += origin * p.stride_b[k];
-            const int64_t left = p.size[k] - origin;
-            t.lim[k] = (int32_t)(left < (int64_t)p.tile[k] ? left : (int64_t)p.tile[k]);
+    for (int i = 0; i < kBoxDims; ++i) {
+        t.lim[i] = 1;
+        if (i < s.nd) {
+            const Digit& d = s.d[i];
+            const int64_t origin = (int64_t)fdigit(tile, d.tile_below, d.tile_cnt) * d.tile;
+            const int64_t left = d.size - origin;
+            t.lim[i] = (int32_t)(left < (int64_t)d.tile ? left : (int64_t)d.tile);
+            t.full = t.full && (t.lim[i] == d.tile);
         }
     }
     return t;
 }
 
-// What one lane keeps for a walk: its fixed coordinates inside the wavefront's sub-box.
+// ---- lane entry ------------------------------------------------------------------------------
+// Offsets are in BYTES (element offsets times `scale`, the element size).
 struct LaneState {
-    int64_t g;                 // offset (elements) into the tensor the walk follows
-    int64_t g2;                // direct kernel: offset into B
-    int32_t l;                 // offset into the LDS tile
-    int32_t c[kMaxDim];        // coordinate along each index, in elements
+    int64_t g;                 // byte offset into the tensor the walk follows
+    int64_t g2;                // direct kernel: byte offset into B
+    int32_t l;                 // byte offset into the LDS tile
+    int32_t c[kBoxDims];       // coordinate along each digit, in elements
     bool    active;
 };
 
 template <bool DIRECT>
-TTC_HD LaneState lane_setup(const KernelParams& p, const Side& s, const int64_t* stride, uint32_t lane)
+TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, int32_t scale)
 {
     LaneState L;
     L.g = 0; L.g2 = 0; L.l = 0;
     L.active = lane < (uint32_t)s.lanes;
 #pragma unroll
-    for (int k = 0; k < kMaxDim; ++k) {
-        L.c[k] = 0;
-        if (k < p.n && s.lane[k] > 1) {
-            const int32_t c = (int32_t)fdigit(lane, s.lane_below[k], s.lane_cnt[k]) * s.lane_mul[k];
-            L.c[k] = c;
-            L.g += (int64_t)c * stride[k];
-            if (DIRECT) L.g2 += (int64_t)c * p.stride_b[k];
-            else L.l += c * p.lds_stride[k];
+    for (int i = 0; i < kBoxDims; ++i) {
+        L.c[i] = 0;
+        if (i < s.nd && s.d[i].lane > 1) {
+            const Digit& d = s.d[i];
+            const int32_t c = (int32_t)fdigit(lane, d.lane_below, d.lane_cnt) * d.lane_mul;
+            L.c[i] = c;
+            L.g += (int64_t)c * d.gstride;
+            if (DIRECT) L.g2 += (int64_t)c * d.g2stride;
+            else L.l += c * d.lstride;
         }
     }
+    L.g *= scale; L.g2 *= scale; L.l *= scale;
     return L;
 }
 
-// Position of the wavefront's sub-box for iteration `it` of a walk (wave-uniform), and whether
-// this lane's element(s) fall inside the tile and the tensor.
-struct IterPos { int64_t g, g2; int32_t l; bool valid; };
+// ---- position entry --------------------------------------------------------------------------
+// 16 + 8 bytes per sub-box position: offsets of the sub-box origin, and its coordinates inside
+// the tile packed 16 bits per digit (tile extents stay below 65536).
+struct alignas(16) PosEntry {
+    int64_t g;                 // byte offset in the tensor the walk follows
+    int64_t l_or_g2;           // staged kernel: LDS byte offset; direct kernel: byte offset in B
+};
+struct alignas(8) PosCoord { uint32_t c01, c23; };
 
 template <bool DIRECT>
-TTC_HD IterPos iter_pos(const KernelParams& p, const Side& s, const int64_t* stride, const int32_t* lim,
-                        const LaneState& L, uint32_t it)
+TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e, PosCoord* c)
 {
-    IterPos r;
-    r.g = 0; r.g2 = 0; r.l = 0;
-    r.valid = L.active;
+    int64_t g = 0, x = 0;
+    uint32_t pc[kBoxDims];
 #pragma unroll
-    for (int k = 0; k < kMaxDim; ++k) {
-        if (k < p.n && p.tile[k] > 1) {
-            int32_t base = 0;
-            if (s.iters[k].div > 1) {
-                base = (int32_t)fdigit(it, s.iter_below[k], s.iters[k]) * s.lane[k];
-                r.g += (int64_t)base * stride[k];
-                if (DIRECT) r.g2 += (int64_t)base * p.stride_b[k];
-                else r.l += base * p.lds_stride[k];
-            }
-            r.valid = r.valid && (L.c[k] < lim[k] - base);
+    for (int i = 0; i < kBoxDims; ++i) {
+        pc[i] = 0;
+        if (i < s.nd && s.d[i].iters > 1) {
+            const Digit& d = s.d[i];
+            const uint32_t q = fdigit(it, d.iter_below, d.iter_cnt) * (uint32_t)d.lane;
+            pc[i] = q;
+            g += (int64_t)q * d.gstride;
+            x += (int64_t)q * (DIRECT ? d.g2stride : (int64_t)d.lstride);
         }
     }
-    return r;
+    e->g = g * scale;
+    e->l_or_g2 = x * scale;
+    c->c01 = pc[0] | (pc[1] << 16);
+    c->c23 = pc[2] | (pc[3] << 16);
+}
+
+// does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
+TTC_HD bool lane_valid(const Side& s, const LaneState& L, const int32_t* lim, const PosCoord& pc)
+{
+    bool v = L.active;
+    const int32_t p0 = (int32_t)(pc.c01 & 0xffffu), p1 = (int32_t)(pc.c01 >> 16);
+    const int32_t p2 = (int32_t)(pc.c23 & 0xffffu), p3 = (int32_t)(pc.c23 >> 16);
+    v = v && (L.c[0] < lim[0] - p0);
+    if (s.nd > 1) v = v && (L.c[1] < lim[1] - p1);
+    if (s.nd > 2) v = v && (L.c[2] < lim[2] - p2);
+    if (s.nd > 3) v = v && (L.c[3] < lim[3] - p3);
+    return v;
+}
+
+// Drive one wavefront through its share of a walk: wavefront `wave` of `nwave` takes the
+// sub-box positions wave, wave + nwave, ...  Positions are handled U at a time: stage1 for all
+// U (issue the loads), then stage2 for all U (consume them), so that U memory instructions are
+// in flight per wavefront.   stage(u, entry): u = slot 0..U-1.
+template <int U, bool FULL, class Stage1, class Stage2>
+TTC_HD void walk(const Side& s, const LaneState& L, const int32_t* lim, const PosEntry* tab,
+                 const PosCoord* tabc, uint32_t wave, uint32_t nwave, Stage1&& stage1, Stage2&& stage2)
+{
+    const uint32_t n_it = (uint32_t)s.n_iter;
+    for (uint32_t it0 = wave; it0 < n_it; it0 += U * nwave) {
+        PosEntry e[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t it = it0 + u * nwave;
+            ok[u] = false;
+            if (it < n_it) {
+                e[u] = tab[it];
+                ok[u] = FULL ? L.active : lane_valid(s, L, lim, tabc[it]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) stage1(u, e[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) stage2(u, e[u]);
+    }
 }
 
 }  // namespace ttc
