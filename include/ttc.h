@@ -63,8 +63,12 @@ typedef struct {
     int     kernel_class;                  /* TTC_KERNEL_* of the selected candidate */
     int     epilogue;                      /* TTC_EPI_* */
     int     tile[TTC_MAX_DIM];             /* extent of the tile (box) along each fused index; 1 = not blocked */
-    int     lane_a[TTC_MAX_DIM];           /* sub-box one wavefront instruction covers on the load side */
-    int     lane_b[TTC_MAX_DIM];           /* ... on the store side */
+    int     digits_a, digits_b;            /* digits of the load walk (A order) and of the store walk (B order): a digit
+                                              is one index, or the leading indices of that tensor that lie whole inside
+                                              the tile merged into one flat, contiguous index */
+    int     digit_tile_a[4], digit_lane_a[4]; /* per digit of the load walk, in its order: flat extent inside the tile,
+                                              and extent of the sub-box one wavefront instruction covers */
+    int     digit_tile_b[4], digit_lane_b[4]; /* the same for the store walk */
     int     tile_order[TTC_MAX_DIM];       /* fused indices from fastest to slowest in the workgroup-id -> tile map */
     int     lds_stride[TTC_MAX_DIM];       /* element stride of each fused index inside the LDS tile (0 = unused) */
     int     vec_a, vec_b;                  /* elements per lane per global access on the A side / B side */
@@ -99,8 +103,8 @@ ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int*
 /*
  * Run the plan: B <- alpha * permute(A) + beta * B (paper Eq. 1).
  *   A, B    DEVICE pointers to prod(sizes) elements each, dense, column-major, aligned to
- *           the element size; 16-byte alignment enables the vector paths (else the plan's
- *           scalar fallback runs).  They must not overlap (TTC_ERR_ALIAS).
+ *           the element size (vector accesses need no more than that).  They must not
+ *           overlap (TTC_ERR_ALIAS).
  *   stream  hipStream_t passed as void*; NULL is the default stream.
  * Asynchronous: enqueues one kernel on `stream`, allocates nothing, never synchronises.
  * With beta == 0, B is never read.  Returns the launch status.

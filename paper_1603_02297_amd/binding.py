@@ -30,8 +30,10 @@ class ttc_plan_info_t(ctypes.Structure):
         ("dtype", ctypes.c_int), ("ndim", ctypes.c_int),
         ("sizes", ctypes.c_int64 * TTC_MAX_DIM), ("perm", ctypes.c_int * TTC_MAX_DIM),
         ("stride1_fixed", ctypes.c_int), ("kernel_class", ctypes.c_int), ("epilogue", ctypes.c_int),
-        ("tile", ctypes.c_int * TTC_MAX_DIM), ("lane_a", ctypes.c_int * TTC_MAX_DIM),
-        ("lane_b", ctypes.c_int * TTC_MAX_DIM), ("tile_order", ctypes.c_int * TTC_MAX_DIM),
+        ("tile", ctypes.c_int * TTC_MAX_DIM), ("digits_a", ctypes.c_int), ("digits_b", ctypes.c_int),
+        ("digit_tile_a", ctypes.c_int * 4), ("digit_lane_a", ctypes.c_int * 4),
+        ("digit_tile_b", ctypes.c_int * 4), ("digit_lane_b", ctypes.c_int * 4),
+        ("tile_order", ctypes.c_int * TTC_MAX_DIM),
         ("lds_stride", ctypes.c_int * TTC_MAX_DIM),
         ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
         ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int),
@@ -45,7 +47,10 @@ class ttc_plan_info_t(ctypes.Structure):
         out = {}
         for name, _ in self._fields_:
             v = getattr(self, name)
-            out[name] = list(v)[:n] if hasattr(v, "__len__") else v
+            if name.startswith("digit_"):
+                out[name] = list(v)[:(self.digits_a if name.endswith("_a") else self.digits_b)]
+            else:
+                out[name] = list(v)[:n] if hasattr(v, "__len__") else v
         return out
 
 

@@ -32,7 +32,9 @@ namespace ttc {
 // ---------------------------------------------------------------------------------
 struct alignas(8) cfloat { float re, im; };
 
-template <typename T, int V> struct alignas(sizeof(T) * V) Pack { T v[V]; };
+// Global vectors are only guaranteed element alignment (gfx950 global dwordx2/x4 accesses need
+// no more); the hardware runs them at full rate at any 4-byte boundary.
+template <typename T, int V> struct alignas(alignof(T)) Pack { T v[V]; };
 
 template <typename T, int MODE> struct Epilogue;
 
@@ -128,8 +130,10 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         const unsigned char* At = reinterpret_cast<const unsigned char*>(A + tb.a);
         unsigned char* Bt = reinterpret_cast<unsigned char*>(B + tb.b);
 
+        const TileLim tl = tile_lim(p, tile);
+        const SideLim sla = side_lim(p.a, tl);
+        const bool full_a = tl.whole && p.a.exact;
         if (DIRECT) {
-            const TileLim tl = tile_lim(p.a, tile);
             Pack<T, VA> ra[kUnroll], rb[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
                 ra[u] = load_pack<T, VA>(At, e.g + LA.g);
@@ -141,8 +145,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
                 *reinterpret_cast<Pack<T, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
             };
-            if (tl.full) walk<kUnroll, true>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, store);
-            else walk<kUnroll, false>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, store);
+            if (full_a) walk<kUnroll, true>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, store);
+            else walk<kUnroll, false>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, store);
             continue;
         }
 
@@ -150,21 +154,22 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         parity ^= 1u;
         // ---- walk 1: A order, global -> LDS
         {
-            const TileLim tl = tile_lim(p.a, tile);
+            const int32_t vs = p.a.vec_lds_stride;
             Pack<T, VA> ra[kUnroll];
             auto load = [&](int u, const PosEntry& e) { ra[u] = load_pack<T, VA>(At, e.g + LA.g); };
             auto park = [&](int u, const PosEntry& e) {
                 T* dst = reinterpret_cast<T*>(lds + ((int32_t)e.l_or_g2 + LA.l));
 #pragma unroll
-                for (int j = 0; j < VA; ++j) dst[j] = ra[u].v[j];
+                for (int j = 0; j < VA; ++j) dst[j * vs] = ra[u].v[j];
             };
-            if (tl.full) walk<kUnroll, true>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, park);
-            else walk<kUnroll, false>(p.a, LA, tl.lim, tab_a, tabc_a, wave, nwave, load, park);
+            if (full_a) walk<kUnroll, true>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, park);
+            else walk<kUnroll, false>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, park);
         }
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
         {
-            const TileLim tl = tile_lim(p.b, tile);
+            const SideLim slb = side_lim(p.b, tl);
+            const bool full_b = tl.whole && p.b.exact;
             const int32_t vs = p.b.vec_lds_stride;
             Pack<T, VB> rb[kUnroll], rl[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
@@ -179,8 +184,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VB; ++j) out.v[j] = epi(rl[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : rl[u].v[j]);
                 *reinterpret_cast<Pack<T, VB>*>(Bt + (e.g + LB.g)) = out;
             };
-            if (tl.full) walk<kUnroll, true>(p.b, LB, tl.lim, tab_b, tabc_b, wave, nwave, load, store);
-            else walk<kUnroll, false>(p.b, LB, tl.lim, tab_b, tabc_b, wave, nwave, load, store);
+            if (full_b) walk<kUnroll, true>(p.b, LB, slb.lim, tab_b, tabc_b, wave, nwave, load, store);
+            else walk<kUnroll, false>(p.b, LB, slb.lim, tab_b, tabc_b, wave, nwave, load, store);
         }
     }
 }
@@ -274,10 +279,8 @@ static int check_buffers(const ttc_plan_s* plan, const void* A, const void* B)
 
 static const Candidate& pick_candidate(const ttc_plan_s* plan, const void* A, const void* B)
 {
-    const Candidate& c = plan->cands[plan->selected];
-    const bool aligned16 = (((uintptr_t)A | (uintptr_t)B) % 16) == 0;
-    if (!aligned16 && (c.kp.a.vec > 1 || c.kp.b.vec > 1)) return plan->cands[plan->fallback];
-    return c;
+    (void)A; (void)B;
+    return plan->cands[plan->selected];
 }
 
 // ---------------------------------------------------------------------------------
@@ -346,14 +349,12 @@ int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max
     const int total = (int)plan->cands.size();
     if (cap < 0 || cap > total) cap = total;
     if (cap == 1) { plan->selected = 0; return TTC_OK; }
-    const bool aligned16 = (((uintptr_t)A | (uintptr_t)B) % 16) == 0;
     ttc::EventPair ev;
     if (!ev.ok) return TTC_ERR_HIP;
     int best = -1;
     float best_ms = 0.f;
     for (int i = 0; i < cap; ++i) {
         ttc::Candidate& c = plan->cands[i];
-        if (!aligned16 && (c.kp.a.vec > 1 || c.kp.b.vec > 1)) continue;
         const int reps = 3;
         if (ttc::launch(plan->prob, c, A, B, s) != hipSuccess) return TTC_ERR_HIP;      // warm-up
         if (hipEventRecord(ev.start, s) != hipSuccess) return TTC_ERR_HIP;

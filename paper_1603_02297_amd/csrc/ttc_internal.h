@@ -28,31 +28,41 @@ FastDiv make_fastdiv(uint32_t d);
 constexpr int kBoxDims = 4;               // a box spans at most this many indices
 constexpr int kMaxIters = 2048;           // sub-box positions per tile and walk (size of the position table)
 
-// One index of the box as one walk sees it.  A walk ("side") lists only the indices the box
-// really spans (extent > 1), in the order of the tensor it follows, stride-1 index first.
+// A box spans at most kBoxDims indices of the tensor; "slot" j is the j-th of them in A order.
+// Each walk ("side") sees the box as up to kBoxDims digits.  A digit is one index, or -- when
+// the leading indices of the walk's tensor lie whole inside the box -- the chain of those
+// indices merged into one flat index (the tile-level form of the paper's index fusion): the
+// flat digit is contiguous in memory over the whole chain.  Digits are stored at the slot of
+// the chain's outermost index, the only one the tensor's edge can cut; a slot whose index is
+// an inner member of a chain holds an empty digit (tile = 1).
 struct Digit {
-    int32_t  tile;                   // box extent along the index
-    int32_t  lane;                   // extent of the sub-box the 64 lanes cover (elements)
-    int32_t  iters;                  // ceil(tile / lane): sub-box positions along the index
-    int32_t  lane_mul;               // elements per lane step: vec on the vector index, else 1
-    FastDiv  lane_below, lane_cnt;   // lane id  -> lane coordinate: (lane / below) % cnt
+    int32_t  tile;                   // flat extent of the digit inside the box
+    int32_t  lane;                   // flat extent of the sub-box the 64 lanes cover
+    int32_t  iters;                  // ceil(tile / lane): sub-box positions along the digit
+    int32_t  lane_mul;               // flat elements per lane step: vec on the vector digit, else 1
+    int32_t  slot_mul;               // flat elements per step of the slot's index (product of merged inner extents)
+    int32_t  lstride;                // LDS element stride of one flat step
+    FastDiv  lane_below, lane_cnt;   // lane id -> lane coordinate: (lane / below) % cnt
     FastDiv  iter_below, iter_cnt;   // position id -> position digit
-    FastDiv  tile_below, tile_cnt;   // tile id -> tile coordinate along this index
-    int64_t  size;                   // extent of the index in the tensor
-    int64_t  gstride;                // element stride in the tensor the walk follows
+    int64_t  gstride;                // element stride of one flat step in the tensor the walk follows
     int64_t  g2stride;               // direct kernel: element stride in B
-    int32_t  lstride;                // element stride inside the LDS tile
-    int32_t  pad;
 };
 
 struct Side {
-    int32_t  nd;                     // digits in use (<= kBoxDims)
-    int32_t  vec;                    // elements per lane per access, along digit 0
+    int32_t  vec;                    // elements per lane per access, along the walk's first digit
     int32_t  lanes;                  // active lanes of a wavefront
     int32_t  n_iter;                 // sub-box positions per tile = prod(iters)
     int32_t  vec_lds_stride;         // LDS element stride between the vec elements of one lane
     int32_t  exact;                  // 1: lane divides tile on every digit (no ragged sub-boxes)
+    int32_t  pad;
     Digit    d[kBoxDims];
+};
+
+struct Slot {
+    int32_t  tile;                   // box extent along the slot's index
+    int32_t  pad;
+    int64_t  size;                   // extent of the index in the tensor
+    FastDiv  tile_below, tile_cnt;   // tile id -> tile coordinate along this index
 };
 
 // Everything a kernel launch needs; passed by value as the kernel argument.
@@ -67,6 +77,9 @@ struct KernelParams {
     uint32_t grid_rem_xcd;           // grid % 8
     int32_t  lds_data_off;           // byte offset of the first data buffer in dynamic LDS
     int32_t  lds_tile_elems;         // elements per LDS data buffer (padded tile)
+    int32_t  nslots;                 // indices the box spans
+    int32_t  pad2;
+    Slot     slot[kBoxDims];
     int32_t  tile[kMaxDim];          // box extent per fused index of A (1 = index not blocked)
     FastDiv  tile_below[kMaxDim];    // prod of tile counts of the indices that vary faster in the tile order
     FastDiv  tile_cnt[kMaxDim];      // ceil(size[k] / tile[k])
@@ -85,7 +98,10 @@ struct Candidate {
     int      wg_per_cu;              // workgroups launched per compute unit (each walks several tiles)
     int      lds_bytes;              // dynamic LDS per workgroup: position tables + two tile buffers
     int      tile_order[kMaxDim];
-    int      tile[kMaxDim], lane_a[kMaxDim], lane_b[kMaxDim], lds_stride[kMaxDim];   // by fused index of A
+    int      tile[kMaxDim], lds_stride[kMaxDim];   // by fused index of A
+    int      digits_a, digits_b;                   // digits of each walk, in the walk's own order:
+    int      dtile_a[kBoxDims], dlane_a[kBoxDims]; //   flat extent and lane sub-box extent
+    int      dtile_b[kBoxDims], dlane_b[kBoxDims];
     int      lds_conflict_a, lds_conflict_b;
     double   score;                  // heuristic cost, smaller is better
     float    tuned_ms;

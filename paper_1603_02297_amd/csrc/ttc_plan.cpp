@@ -170,111 +170,159 @@ static int64_t box_run(const Problem& P, const int* order, const int* t)
 }
 
 // ---------------------------------------------------------------------------------
-// Lane mapping: which sub-box of the tile one wavefront instruction covers.
+// Walks: how each side sees the box
 // ---------------------------------------------------------------------------------
-struct LaneChoice { int lane[kMaxDim]; int n_iter; int lanes; };
+struct DigitSpec {
+    int first_dim;      // innermost index of the chain (the stride-1 end)
+    int outer_dim;      // outermost index of the chain: the only one the tensor's edge can cut
+    int tile;           // flat extent inside the box
+    int inner;          // product of the box extents of the chain's inner indices
+    int lane;           // flat extent of the lane sub-box (filled by choose_lanes)
+};
+struct WalkSpec { int nd; DigitSpec d[kBoxDims]; };
 
-static LaneChoice choose_lanes(const Problem& P, const int* order, const int* t, int vec)
+// Digits of one walk in the walk's own order.  With `merge`, the leading indices that lie whole
+// inside the box fuse with their successor into one flat digit (tile-level index fusion); an
+// index whose bit is set in `no_tail` may not be appended to a chain.
+static bool build_walk(const Problem& P, const int* order, const int* t, bool merge, unsigned no_tail,
+                       WalkSpec* w)
 {
-    LaneChoice best;
-    best.n_iter = INT32_MAX;
-    best.lanes = 0;
+    w->nd = 0;
+    bool leading = true;
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = order[i];
+        if (t[k] <= 1) { leading = false; continue; }
+        if (merge && leading && w->nd == 1) {
+            DigitSpec& d = w->d[0];
+            const int prev = d.outer_dim;
+            if (i > 0 && order[i - 1] == prev && t[prev] == P.size[prev] && !(no_tail & (1u << k)) &&
+                (int64_t)d.tile * t[k] < 65536) {
+                d.inner = d.tile;
+                d.tile *= t[k];
+                d.outer_dim = k;
+                continue;
+            }
+        }
+        if (w->nd >= 1) leading = false;
+        if (w->nd == kBoxDims) return false;
+        DigitSpec& d = w->d[w->nd++];
+        d.first_dim = d.outer_dim = k;
+        d.tile = t[k];
+        d.inner = 1;
+        d.lane = 1;
+        if (t[k] >= 65536) return false;
+    }
+    return w->nd >= 1;
+}
+
+// Largest vector width (elements) for a walk: vectors lie along the first digit and must not
+// straddle its end, in whole tiles and in the tiles the tensor's edge cuts.
+static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit)
+{
+    int v = std::min(limit, 16 / P.elem_bytes);
+    const DigitSpec& d = w.d[0];
+    const int64_t rest = P.size[d.outer_dim] % t[d.outer_dim];
+    while (v > 1 && (d.tile % v != 0 || (rest * d.inner) % v != 0)) v /= 2;
+    return std::max(v, 1);
+}
+
+// Lane mapping: which sub-box of the tile one wavefront instruction covers.
+static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int* n_iter_out, int* lanes_out)
+{
+    int best_lane[kBoxDims] = {1, 1, 1, 1};
     int64_t best_cost = INT64_MAX;
-    for (int k = 0; k < kMaxDim; ++k) best.lane[k] = 1;
-    const int first = order[0];
-    const int t0 = t[first];
-    // candidate extents along the vector index: divisors of t0 that are multiples of vec, and
-    // the largest extent 64 lanes can cover
+    int best_iter = 1, best_lanes = 1;
+    const int t0 = w->d[0].tile;
     std::vector<int> opts;
     const int cap = std::min(t0, kWave * vec);
     for (int l = vec; l <= cap; l += vec)
         if (t0 % l == 0 || l == cap) opts.push_back(l);
-    if (opts.empty()) opts.push_back(std::max(vec, std::min(t0, vec)));
+    if (opts.empty()) opts.push_back(vec);
     for (int l0 : opts) {
-        LaneChoice c;
-        for (int k = 0; k < kMaxDim; ++k) c.lane[k] = 1;
-        c.lane[first] = l0;
+        int lane[kBoxDims] = {1, 1, 1, 1};
+        lane[0] = l0;
         int lanes = l0 / vec;
-        int rem = kWave / lanes;
+        int rem = kWave / std::max(lanes, 1);
         int64_t iters = ceil_div(t0, l0);
-        for (int i = 1; i < P.ndim; ++i) {
-            const int k = order[i];
-            if (t[k] <= 1) continue;
+        for (int i = 1; i < w->nd; ++i) {
+            const int ti = w->d[i].tile;
             int l = 1;
             if (rem > 1) {
-                l = std::min(rem, t[k]);
-                l = (int)ceil_div(t[k], ceil_div(t[k], l));      // same count, less ragged
+                l = std::min(rem, ti);
+                l = (int)ceil_div(ti, ceil_div(ti, l));      // same count, less ragged
                 rem /= l;
                 lanes *= l;
             }
-            c.lane[k] = l;
-            iters *= ceil_div(t[k], l);
+            lane[i] = l;
+            iters *= ceil_div(ti, l);
         }
-        c.n_iter = (int)std::min<int64_t>(iters, INT32_MAX);
-        c.lanes = lanes;
-        // short segments along the stride-1 index cost coalescing: require 64 B unless the tile is shorter
-        const bool short_seg = (l0 < t0) && (l0 * P.elem_bytes < 64);
-        const int64_t cost = (int64_t)c.n_iter * (short_seg ? 2 : 1);
-        if (cost < best_cost || (cost == best_cost && l0 > best.lane[first])) { best = c; best_cost = cost; }
+        // short segments along the stride-1 index cost coalescing: ask for a 128-byte line unless the tile is shorter
+        const bool short_seg = (l0 < t0) && (l0 * P.elem_bytes < 128);
+        const int64_t cost = iters * (short_seg ? 2 : 1);
+        if (cost < best_cost || (cost == best_cost && l0 > best_lane[0])) {
+            best_cost = cost;
+            for (int i = 0; i < kBoxDims; ++i) best_lane[i] = lane[i];
+            best_iter = (int)std::min<int64_t>(iters, INT32_MAX);
+            best_lanes = lanes;
+        }
     }
-    return best;
+    for (int i = 0; i < w->nd; ++i) w->d[i].lane = best_lane[i];
+    *n_iter_out = best_iter;
+    *lanes_out = best_lanes;
 }
 
-// Lay one walk out digit by digit (only the indices the box spans, in the walk's order).
-// Returns false if the box spans more indices than a walk supports.
-static bool fill_side(const Problem& P, const KernelParams& kp, const int* order, const int* t, int vec,
-                      const LaneChoice& lc, const int* lds_stride, bool follows_b, Side* s)
+// Lay one walk out for the kernel: digits go to the slot of their outermost index.
+static bool fill_side(const Problem& P, const WalkSpec& w, int vec, const int* slot_of_dim,
+                      const int* lds_stride, bool follows_b, Side* s)
 {
     std::memset(s, 0, sizeof(*s));
     s->vec = vec;
-    const int vdim = order[0];
+    s->exact = 1;
+    for (int j = 0; j < kBoxDims; ++j) {
+        Digit& d = s->d[j];
+        d.tile = 1; d.lane = 1; d.iters = 1; d.lane_mul = 1; d.slot_mul = 1;
+        d.lane_below = d.lane_cnt = d.iter_below = d.iter_cnt = make_fastdiv(1);
+    }
     uint32_t lane_below = 1, iter_below = 1;
     int64_t n_iter = 1;
-    int nd = 0;
-    s->exact = 1;
-    for (int i = 0; i < kBoxDims; ++i) {
-        Digit& d = s->d[i];
-        d.tile = 1; d.lane = 1; d.iters = 1; d.lane_mul = 1; d.size = 1;
-        d.lane_below = d.lane_cnt = d.iter_below = d.iter_cnt = d.tile_below = d.tile_cnt = make_fastdiv(1);
-    }
-    for (int i = 0; i < P.ndim; ++i) {
-        const int k = order[i];
-        if (t[k] <= 1) continue;
-        if (nd == kBoxDims || t[k] >= 65536) return false;
-        Digit& d = s->d[nd++];
-        const int mul = (k == vdim) ? vec : 1;
-        const int cnt = lc.lane[k] / mul;
-        const int its = (int)ceil_div(t[k], lc.lane[k]);
-        d.tile = t[k];
-        d.lane = lc.lane[k];
+    for (int i = 0; i < w.nd; ++i) {
+        const DigitSpec& ds = w.d[i];
+        const int j = slot_of_dim[ds.outer_dim];
+        if (j < 0 || j >= kBoxDims) return false;
+        Digit& d = s->d[j];
+        const int mul = (i == 0) ? vec : 1;
+        if (ds.lane % mul != 0) return false;
+        const int cnt = ds.lane / mul;
+        const int its = (int)ceil_div(ds.tile, ds.lane);
+        d.tile = ds.tile;
+        d.lane = ds.lane;
         d.iters = its;
         d.lane_mul = mul;
+        d.slot_mul = ds.inner;
         d.lane_below = make_fastdiv(lane_below);
         d.lane_cnt = make_fastdiv((uint32_t)cnt);
         d.iter_below = make_fastdiv(iter_below);
         d.iter_cnt = make_fastdiv((uint32_t)its);
-        d.tile_below = kp.tile_below[k];
-        d.tile_cnt = kp.tile_cnt[k];
-        d.size = P.size[k];
-        d.gstride = follows_b ? P.stride_b[k] : P.stride_a[k];
-        d.g2stride = P.stride_b[k];
-        d.lstride = lds_stride ? lds_stride[k] : 0;
-        if (t[k] % lc.lane[k] != 0) s->exact = 0;
+        d.gstride = follows_b ? P.stride_b[ds.first_dim] : P.stride_a[ds.first_dim];
+        d.g2stride = P.stride_b[ds.first_dim];
+        d.lstride = lds_stride ? lds_stride[ds.first_dim] : 0;
+        if (ds.tile % ds.lane != 0) s->exact = 0;
         lane_below *= (uint32_t)cnt;
         iter_below *= (uint32_t)its;
         n_iter *= its;
-        if (n_iter > kMaxIters) return false;
+        if (n_iter > kMaxIters || lane_below > (uint32_t)kWave) return false;
     }
-    s->nd = nd;
     s->lanes = (int)lane_below;
     s->n_iter = (int)n_iter;
-    s->vec_lds_stride = lds_stride ? lds_stride[vdim] : 0;
+    s->vec_lds_stride = lds_stride ? lds_stride[w.d[0].first_dim] : 0;
     return true;
 }
 
 // ---------------------------------------------------------------------------------
-// LDS layout: A order with small pads on the strides, chosen by simulating which banks the
-// 64 lanes of one instruction touch.
+// LDS layout.  Indices that a walk merged into one flat digit must be affine in LDS as well:
+// stride(next) = extent(cur) * stride(cur).  These links form chains; the chain holding A's
+// stride-1 index comes first, the others follow, each chain head on a small pad chosen by
+// simulating which banks the 64 lanes of one LDS instruction touch.
 // ---------------------------------------------------------------------------------
 static int bank_multiplicity(const Problem& P, const Side& s, int banks)
 {
@@ -285,7 +333,7 @@ static int bank_multiplicity(const Problem& P, const Side& s, int banks)
         int n = 0;
         for (int lane = 0; lane < s.lanes; ++lane) {
             int64_t a = (int64_t)j * s.vec_lds_stride;
-            for (int i = 0; i < s.nd; ++i) {
+            for (int i = 0; i < kBoxDims; ++i) {
                 const Digit& d = s.d[i];
                 const uint32_t c = (lane / d.lane_below.div) % d.lane_cnt.div;
                 a += (int64_t)c * d.lane_mul * d.lstride;
@@ -308,35 +356,35 @@ static int bank_multiplicity(const Problem& P, const Side& s, int banks)
 
 struct LdsLayout { int stride[kMaxDim]; int elems; int conflict_a, conflict_b; };
 
-static LdsLayout choose_lds_layout(const Problem& P, const KernelParams& kp, const int* t, const int* order_b,
-                                   int va, int vb, const LaneChoice& la, const LaneChoice& lb)
+static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* slot_of_dim,
+                                   const WalkSpec& wa, const WalkSpec& wb, int va, int vb,
+                                   const int* next_in_chain /* by dim, -1 = chain end */,
+                                   const bool* is_head /* by dim */)
 {
-    int order_a[kMaxDim];
-    for (int k = 0; k < kMaxDim; ++k) order_a[k] = k;
-    int box_dims[kMaxDim], nb = 0;
-    for (int k = 0; k < P.ndim; ++k) if (t[k] > 1) box_dims[nb++] = k;
-    const int npad = std::max(0, std::min(nb - 1, 3));          // strides of the 2nd..4th box index get a pad
+    // chain heads in layout order: the chain of index 0 first, then by index
+    int heads[kMaxDim], nh = 0;
+    for (int k = 0; k < P.ndim; ++k) if (t[k] > 1 && is_head[k]) heads[nh++] = k;
+    const int npad = std::max(0, std::min(nh - 1, 3));
     LdsLayout best;
     best.elems = 0; best.conflict_a = best.conflict_b = 1 << 20;
     int64_t best_cost = INT64_MAX;
-    const int combos = 1 << (2 * npad);                          // pad in 0..3 each
+    const int combos = 1 << (2 * npad);
     for (int c = 0; c < combos; ++c) {
         LdsLayout L;
         for (int k = 0; k < kMaxDim; ++k) L.stride[k] = 0;
         int64_t run = 1;
-        for (int i = 0; i < nb; ++i) {
-            const int k = box_dims[i];
-            if (i >= 1 && i - 1 < npad) run += (c >> (2 * (i - 1))) & 3;
-            L.stride[k] = (int)run;
-            run *= t[k];
+        for (int h = 0; h < nh; ++h) {
+            if (h >= 1 && h - 1 < npad) run += (c >> (2 * (h - 1))) & 3;
+            for (int k = heads[h]; k >= 0; k = next_in_chain[k]) {
+                L.stride[k] = (int)run;
+                run *= t[k];
+            }
         }
-        if (nb == 0) run = 1;
         L.elems = (int)run;
         if (2 * (int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
         Side sa, sb;
-        if (!fill_side(P, kp, order_a, t, va, la, L.stride, false, &sa)) continue;
-        if (!fill_side(P, kp, order_b, t, vb, lb, L.stride, true, &sb)) continue;
-        sa.vec_lds_stride = 1;
+        if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &sa)) continue;
+        if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &sb)) continue;
         L.conflict_a = bank_multiplicity(P, sa, 32) + bank_multiplicity(P, sa, 64);
         L.conflict_b = bank_multiplicity(P, sb, 32) + bank_multiplicity(P, sb, 64);
         const int64_t cost = ((int64_t)(L.conflict_a + L.conflict_b) << 24) + L.elems;
@@ -349,14 +397,7 @@ static LdsLayout choose_lds_layout(const Problem& P, const KernelParams& kp, con
 // ---------------------------------------------------------------------------------
 // Candidate assembly
 // ---------------------------------------------------------------------------------
-static int max_vec(const Problem& P, int64_t extent)
-{
-    int v = 16 / P.elem_bytes;
-    while (v > 1 && extent % v != 0) v /= 2;
-    return v;
-}
-
-static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bool direct, int threads,
+static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, bool direct, int threads,
                            int wg_per_cu, const int* tile_order, int xcd_remap, Candidate* out)
 {
     Candidate C;
@@ -393,23 +434,87 @@ static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bo
     kp.alpha[0] = P.alpha[0]; kp.alpha[1] = P.alpha[1];
     kp.beta[0] = P.beta[0];   kp.beta[1] = P.beta[1];
 
-    const LaneChoice la = choose_lanes(P, order_a, t, va);
-    for (int k = 0; k < kMaxDim; ++k) { C.tile[k] = t[k]; C.lane_a[k] = la.lane[k]; C.lane_b[k] = la.lane[k]; C.lds_stride[k] = 0; }
+    // slots: the indices the box spans, in A order
+    int slot_of_dim[kMaxDim];
+    int nslots = 0;
+    for (int k = 0; k < kMaxDim; ++k) {
+        slot_of_dim[k] = -1;
+        if (k < P.ndim && t[k] > 1) {
+            if (nslots == kBoxDims) return false;
+            Slot& sl = kp.slot[nslots];
+            sl.tile = t[k];
+            sl.size = P.size[k];
+            sl.tile_below = kp.tile_below[k];
+            sl.tile_cnt = kp.tile_cnt[k];
+            slot_of_dim[k] = nslots++;
+        }
+    }
+    for (int j = nslots; j < kBoxDims; ++j) {
+        kp.slot[j].tile = 1; kp.slot[j].size = 1;
+        kp.slot[j].tile_below = kp.slot[j].tile_cnt = make_fastdiv(1);
+    }
+    kp.nslots = nslots;
+    if (nslots == 0) {                      // a one-element tensor: give the walks one trivial digit
+        kp.nslots = 1;
+        slot_of_dim[0] = 0;
+    }
+
+    for (int k = 0; k < kMaxDim; ++k) { C.tile[k] = t[k]; C.lds_stride[k] = 0; }
+    WalkSpec wa, wb;
+    auto trivial_walk = [&](WalkSpec* w) {
+        w->nd = 1;
+        w->d[0].first_dim = w->d[0].outer_dim = 0;
+        w->d[0].tile = 1; w->d[0].inner = 1; w->d[0].lane = 1;
+    };
     if (direct) {
-        if (!fill_side(P, kp, order_a, t, va, la, nullptr, false, &kp.a)) return false;
+        if (nslots == 0) trivial_walk(&wa);
+        else if (!build_walk(P, order_a, t, false, 0u, &wa)) return false;
+        const int v = (nslots == 0) ? 1 : walk_vec(P, wa, t, vec_limit);
+        int n_iter, lanes;
+        choose_lanes(P, &wa, v, &n_iter, &lanes);
+        if (!fill_side(P, wa, v, slot_of_dim, nullptr, false, &kp.a)) return false;
         kp.b = kp.a;
+        wb = wa;
         C.kernel_class = TTC_KERNEL_DIRECT;
         C.lds_bytes = (int)round_up(24 * (int64_t)kp.a.n_iter, 16);
         kp.lds_data_off = C.lds_bytes;
         kp.lds_tile_elems = 0;
         C.lds_conflict_a = C.lds_conflict_b = 0;
     } else {
-        const LaneChoice lb = choose_lanes(P, order_b, t, vb);
-        const LdsLayout L = choose_lds_layout(P, kp, t, order_b, va, vb, la, lb);
+        if (nslots == 0) return false;
+        if (!build_walk(P, order_a, t, true, 0u, &wa)) return false;
+        // LDS chains from A's merged digit; B may chain its own leading indices only where that
+        // does not give an index a second predecessor or a second successor
+        int next_in_chain[kMaxDim];
+        bool is_head[kMaxDim];
+        unsigned in_a_chain = 0, a_nonlast = 0;
+        for (int k = 0; k < kMaxDim; ++k) { next_in_chain[k] = -1; is_head[k] = true; }
+        if (wa.d[0].first_dim != wa.d[0].outer_dim)
+            for (int k = wa.d[0].first_dim; k <= wa.d[0].outer_dim; ++k) {      // A's chain is consecutive indices
+                in_a_chain |= 1u << k;
+                if (k < wa.d[0].outer_dim) { next_in_chain[k] = k + 1; is_head[k + 1] = false; a_nonlast |= 1u << k; }
+            }
+        const bool b_may_merge = !(a_nonlast & (1u << order_b[0]));
+        if (!build_walk(P, order_b, t, b_may_merge, in_a_chain, &wb)) return false;
+        if (wb.d[0].first_dim != wb.d[0].outer_dim) {
+            int prev = -1;
+            for (int i = 0; i < P.ndim; ++i) {
+                const int k = order_b[i];
+                if (prev >= 0) { next_in_chain[prev] = k; is_head[k] = false; }
+                prev = k;
+                if (k == wb.d[0].outer_dim) break;
+            }
+        }
+        const int va = walk_vec(P, wa, t, vec_limit);
+        const int vb = walk_vec(P, wb, t, vec_limit);
+        int ia, la_, ib, lb_;
+        choose_lanes(P, &wa, va, &ia, &la_);
+        choose_lanes(P, &wb, vb, &ib, &lb_);
+        const LdsLayout L = choose_lds_layout(P, t, slot_of_dim, wa, wb, va, vb, next_in_chain, is_head);
         if (L.elems == 0) return false;
-        for (int k = 0; k < kMaxDim; ++k) { C.lds_stride[k] = L.stride[k]; C.lane_b[k] = lb.lane[k]; }
-        if (!fill_side(P, kp, order_a, t, va, la, L.stride, false, &kp.a)) return false;
-        if (!fill_side(P, kp, order_b, t, vb, lb, L.stride, true, &kp.b)) return false;
+        for (int k = 0; k < kMaxDim; ++k) C.lds_stride[k] = L.stride[k];
+        if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &kp.a)) return false;
+        if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &kp.b)) return false;
         C.kernel_class = TTC_KERNEL_LDS;
         kp.lds_data_off = (int)round_up(24 * (int64_t)(kp.a.n_iter + kp.b.n_iter), 16);
         kp.lds_tile_elems = (int)round_up(L.elems, 16 / P.elem_bytes);
@@ -417,6 +522,12 @@ static bool make_candidate(const Problem& P, const int* t_in, int va, int vb, bo
         if (C.lds_bytes > kMaxLdsBytes) return false;
         C.lds_conflict_a = L.conflict_a;
         C.lds_conflict_b = L.conflict_b;
+    }
+    C.digits_a = wa.nd;
+    C.digits_b = wb.nd;
+    for (int i = 0; i < kBoxDims; ++i) {
+        C.dtile_a[i] = i < wa.nd ? wa.d[i].tile : 0;  C.dlane_a[i] = i < wa.nd ? wa.d[i].lane : 0;
+        C.dtile_b[i] = i < wb.nd ? wb.d[i].tile : 0;  C.dlane_b[i] = i < wb.nd ? wb.d[i].lane : 0;
     }
     C.threads = threads;
     C.wg_per_cu = wg_per_cu;
@@ -492,8 +603,10 @@ static bool same_config(const Candidate& x, const Candidate& y)
     for (int k = 0; k < kMaxDim; ++k) {
         if (x.tile[k] != y.tile[k]) return false;
         if (x.kp.tile_below[k].div != y.kp.tile_below[k].div) return false;
-        if (x.lane_a[k] != y.lane_a[k] || x.lane_b[k] != y.lane_b[k]) return false;
     }
+    for (int i = 0; i < kBoxDims; ++i)
+        if (x.dlane_a[i] != y.dlane_a[i] || x.dlane_b[i] != y.dlane_b[i] || x.dtile_a[i] != y.dtile_a[i] ||
+            x.dtile_b[i] != y.dtile_b[i]) return false;
     return true;
 }
 
@@ -502,6 +615,13 @@ static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Can
     for (const Candidate& o : v) if (same_config(o, c)) return;
     v.push_back(c);
     v.back().score = heuristic_cost(P, c);
+}
+
+static int max_vec(const Problem& P, int64_t extent)
+{
+    int v = 16 / P.elem_bytes;
+    while (v > 1 && extent % v != 0) v /= 2;
+    return v;
 }
 
 // Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
@@ -520,7 +640,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     // -- direct candidates: only when the stride-1 index keeps its place
     if (stride1_fixed) {
         const int vfull = max_vec(P, P.size[0]);
-        for (int v = vfull; v >= 1; v /= 2) {
+        for (int v = vfull; v >= 1; v = (v > 1 && vfull > 1) ? 1 : 0) {
             const int64_t tile_bytes_opts[4] = {16384, 32768, 8192, 65536};
             for (int64_t tb : tile_bytes_opts) {
                 int t[kMaxDim];
@@ -528,7 +648,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                 for (int o = 0; o < 2; ++o)
                     for (const LaunchShape& ls : kLaunchShapes) {
                         Candidate c;
-                        if (make_candidate(P, t, v, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                        if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
                             add_candidate(P, out, c);
                     }
             }
@@ -542,9 +662,9 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
         const int vb_full = max_vec(P, P.size[p0]);
         const int64_t run_bytes[8] = {256, 512, 128, 1024, 64, 2048, 4096, 8192};
         for (int vsel = 0; vsel < 2; ++vsel) {
-            const int va = vsel == 0 ? va_full : 1;
+            const int va = vsel == 0 ? va_full : 1;       // multiples the group builder keeps on the stride-1 extents
             const int vb = vsel == 0 ? vb_full : 1;
-            if (vsel == 1 && va_full == 1 && vb_full == 1) break;
+            const int vec_limit = vsel == 0 ? 16 : 1;
             for (int md = 3; md >= 1; --md)
                 for (int64_t ra : run_bytes)
                     for (int64_t rb : run_bytes) {
@@ -554,8 +674,6 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         int64_t vol = 1;
                         int spanned = 0;
                         for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
-                        t[0] = (int)std::min<int64_t>(round_up(t[0], va), P.size[0]);
-                        t[p0] = (int)std::min<int64_t>(round_up(t[p0], (p0 == 0) ? std::max(va, vb) : vb), P.size[p0]);
                         for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
                         if (spanned > kBoxDims) continue;
                         if (2 * vol * eb > kMaxLdsBytes - 1024) continue;
@@ -563,7 +681,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         for (int o = 0; o < 2; ++o)
                             for (const LaunchShape& ls : kLaunchShapes) {
                                 Candidate c;
-                                if (make_candidate(P, t, va, vb, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                                if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
                                     add_candidate(P, out, c);
                             }
                     }
@@ -575,7 +693,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
         int t[kMaxDim];
         build_group(P, order_a, 16384 / eb, 1, kBoxDims, t);
         Candidate c;
-        if (make_candidate(P, t, 1, 1, true, 256, 8, order_a, 1, &c)) add_candidate(P, out, c);
+        if (make_candidate(P, t, 1, true, 256, 8, order_a, 1, &c)) add_candidate(P, out, c);
     }
 }
 
@@ -598,7 +716,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
         // every candidate is vectorised: add the scalar variant of the best one
         const Candidate& b = plan->cands[0];
         Candidate c;
-        if (!make_candidate(P, b.tile, 1, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c))
+        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c))
             return TTC_ERR_OVERFLOW;
         c.score = heuristic_cost(P, c);
         plan->cands.push_back(c);
@@ -670,10 +788,14 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
         out->sizes[k] = P.size[k];
         out->perm[k] = P.perm[k];
         out->tile[k] = C.tile[k];
-        out->lane_a[k] = C.lane_a[k];
-        out->lane_b[k] = C.lane_b[k];
         out->tile_order[k] = C.tile_order[k];
         out->lds_stride[k] = C.lds_stride[k];
+    }
+    out->digits_a = C.digits_a;
+    out->digits_b = C.digits_b;
+    for (int i = 0; i < ttc::kBoxDims; ++i) {
+        out->digit_tile_a[i] = C.dtile_a[i];  out->digit_lane_a[i] = C.dlane_a[i];
+        out->digit_tile_b[i] = C.dtile_b[i];  out->digit_lane_b[i] = C.dlane_b[i];
     }
     out->stride1_fixed = (P.perm[0] == 0) ? 1 : 0;
     out->kernel_class = C.kernel_class;
@@ -754,7 +876,9 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             seen[tile] = 1;
             const TileBase tb = tile_base(p, tile);
             const int64_t base_a = tb.a * eb, base_b = tb.b * eb;
-            const TileLim la = tile_lim(p.a, tile);
+            const TileLim tl = tile_lim(p, tile);
+            const SideLim la = side_lim(p.a, tl);
+            const bool full_a = tl.whole && p.a.exact, full_b = tl.whole && p.b.exact;
             if (direct) {
                 for (uint32_t wave = 0; wave < nwave; ++wave)
                     for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
@@ -769,7 +893,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                                 b_from_a[ob / eb + j] = oa / eb + j;
                             }
                         };
-                        if (la.full) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                        if (full_a) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
                         else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
                     }
                 continue;
@@ -783,16 +907,18 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
                         const int64_t w = (int64_t)p.a.vec * eb;
                         if (oa % w || lo % eb) return fail();
-                        if (oa < 0 || oa + w > total_bytes || lo < 0 || lo + w > lds_bytes) return fail();
+                        if (oa < 0 || oa + w > total_bytes || lo < 0 || lo >= lds_bytes) return fail();
                         for (int j = 0; j < p.a.vec; ++j) {
-                            if (lds[lo / eb + j] != -1) return fail();
-                            lds[lo / eb + j] = oa / eb + j;
+                            const int64_t li = lo / eb + (int64_t)j * p.a.vec_lds_stride;
+                            if (li < 0 || li >= p.lds_tile_elems) return fail();
+                            if (lds[li] != -1) return fail();
+                            lds[li] = oa / eb + j;
                         }
                     };
-                    if (la.full) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                    if (full_a) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
                     else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
                 }
-            const TileLim lb = tile_lim(p.b, tile);
+            const SideLim lb = side_lim(p.b, tl);
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.b, lane, eb);
@@ -809,7 +935,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                             b_from_a[ob / eb + j] = lds[li];
                         }
                     };
-                    if (lb.full) walk<4, true>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
+                    if (full_b) walk<4, true>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
                     else walk<4, false>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
                 }
         }

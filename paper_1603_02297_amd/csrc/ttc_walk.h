@@ -67,26 +67,36 @@ TTC_HD TileBase tile_base(const KernelParams& p, uint32_t tile)
     return t;
 }
 
-// How much of the box lies inside the tensor, per digit of one walk.  full: nothing is cut
-// off and the sub-box tiles the box exactly, so the walk needs no per-lane bounds test.
-struct TileLim { int32_t lim[kBoxDims]; bool full; };
+// How much of the box lies inside the tensor along each slot.  whole: nothing is cut off.
+struct TileLim { int32_t lim[kBoxDims]; bool whole; };
 
-TTC_HD TileLim tile_lim(const Side& s, uint32_t tile)
+TTC_HD TileLim tile_lim(const KernelParams& p, uint32_t tile)
 {
     TileLim t;
-    t.full = (s.exact != 0);
+    t.whole = true;
 #pragma unroll
-    for (int i = 0; i < kBoxDims; ++i) {
-        t.lim[i] = 1;
-        if (i < s.nd) {
-            const Digit& d = s.d[i];
-            const int64_t origin = (int64_t)fdigit(tile, d.tile_below, d.tile_cnt) * d.tile;
-            const int64_t left = d.size - origin;
-            t.lim[i] = (int32_t)(left < (int64_t)d.tile ? left : (int64_t)d.tile);
-            t.full = t.full && (t.lim[i] == d.tile);
+    for (int j = 0; j < kBoxDims; ++j) {
+        t.lim[j] = 1;
+        if (j < p.nslots) {
+            const Slot& sl = p.slot[j];
+            const int64_t origin = (int64_t)fdigit(tile, sl.tile_below, sl.tile_cnt) * sl.tile;
+            const int64_t left = sl.size - origin;
+            t.lim[j] = (int32_t)(left < (int64_t)sl.tile ? left : (int64_t)sl.tile);
+            t.whole = t.whole && (t.lim[j] == sl.tile);
         }
     }
     return t;
+}
+
+// The same limits in the flat units of one walk's digits.
+struct SideLim { int32_t lim[kBoxDims]; };
+
+TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
+{
+    SideLim r;
+#pragma unroll
+    for (int j = 0; j < kBoxDims; ++j) r.lim[j] = t.lim[j] * s.d[j].slot_mul;
+    return r;
 }
 
 // ---- lane entry ------------------------------------------------------------------------------
@@ -95,7 +105,7 @@ struct LaneState {
     int64_t g;                 // byte offset into the tensor the walk follows
     int64_t g2;                // direct kernel: byte offset into B
     int32_t l;                 // byte offset into the LDS tile
-    int32_t c[kBoxDims];       // coordinate along each digit, in elements
+    int32_t c[kBoxDims];       // flat coordinate along each digit, in elements
     bool    active;
 };
 
@@ -106,12 +116,12 @@ TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, int32_t scale)
     L.g = 0; L.g2 = 0; L.l = 0;
     L.active = lane < (uint32_t)s.lanes;
 #pragma unroll
-    for (int i = 0; i < kBoxDims; ++i) {
-        L.c[i] = 0;
-        if (i < s.nd && s.d[i].lane > 1) {
-            const Digit& d = s.d[i];
+    for (int j = 0; j < kBoxDims; ++j) {
+        L.c[j] = 0;
+        if (s.d[j].lane > 1) {
+            const Digit& d = s.d[j];
             const int32_t c = (int32_t)fdigit(lane, d.lane_below, d.lane_cnt) * d.lane_mul;
-            L.c[i] = c;
+            L.c[j] = c;
             L.g += (int64_t)c * d.gstride;
             if (DIRECT) L.g2 += (int64_t)c * d.g2stride;
             else L.l += c * d.lstride;
@@ -138,7 +148,7 @@ TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e
 #pragma unroll
     for (int i = 0; i < kBoxDims; ++i) {
         pc[i] = 0;
-        if (i < s.nd && s.d[i].iters > 1) {
+        if (s.d[i].iters > 1) {
             const Digit& d = s.d[i];
             const uint32_t q = fdigit(it, d.iter_below, d.iter_cnt) * (uint32_t)d.lane;
             pc[i] = q;
@@ -153,16 +163,12 @@ TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e
 }
 
 // does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
-TTC_HD bool lane_valid(const Side& s, const LaneState& L, const int32_t* lim, const PosCoord& pc)
+TTC_HD bool lane_valid(const LaneState& L, const int32_t* lim, const PosCoord& pc)
 {
-    bool v = L.active;
     const int32_t p0 = (int32_t)(pc.c01 & 0xffffu), p1 = (int32_t)(pc.c01 >> 16);
     const int32_t p2 = (int32_t)(pc.c23 & 0xffffu), p3 = (int32_t)(pc.c23 >> 16);
-    v = v && (L.c[0] < lim[0] - p0);
-    if (s.nd > 1) v = v && (L.c[1] < lim[1] - p1);
-    if (s.nd > 2) v = v && (L.c[2] < lim[2] - p2);
-    if (s.nd > 3) v = v && (L.c[3] < lim[3] - p3);
-    return v;
+    return L.active && (L.c[0] < lim[0] - p0) && (L.c[1] < lim[1] - p1) &&
+           (L.c[2] < lim[2] - p2) && (L.c[3] < lim[3] - p3);
 }
 
 // Drive one wavefront through its share of a walk: wavefront `wave` of `nwave` takes the
@@ -183,7 +189,7 @@ TTC_HD void walk(const Side& s, const LaneState& L, const int32_t* lim, const Po
             ok[u] = false;
             if (it < n_it) {
                 e[u] = tab[it];
-                ok[u] = FULL ? L.active : lane_valid(s, L, lim, tabc[it]);
+                ok[u] = FULL ? L.active : lane_valid(L, lim, tabc[it]);
             }
         }
 #pragma unroll

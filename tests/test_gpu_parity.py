@@ -97,11 +97,13 @@ def test_all_perms_small_odd_extents(dtype, n):
     ((2, 3, 5, 7, 11, 13), (5, 4, 3, 2, 1, 0)),
 ])
 def test_every_candidate_every_epilogue(dtype, sizes, perm):
-    """Ragged shapes spanning several tiles; every candidate configuration of the plan."""
+    """Ragged shapes spanning several tiles; the plan's candidate configurations (all of them, or
+    48 spread evenly over the ranked list when there are more)."""
     p = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, None, None)
     ncand = ttc.ttc_plan_candidate_count(p)
     ttc.ttc_plan_destroy(p)
-    for k in range(ncand):
+    picks = range(ncand) if ncand <= 48 else sorted(set(np.linspace(0, ncand - 1, 48).astype(int).tolist()))
+    for k in picks:
         al, be = SCALARS[dtype][k % len(SCALARS[dtype])]
         check(dtype, sizes, perm, al, be, seed=k, candidate=k)
 
@@ -146,8 +148,9 @@ def test_rejects_alias_null_and_misaligned():
     ttc.ttc_plan_destroy(plan)
 
 
-def test_unaligned_pointers_take_the_scalar_fallback():
-    """Pointers aligned to the element but not to 16 bytes still give the exact result."""
+def test_pointers_aligned_to_the_element_only():
+    """Pointers aligned to the element but not to 16 bytes: the vector kernels still apply and
+    give the exact result, writing nothing outside B."""
     dev = torch.device("cuda:0")
     sizes, perm = (64, 48, 5), (1, 0, 2)
     n = int(np.prod(sizes))
