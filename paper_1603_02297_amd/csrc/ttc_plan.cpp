@@ -397,8 +397,21 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
 // ---------------------------------------------------------------------------------
 // Candidate assembly
 // ---------------------------------------------------------------------------------
+// The LDS layout depends on the box and the walks only, not on the launch shape or the tile
+// order: candidates that differ only in those share one layout search.
+struct LayoutKey {
+    int t[kMaxDim]; int vec_limit; bool merge_a, merge_b;
+    bool operator==(const LayoutKey& o) const
+    {
+        for (int k = 0; k < kMaxDim; ++k) if (t[k] != o.t[k]) return false;
+        return vec_limit == o.vec_limit && merge_a == o.merge_a && merge_b == o.merge_b;
+    }
+};
+struct LayoutCache { std::vector<std::pair<LayoutKey, LdsLayout>> items; };
+
 static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, bool direct, int threads,
-                           int wg_per_cu, const int* tile_order, int xcd_remap, Candidate* out)
+                           int wg_per_cu, const int* tile_order, int xcd_remap, Candidate* out,
+                           bool merge_a = true, bool merge_b = true, LayoutCache* cache = nullptr)
 {
     Candidate C;
     std::memset(&C, 0, sizeof(C));
@@ -482,7 +495,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         C.lds_conflict_a = C.lds_conflict_b = 0;
     } else {
         if (nslots == 0) return false;
-        if (!build_walk(P, order_a, t, true, 0u, &wa)) return false;
+        if (!build_walk(P, order_a, t, merge_a, 0u, &wa)) return false;
         // LDS chains from A's merged digit; B may chain its own leading indices only where that
         // does not give an index a second predecessor or a second successor
         int next_in_chain[kMaxDim];
@@ -494,7 +507,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
                 in_a_chain |= 1u << k;
                 if (k < wa.d[0].outer_dim) { next_in_chain[k] = k + 1; is_head[k + 1] = false; a_nonlast |= 1u << k; }
             }
-        const bool b_may_merge = !(a_nonlast & (1u << order_b[0]));
+        const bool b_may_merge = merge_b && !(a_nonlast & (1u << order_b[0]));
         if (!build_walk(P, order_b, t, b_may_merge, in_a_chain, &wb)) return false;
         if (wb.d[0].first_dim != wb.d[0].outer_dim) {
             int prev = -1;
@@ -510,7 +523,17 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         int ia, la_, ib, lb_;
         choose_lanes(P, &wa, va, &ia, &la_);
         choose_lanes(P, &wb, vb, &ib, &lb_);
-        const LdsLayout L = choose_lds_layout(P, t, slot_of_dim, wa, wb, va, vb, next_in_chain, is_head);
+        LdsLayout L;
+        bool cached = false;
+        LayoutKey key;
+        for (int k = 0; k < kMaxDim; ++k) key.t[k] = t[k];
+        key.vec_limit = vec_limit; key.merge_a = merge_a; key.merge_b = merge_b;
+        if (cache)
+            for (const auto& it : cache->items) if (it.first == key) { L = it.second; cached = true; break; }
+        if (!cached) {
+            L = choose_lds_layout(P, t, slot_of_dim, wa, wb, va, vb, next_in_chain, is_head);
+            if (cache) cache->items.emplace_back(key, L);
+        }
         if (L.elems == 0) return false;
         for (int k = 0; k < kMaxDim; ++k) C.lds_stride[k] = L.stride[k];
         if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &kp.a)) return false;
@@ -560,15 +583,17 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
     int order_a[kMaxDim], order_b[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < P.ndim) ? P.perm[k] : k; }
     const double eb = P.elem_bytes;
-    auto run_eff = [&](const int* order, int vec) {
+    const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
+    // coalescing: length of the contiguous runs the box spans in each tensor
+    auto run_cost = [&](const int* order, int vec) {
         const double run = (double)box_run(P, order, kp.tile) * eb;
-        // a run that is not a whole number of 128-byte lines shares its end lines with a neighbour
-        const bool aligned = std::fmod(run, 128.0) == 0.0;
-        double e = aligned ? 1.0 : run / (run + 48.0);
-        if (run < 256.0) e *= 0.5 + run / 512.0;
+        double c = 1.0;
+        if (std::fmod(run, 128.0) != 0.0) c *= 1.0 + 32.0 / run;      // ragged ends share cache lines with a neighbour
+        if (run < 512.0) c *= 1.0 + 0.25 * (512.0 - run) / 512.0;
+        if (run < 128.0) c *= 1.0 + (128.0 - run) / 128.0;
         const double vbytes = vec * eb;
-        e *= (vbytes >= 16 ? 1.0 : (vbytes >= 8 ? 0.95 : 0.85));
-        return e;
+        c *= (vbytes >= 16 ? 1.0 : (vbytes >= 8 ? 1.04 : 1.12));
+        return c;
     };
     double volume = 1, padded = 1;
     for (int k = 0; k < P.ndim; ++k) {
@@ -576,23 +601,33 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
         padded *= (double)ceil_div(P.size[k], kp.tile[k]) * kp.tile[k] / (double)P.size[k];
     }
     const double tile_bytes = volume * eb;
-    double cost = 0.5 / run_eff(order_a, kp.a.vec) + 0.5 / run_eff(order_b, C.kernel_class == TTC_KERNEL_DIRECT ? kp.a.vec : kp.b.vec);
-    cost *= padded;
-    cost *= 1.0 + 1536.0 / tile_bytes;                               // per-workgroup overhead
-    if (C.kernel_class == TTC_KERNEL_LDS) {
-        if (C.lds_bytes > 40 * 1024) cost *= 1.0 + (C.lds_bytes - 40 * 1024) / (96.0 * 1024);   // occupancy
-        const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
+    double cost = 0.5 * run_cost(order_a, kp.a.vec) + 0.5 * run_cost(order_b, direct ? kp.a.vec : kp.b.vec);
+    cost *= padded;                                                    // remainder tiles (paper Section 3.2, rule 2)
+    // tile size: measured optimum 8..16 KB for staged tiles, 16..64 KB for direct ones
+    const double lo = direct ? 16384.0 : 8192.0, hi = direct ? 65536.0 : 16384.0;
+    if (tile_bytes < lo) cost *= 1.0 + 0.45 * std::log2(lo / tile_bytes);
+    if (tile_bytes > hi) cost *= 1.0 + 0.06 * std::log2(tile_bytes / hi);
+    const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
+    if (!direct) {
+        // occupancy: workgroups of one CU share 160 KB of LDS
+        const double resident_waves = std::min(32.0, std::floor(160.0 * 1024 / C.lds_bytes) * (C.threads / kWave));
+        if (resident_waves < 16.0) cost *= 1.0 + 0.03 * (16.0 - resident_waves);
         const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
-        cost *= 1.0 + 0.15 * (lane_a - 1.0) + 0.15 * (lane_b - 1.0);
-        cost *= 1.0 + 0.02 * (C.lds_conflict_a + C.lds_conflict_b - 4);
-        cost *= 1.08;                                                 // staging costs a barrier and LDS traffic
+        cost *= 1.0 + 0.20 * (lane_a - 1.0) + 0.20 * (lane_b - 1.0);
+        cost *= 1.0 + 0.015 * (C.lds_conflict_a + C.lds_conflict_b - 4);
+        cost *= 1.06;                                                  // staging costs a barrier and LDS traffic
     } else {
-        const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
-        cost *= 1.0 + 0.15 * (lane_a - 1.0);
-        if (tile_bytes > 64 * 1024) cost *= 1.05;
+        cost *= 1.0 + 0.20 * (lane_a - 1.0);
     }
-    if (C.threads != 256 || C.wg_per_cu != 8) cost *= 1.03;
-    if (kp.num_tiles < 1024) cost *= 1.0 + 256.0 / (kp.num_tiles + 1.0) * 0.25;   // fewer tiles than the chip has slots
+    // launch shape: measured preference
+    if (C.threads == 256 && C.wg_per_cu == 16) cost *= 1.00;
+    else if (C.threads == 128 && C.wg_per_cu == 8) cost *= 1.01;
+    else if (C.threads == 256 && C.wg_per_cu == 8) cost *= 1.02;
+    else cost *= 1.04;
+    bool b_order = true;
+    for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
+    if (!b_order) cost *= 1.005;
+    if (kp.num_tiles < 2048) cost *= 1.0 + 0.25 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
     return cost;
 }
 
@@ -626,10 +661,11 @@ static int max_vec(const Problem& P, int64_t extent)
 
 // Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
 struct LaunchShape { int threads, wg_per_cu; };
-static const LaunchShape kLaunchShapes[] = {{256, 8}, {128, 16}, {128, 8}, {256, 4}, {512, 4}, {256, 16}};
+static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}};
 
 static void enumerate(const Problem& P, std::vector<Candidate>& out)
 {
+    LayoutCache cache;
     const int n = P.ndim;
     const int eb = P.elem_bytes;
     int order_a[kMaxDim], order_b[kMaxDim];
@@ -637,21 +673,32 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     const bool stride1_fixed = (P.perm[0] == 0);
     const int* orders[2] = {order_b, order_a};
 
-    // -- direct candidates: only when the stride-1 index keeps its place
+    // -- direct candidates: only when the stride-1 index keeps its place.  The box takes leading
+    //    indices of A and of B so that both sides move a few long contiguous chunks per tile.
     if (stride1_fixed) {
         const int vfull = max_vec(P, P.size[0]);
-        for (int v = vfull; v >= 1; v = (v > 1 && vfull > 1) ? 1 : 0) {
-            const int64_t tile_bytes_opts[4] = {16384, 32768, 8192, 65536};
-            for (int64_t tb : tile_bytes_opts) {
-                int t[kMaxDim];
-                build_group(P, order_a, tb / eb, v, kBoxDims, t);
-                for (int o = 0; o < 2; ++o)
-                    for (const LaunchShape& ls : kLaunchShapes) {
-                        Candidate c;
-                        if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
-                            add_candidate(P, out, c);
-                    }
-            }
+        const int64_t chunk_bytes[6] = {16384, 4096, 32768, 8192, 2048, 65536};
+        for (int vsel = 0; vsel < 2; ++vsel) {
+            if (vsel == 1 && vfull == 1) break;
+            const int v = vsel == 0 ? vfull : 1;
+            for (int64_t ra : chunk_bytes)
+                for (int64_t rb : chunk_bytes) {
+                    int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
+                    build_group(P, order_a, ra / eb, v, kBoxDims, ta);
+                    build_group(P, order_b, rb / eb, v, kBoxDims, tb);
+                    int64_t vol = 1;
+                    int spanned = 0;
+                    for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
+                    for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
+                    if (spanned > kBoxDims || vol * eb > 128 * 1024) continue;
+                    if (vol * eb < 4096 && vol < P.elements) continue;
+                    for (int o = 0; o < 2; ++o)
+                        for (const LaunchShape& ls : kLaunchShapes) {
+                            Candidate c;
+                            if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                                add_candidate(P, out, c);
+                        }
+                }
         }
     }
 
@@ -678,12 +725,14 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         if (spanned > kBoxDims) continue;
                         if (2 * vol * eb > kMaxLdsBytes - 1024) continue;
                         if (vol * eb < 2048 && md > 1 && vol < P.elements) continue;
-                        for (int o = 0; o < 2; ++o)
-                            for (const LaunchShape& ls : kLaunchShapes) {
-                                Candidate c;
-                                if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
-                                    add_candidate(P, out, c);
-                            }
+                        for (int mg = 0; mg < 4; ++mg)
+                            for (int o = 0; o < 2; ++o)
+                                for (const LaunchShape& ls : kLaunchShapes) {
+                                    Candidate c;
+                                    if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c,
+                                                       (mg & 1) == 0, (mg & 2) == 0, &cache))
+                                        add_candidate(P, out, c);
+                                }
                     }
         }
     }
