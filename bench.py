@@ -43,29 +43,56 @@ def parse():
 
 
 def cpu_baseline(cases, budget_s: float = 25.0):
-    """The oracle as it stands, timed on the host cores, on a bounded sample of the suite."""
+    """The oracle as it stands, timed on the host cores: every case of the suite once on one
+    thread (while the budget lasts) and three times on all available threads (best kept)."""
     import oracle
     from paper_1603_02297_amd import workloads as wl
     cores = len(os.sched_getaffinity(0))
-    threads = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
-    rates, names, spent = [], [], 0.0
-    # one case per workload, the first permutation of each, until the budget is used
-    seen = set()
+    threads = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+    multi, single, spent = {}, {}, 0.0
+    cache = {}
     for c in cases:
-        if c.config in seen or spent > budget_s:
-            continue
-        seen.add(c.config)
-        A, B = wl.case_inputs(c)
-        t0 = time.perf_counter()
-        oracle.transpose(c.dtype, c.sizes, c.perm, c.alpha, c.beta, A, B, threads)
-        dt = time.perf_counter() - t0
-        spent += dt
-        rates.append(c.traffic_bytes / dt / 1e9)
-        names.append(c.name)
-        log(f"[cpu] {c.name}: {rates[-1]:.2f} GB/s on {threads} threads ({dt:.2f} s)")
-    return {"value": statistics.median(rates), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "one run of the first permutation of each workload: " + ", ".join(names),
-            "per_case": dict(zip(names, [round(r, 3) for r in rates]))}
+        if spent > budget_s:
+            break
+        if c.config not in cache:
+            cache = {c.config: wl.case_inputs(c)}
+        A, B0 = cache[c.config]
+        best = None
+        for _ in range(3):
+            B = B0.copy()
+            t0 = time.perf_counter()
+            oracle.transpose(c.dtype, c.sizes, c.perm, c.alpha, c.beta, A, B, threads)
+            dt = time.perf_counter() - t0
+            spent += dt
+            best = dt if best is None else min(best, dt)
+        multi[c.name] = c.traffic_bytes / best / 1e9
+        if spent < budget_s * 0.6:
+            B = B0.copy()
+            t0 = time.perf_counter()
+            oracle.transpose(c.dtype, c.sizes, c.perm, c.alpha, c.beta, A, B, 1)
+            dt = time.perf_counter() - t0
+            spent += dt
+            single[c.name] = c.traffic_bytes / dt / 1e9
+        log(f"[cpu] {c.name}: {multi[c.name]:.2f} GB/s on {threads} threads"
+            + (f", {single[c.name]:.2f} GB/s on 1" if c.name in single else ""))
+    return {"value": round(statistics.median(multi.values()), 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(multi)} of {len(cases)} suite cases at full size, best of 3 runs each on {threads} threads "
+                      f"(median over cases); {len(single)} of them also once on 1 thread; {spent:.0f} s of CPU wall time",
+            "single_thread_median": round(statistics.median(single.values()), 3) if single else None,
+            "per_case": {k: round(v, 3) for k, v in multi.items()}}
+
+
+def measured_traffic(case_name: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 2 and parts[0] == case_name:
+                return int(float(parts[1]))
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -89,6 +116,12 @@ def main() -> int:
     sel = [s for s in args.cases.split(",") if s]
     cases = [c for c in wl.CASES if not sel or any(s in c.name for s in sel)]
     K, W = args.steps, args.warmup
+
+    # bring the clocks up before anything is timed
+    warm = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+    warm2 = torch.empty_like(warm)
+    ttc.ttc_time_ceiling(0, warm.numel() * 4, [warm.data_ptr()], [warm2.data_ptr()], stream, 5, 100)
+    del warm, warm2
 
     results = []
     ceil_cache = {}
@@ -154,7 +187,7 @@ def main() -> int:
     # roofline: the staged kernel on the quoted workload (3-D fp32 384^3, full index reversal)
     dom = next((r for r in results if r["case"].startswith("cfg2-f32-p210")), results[0])
     roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom["case"]),
                 "kernel": "box_kernel (" + dom["kernel_class"] + ")", "case": dom["case"],
                 "algorithmic_bytes_per_launch": dom["traffic_bytes"], "avg_launch_ms": dom["ms"]}
     out = {

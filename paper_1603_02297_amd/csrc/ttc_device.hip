@@ -103,7 +103,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
 {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int32_t kScale = (int32_t)sizeof(T);
-    const uint32_t n_a = (uint32_t)p.a.n_iter, n_b = DIRECT ? 0u : (uint32_t)p.b.n_iter;
+    const uint32_t nwave = blockDim.x >> 6;
+    const uint32_t n_a = nwave * (uint32_t)p.a.chunk, n_b = DIRECT ? 0u : nwave * (uint32_t)p.b.chunk;
     PosEntry* tab_a = reinterpret_cast<PosEntry*>(smem);
     PosEntry* tab_b = tab_a + n_a;
     PosCoord* tabc_a = reinterpret_cast<PosCoord*>(tab_b + n_b);
@@ -111,13 +112,9 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t nwave = blockDim.x >> 6;
 
-    for (uint32_t it = threadIdx.x; it < n_a; it += blockDim.x)
-        make_position<DIRECT>(p.a, it, kScale, &tab_a[it], &tabc_a[it]);
-    if (!DIRECT)
-        for (uint32_t it = threadIdx.x; it < n_b; it += blockDim.x)
-            make_position<false>(p.b, it, kScale, &tab_b[it], &tabc_b[it]);
+    build_tables<DIRECT>(p.a, nwave, threadIdx.x, blockDim.x, kScale, tab_a, tabc_a);
+    if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, kScale, tab_b, tabc_b);
     const LaneState LA = lane_setup<DIRECT>(p.a, lane, kScale);
     const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, kScale);
     __syncthreads();
@@ -145,8 +142,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
                 *reinterpret_cast<Pack<T, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
             };
-            if (full_a) walk<kUnroll, true>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, store);
-            else walk<kUnroll, false>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, store);
+            if (full_a) walk<kUnroll, true>(p.a, LA, sla, tab_a, tabc_a, wave, load, store);
+            else walk<kUnroll, false>(p.a, LA, sla, tab_a, tabc_a, wave, load, store);
             continue;
         }
 
@@ -162,8 +159,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
 #pragma unroll
                 for (int j = 0; j < VA; ++j) dst[j * vs] = ra[u].v[j];
             };
-            if (full_a) walk<kUnroll, true>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, park);
-            else walk<kUnroll, false>(p.a, LA, sla.lim, tab_a, tabc_a, wave, nwave, load, park);
+            if (full_a) walk<kUnroll, true>(p.a, LA, sla, tab_a, tabc_a, wave, load, park);
+            else walk<kUnroll, false>(p.a, LA, sla, tab_a, tabc_a, wave, load, park);
         }
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
@@ -184,8 +181,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VB; ++j) out.v[j] = epi(rl[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : rl[u].v[j]);
                 *reinterpret_cast<Pack<T, VB>*>(Bt + (e.g + LB.g)) = out;
             };
-            if (full_b) walk<kUnroll, true>(p.b, LB, slb.lim, tab_b, tabc_b, wave, nwave, load, store);
-            else walk<kUnroll, false>(p.b, LB, slb.lim, tab_b, tabc_b, wave, nwave, load, store);
+            if (full_b) walk<kUnroll, true>(p.b, LB, slb, tab_b, tabc_b, wave, load, store);
+            else walk<kUnroll, false>(p.b, LB, slb, tab_b, tabc_b, wave, load, store);
         }
     }
 }

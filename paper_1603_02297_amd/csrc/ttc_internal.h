@@ -54,7 +54,10 @@ struct Side {
     int32_t  n_iter;                 // sub-box positions per tile = prod(iters)
     int32_t  vec_lds_stride;         // LDS element stride between the vec elements of one lane
     int32_t  exact;                  // 1: lane divides tile on every digit (no ragged sub-boxes)
+    int32_t  chunk;                  // positions per wavefront, rounded up: ceil(n_iter / waves)
+    int32_t  chunk_rem;              // wavefronts that really have `chunk` positions (the others have one less)
     int32_t  pad;
+    FastDiv  chunk_div;
     Digit    d[kBoxDims];
 };
 

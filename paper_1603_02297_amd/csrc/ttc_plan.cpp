@@ -554,6 +554,19 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     }
     C.threads = threads;
     C.wg_per_cu = wg_per_cu;
+    const int nwave = threads / kWave;
+    auto set_chunks = [&](Side* sd) {
+        sd->chunk = (int)ceil_div(sd->n_iter, nwave);
+        sd->chunk_rem = sd->n_iter - (sd->chunk - 1) * nwave;
+        sd->chunk_div = make_fastdiv((uint32_t)sd->chunk);
+    };
+    set_chunks(&kp.a);
+    set_chunks(&kp.b);
+    const int64_t tab_entries = (int64_t)nwave * (kp.a.chunk + (direct ? 0 : kp.b.chunk));
+    const int tab_bytes = (int)round_up(24 * tab_entries, 16);
+    C.lds_bytes += tab_bytes - kp.lds_data_off;
+    kp.lds_data_off = tab_bytes;
+    if (C.lds_bytes > kMaxLdsBytes) return false;
     set_grid(&kp, launch_grid(C, 256));
     C.tuned_ms = 0.f;
     *out = C;
@@ -899,18 +912,24 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     const uint32_t nwave = (uint32_t)C.threads / kWave;
     if (nwave < 1 || C.threads % kWave) return TTC_ERR_INTERNAL;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
-    const uint32_t n_a = (uint32_t)p.a.n_iter, n_b = direct ? 0u : (uint32_t)p.b.n_iter;
-    if ((int64_t)24 * (n_a + n_b) > p.lds_data_off) return TTC_ERR_INTERNAL;
     if (p.lds_data_off + 2 * (int64_t)p.lds_tile_elems * eb != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
         return TTC_ERR_INTERNAL;
     // position tables, as a workgroup builds them
-    std::vector<PosEntry> tab_a(n_a), tab_b(n_b);
-    std::vector<PosCoord> tabc_a(n_a), tabc_b(n_b);
-    for (uint32_t it = 0; it < n_a; ++it) {
-        if (direct) make_position<true>(p.a, it, eb, &tab_a[it], &tabc_a[it]);
-        else make_position<false>(p.a, it, eb, &tab_a[it], &tabc_a[it]);
+    const uint32_t ta = nwave * (uint32_t)p.a.chunk, tbn = direct ? 0u : nwave * (uint32_t)p.b.chunk;
+    if ((int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
+    if (p.a.chunk_rem < 1 || p.a.chunk_rem > (int)nwave || (p.a.chunk - 1) * (int)nwave + p.a.chunk_rem != p.a.n_iter)
+        return TTC_ERR_INTERNAL;
+    if (!direct && (p.b.chunk_rem < 1 || p.b.chunk_rem > (int)nwave ||
+                    (p.b.chunk - 1) * (int)nwave + p.b.chunk_rem != p.b.n_iter)) return TTC_ERR_INTERNAL;
+    std::vector<PosEntry> tab_a(ta), tab_b(tbn);
+    std::vector<PosCoord> tabc_a(ta), tabc_b(tbn);
+    for (uint32_t th = 0; th < (uint32_t)C.threads; ++th) {
+        if (direct) build_tables<true>(p.a, nwave, th, (uint32_t)C.threads, eb, tab_a.data(), tabc_a.data());
+        else {
+            build_tables<false>(p.a, nwave, th, (uint32_t)C.threads, eb, tab_a.data(), tabc_a.data());
+            build_tables<false>(p.b, nwave, th, (uint32_t)C.threads, eb, tab_b.data(), tabc_b.data());
+        }
     }
-    for (uint32_t it = 0; it < n_b; ++it) make_position<false>(p.b, it, eb, &tab_b[it], &tabc_b[it]);
 
     const int64_t lds_bytes = (int64_t)p.lds_tile_elems * eb;
     std::vector<int64_t> lds((size_t)p.lds_tile_elems);          // which byte offset of A each slot holds
@@ -942,8 +961,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                                 b_from_a[ob / eb + j] = oa / eb + j;
                             }
                         };
-                        if (full_a) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
-                        else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                        if (full_a) walk<4, true>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
+                        else walk<4, false>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
                     }
                 continue;
             }
@@ -964,8 +983,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                             lds[li] = oa / eb + j;
                         }
                     };
-                    if (full_a) walk<4, true>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
-                    else walk<4, false>(p.a, L, la.lim, tab_a.data(), tabc_a.data(), wave, nwave, st, nop);
+                    if (full_a) walk<4, true>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
+                    else walk<4, false>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
                 }
             const SideLim lb = side_lim(p.b, tl);
             for (uint32_t wave = 0; wave < nwave; ++wave)
@@ -984,8 +1003,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                             b_from_a[ob / eb + j] = lds[li];
                         }
                     };
-                    if (full_b) walk<4, true>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
-                    else walk<4, false>(p.b, L, lb.lim, tab_b.data(), tabc_b.data(), wave, nwave, st, nop);
+                    if (full_b) walk<4, true>(p.b, L, lb, tab_b.data(), tabc_b.data(), wave, st, nop);
+                    else walk<4, false>(p.b, L, lb, tab_b.data(), tabc_b.data(), wave, st, nop);
                 }
         }
     }

@@ -163,41 +163,70 @@ TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e
 }
 
 // does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
-TTC_HD bool lane_valid(const LaneState& L, const int32_t* lim, const PosCoord& pc)
+// (bitwise and: no short-circuit branches between the comparisons)
+TTC_HD bool lane_valid(const LaneState& L, const SideLim& lim, const PosCoord& pc)
 {
     const int32_t p0 = (int32_t)(pc.c01 & 0xffffu), p1 = (int32_t)(pc.c01 >> 16);
     const int32_t p2 = (int32_t)(pc.c23 & 0xffffu), p3 = (int32_t)(pc.c23 >> 16);
-    return L.active && (L.c[0] < lim[0] - p0) && (L.c[1] < lim[1] - p1) &&
-           (L.c[2] < lim[2] - p2) && (L.c[3] < lim[3] - p3);
+    const int ok = (int)(L.c[0] < lim.lim[0] - p0) & (int)(L.c[1] < lim.lim[1] - p1) &
+                   (int)(L.c[2] < lim.lim[2] - p2) & (int)(L.c[3] < lim.lim[3] - p3);
+    return ok != 0;
 }
 
-// Drive one wavefront through its share of a walk: wavefront `wave` of `nwave` takes the
-// sub-box positions wave, wave + nwave, ...  Positions are handled U at a time: stage1 for all
-// U (issue the loads), then stage2 for all U (consume them), so that U memory instructions are
-// in flight per wavefront.   stage(u, entry): u = slot 0..U-1.
-template <int U, bool FULL, class Stage1, class Stage2>
-TTC_HD void walk(const Side& s, const LaneState& L, const int32_t* lim, const PosEntry* tab,
-                 const PosCoord* tabc, uint32_t wave, uint32_t nwave, Stage1&& stage1, Stage2&& stage2)
+// Which sub-box positions a wavefront takes, and where their table entries sit.  Wavefront w of
+// nwave takes positions w, w + nwave, w + 2 nwave, ...; the tables are stored wave-major, the
+// k-th position of wavefront w at index w * chunk + k, so that a wavefront reads consecutive
+// entries.
+TTC_HD uint32_t wave_positions(const Side& s, uint32_t wave)
 {
-    const uint32_t n_it = (uint32_t)s.n_iter;
-    for (uint32_t it0 = wave; it0 < n_it; it0 += U * nwave) {
-        PosEntry e[U];
-        bool ok[U];
+    return (uint32_t)s.chunk - (wave >= (uint32_t)s.chunk_rem ? 1u : 0u);
+}
+
+// U positions at a time: stage1 for all U (issue the loads), then stage2 for all U (consume
+// them), so that U memory instructions are in flight per wavefront.
+template <int U, bool FULL, class Stage1, class Stage2>
+TTC_HD void walk_group(const LaneState& L, const SideLim& lim, const PosEntry* e_ptr, const PosCoord* c_ptr,
+                       Stage1&& stage1, Stage2&& stage2)
+{
+    PosEntry e[U];
+    bool ok[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t it = it0 + u * nwave;
-            ok[u] = false;
-            if (it < n_it) {
-                e[u] = tab[it];
-                ok[u] = FULL ? L.active : lane_valid(L, lim, tabc[it]);
-            }
-        }
+    for (int u = 0; u < U; ++u) {
+        e[u] = e_ptr[u];
+        ok[u] = FULL ? true : lane_valid(L, lim, c_ptr[u]);
+    }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) stage1(u, e[u]);
+    for (int u = 0; u < U; ++u)
+        if (ok[u]) stage1(u, e[u]);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) stage2(u, e[u]);
+    for (int u = 0; u < U; ++u)
+        if (ok[u]) stage2(u, e[u]);
+}
+
+// Drive one wavefront through its share of a walk.   stage(u, entry): u = slot 0..U-1.
+template <int U, bool FULL, class Stage1, class Stage2>
+TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const PosEntry* tab,
+                 const PosCoord* tabc, uint32_t wave, Stage1&& stage1, Stage2&& stage2)
+{
+    if (!L.active) return;
+    const uint32_t cnt = wave_positions(s, wave);
+    const PosEntry* my = tab + wave * (uint32_t)s.chunk;
+    const PosCoord* myc = tabc + wave * (uint32_t)s.chunk;
+    uint32_t k = 0;
+    for (; k + U <= cnt; k += U) walk_group<U, FULL>(L, lim, my + k, myc + k, stage1, stage2);
+    for (; k < cnt; ++k) walk_group<1, FULL>(L, lim, my + k, myc + k, stage1, stage2);
+}
+
+// Fill the two tables of one walk (all threads of the workgroup take part).
+template <bool DIRECT>
+TTC_HD void build_tables(const Side& s, uint32_t nwave, uint32_t thread, uint32_t nthreads, int32_t scale,
+                         PosEntry* tab, PosCoord* tabc)
+{
+    const uint32_t total = nwave * (uint32_t)s.chunk;
+    for (uint32_t j = thread; j < total; j += nthreads) {
+        const uint32_t w = fdiv(j, s.chunk_div);
+        const uint32_t it = w + (j - w * (uint32_t)s.chunk) * nwave;
+        if (it < (uint32_t)s.n_iter) make_position<DIRECT>(s, it, scale, &tab[j], &tabc[j]);
     }
 }
 
