@@ -150,7 +150,7 @@ def main() -> int:
         heur = ttc.ttc_plan_get_info(plan)
         ms_heur = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, K)
         t0 = time.perf_counter()
-        ttc.ttc_plan_tune(plan, a_ptrs[0], b_ptrs[0], stream, args.max_candidates)
+        ttc.ttc_plan_tune_pairs(plan, a_ptrs, b_ptrs, stream, args.max_candidates)
         tune_s = time.perf_counter() - t0
         info = ttc.ttc_plan_get_info(plan)
         ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, K)

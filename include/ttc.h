@@ -139,6 +139,14 @@ int ttc_plan_tune(ttc_plan_t plan, const void* A_scratch, void* B_scratch, void*
                   int max_candidates);
 
 /*
+ * The same search over `npairs` buffer pairs (HOST arrays of DEVICE pointers) used in rotation,
+ * launch after launch, so that a last-level cache as large as a tensor cannot hold the working
+ * set and flatter some candidates.  Every B_list[i] is overwritten.  SYNCHRONISES the stream.
+ */
+int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                        void* stream, int max_candidates);
+
+/*
  * Measurement helper: enqueue `warmup` untimed and `iters` timed ttc_execute calls on
  * `stream`, launch i using the buffer pair (A_list[i % npairs], B_list[i % npairs])
  * (HOST arrays of DEVICE pointers; rotating pairs keeps the last-level cache from holding

@@ -21,7 +21,7 @@ TTC_EPI_COPY, TTC_EPI_SCALE, TTC_EPI_AXPBY = 0, 1, 2
 EXPORTS = (
     "ttc_plan_create", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
     "ttc_plan_get_info", "ttc_plan_candidate_count", "ttc_plan_select_candidate", "ttc_plan_tune",
-    "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
+    "ttc_plan_tune_pairs", "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
 )
 
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.ttc_plan_tune.restype = i
         L.ttc_plan_tune.argtypes = [vp, vp, vp, vp, i]
         pvp = ctypes.POINTER(ctypes.c_void_p)
+        L.ttc_plan_tune_pairs.restype = i
+        L.ttc_plan_tune_pairs.argtypes = [vp, i, pvp, pvp, vp, i]
         L.ttc_time_execute.restype = i
         L.ttc_time_execute.argtypes = [vp, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
         L.ttc_time_ceiling.restype = i
@@ -174,6 +176,14 @@ def ttc_plan_tune(plan: int, A: int, B: int, stream: Optional[int] = None, max_c
     st = lib().ttc_plan_tune(plan, A, B, stream or None, int(max_candidates))
     if st != TTC_OK:
         raise TtcError(st, "ttc_plan_tune")
+
+
+def ttc_plan_tune_pairs(plan: int, A_list: Sequence[int], B_list: Sequence[int], stream: Optional[int] = None,
+                        max_candidates: int = 0) -> None:
+    st = lib().ttc_plan_tune_pairs(plan, len(A_list), _ptr_array(A_list), _ptr_array(B_list), stream or None,
+                                   int(max_candidates))
+    if st != TTC_OK:
+        raise TtcError(st, "ttc_plan_tune_pairs")
 
 
 def _ptr_array(ptrs: Sequence[int]):

@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
 
         const TileLim tl = tile_lim(p, tile);
         const SideLim sla = side_lim(p.a, tl);
-        const bool full_a = tl.whole && p.a.exact;
+        const WalkMask wma = walk_mask(p.a, LA, sla);
         if (DIRECT) {
             Pack<T, VA> ra[kUnroll], rb[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
@@ -142,8 +142,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
                 *reinterpret_cast<Pack<T, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
             };
-            if (full_a) walk<kUnroll, true>(p.a, LA, sla, tab_a, tabc_a, wave, load, store);
-            else walk<kUnroll, false>(p.a, LA, sla, tab_a, tabc_a, wave, load, store);
+            walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, store);
             continue;
         }
 
@@ -159,14 +158,13 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
 #pragma unroll
                 for (int j = 0; j < VA; ++j) dst[j * vs] = ra[u].v[j];
             };
-            if (full_a) walk<kUnroll, true>(p.a, LA, sla, tab_a, tabc_a, wave, load, park);
-            else walk<kUnroll, false>(p.a, LA, sla, tab_a, tabc_a, wave, load, park);
+            walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, park);
         }
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
         {
             const SideLim slb = side_lim(p.b, tl);
-            const bool full_b = tl.whole && p.b.exact;
+            const WalkMask wmb = walk_mask(p.b, LB, slb);
             const int32_t vs = p.b.vec_lds_stride;
             Pack<T, VB> rb[kUnroll], rl[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
@@ -181,8 +179,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                 for (int j = 0; j < VB; ++j) out.v[j] = epi(rl[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : rl[u].v[j]);
                 *reinterpret_cast<Pack<T, VB>*>(Bt + (e.g + LB.g)) = out;
             };
-            if (full_b) walk<kUnroll, true>(p.b, LB, slb, tab_b, tabc_b, wave, load, store);
-            else walk<kUnroll, false>(p.b, LB, slb, tab_b, tabc_b, wave, load, store);
+            walk<kUnroll>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
         }
     }
 }
@@ -332,10 +329,15 @@ int ttc_execute(ttc_plan_t plan, const void* A, void* B, void* stream)
     return ttc::launch(plan->prob, c, A, B, (hipStream_t)stream) == hipSuccess ? TTC_OK : TTC_ERR_HIP;
 }
 
-int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max_candidates)
+int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                        void* stream, int max_candidates)
 {
-    const int st = ttc::check_buffers(plan, A, B);
-    if (st != TTC_OK) return st;
+    if (!plan || !A_list || !B_list) return TTC_ERR_NULL_POINTER;
+    if (npairs < 1) return TTC_ERR_INVALID_VALUE;
+    for (int i = 0; i < npairs; ++i) {
+        const int st = ttc::check_buffers(plan, A_list[i], B_list[i]);
+        if (st != TTC_OK) return st;
+    }
     hipStream_t s = (hipStream_t)stream;
     int cap = max_candidates;
     if (cap == 0) {
@@ -348,13 +350,14 @@ int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max
     if (cap == 1) { plan->selected = 0; return TTC_OK; }
     ttc::EventPair ev;
     if (!ev.ok) return TTC_ERR_HIP;
+    int turn = 0;
     // one launch configuration, timed: `warm` untimed launches, then the mean of `reps`
     auto time_one = [&](const ttc::Candidate& c, int warm, int reps, float* ms_out) -> int {
-        for (int r = 0; r < warm; ++r)
-            if (ttc::launch(plan->prob, c, A, B, s) != hipSuccess) return TTC_ERR_HIP;
+        for (int r = 0; r < warm; ++r, ++turn)
+            if (ttc::launch(plan->prob, c, A_list[turn % npairs], B_list[turn % npairs], s) != hipSuccess) return TTC_ERR_HIP;
         if (hipEventRecord(ev.start, s) != hipSuccess) return TTC_ERR_HIP;
-        for (int r = 0; r < reps; ++r)
-            if (ttc::launch(plan->prob, c, A, B, s) != hipSuccess) return TTC_ERR_HIP;
+        for (int r = 0; r < reps; ++r, ++turn)
+            if (ttc::launch(plan->prob, c, A_list[turn % npairs], B_list[turn % npairs], s) != hipSuccess) return TTC_ERR_HIP;
         if (hipEventRecord(ev.stop, s) != hipSuccess) return TTC_ERR_HIP;
         if (hipEventSynchronize(ev.stop) != hipSuccess) return TTC_ERR_HIP;
         float ms = 0.f;
@@ -385,6 +388,11 @@ int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max
     }
     if (best >= 0) plan->selected = best;
     return TTC_OK;
+}
+
+int ttc_plan_tune(ttc_plan_t plan, const void* A, void* B, void* stream, int max_candidates)
+{
+    return ttc_plan_tune_pairs(plan, 1, &A, &B, stream, max_candidates);
 }
 
 int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,

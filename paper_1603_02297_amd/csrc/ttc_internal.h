@@ -42,6 +42,8 @@ struct Digit {
     int32_t  lane_mul;               // flat elements per lane step: vec on the vector digit, else 1
     int32_t  slot_mul;               // flat elements per step of the slot's index (product of merged inner extents)
     int32_t  lstride;                // LDS element stride of one flat step
+    int32_t  ragged;                 // 1: lane does not divide tile (the last sub-box position overhangs)
+    int32_t  pad;
     FastDiv  lane_below, lane_cnt;   // lane id -> lane coordinate: (lane / below) % cnt
     FastDiv  iter_below, iter_cnt;   // position id -> position digit
     int64_t  gstride;                // element stride of one flat step in the tensor the walk follows

@@ -124,10 +124,18 @@ static int normalise(int dtype, int ndim, const int64_t* sizes, const int* perm,
 // Extent near `want` along an index of size s, a multiple of mult (s % mult == 0).
 // Divisors of s are preferred (no remainder tiles: the second rule of the paper's blocking
 // heuristic, Section 3.2); otherwise the index is cut into equal pieces.
-static int pick_extent(int64_t s, int64_t want, int mult)
+static int pick_extent(int64_t s, int64_t want, int mult, int style = 0, int nice = 1)
 {
     if (want < mult) want = mult;
     if (want >= s) return (int)s;
+    if (style == 1) {
+        // cache-line friendly: a multiple of `nice` elements (64 bytes) even if that leaves a remainder tile
+        const int64_t unit = std::max<int64_t>(nice, mult);
+        for (int64_t t = round_up(want, unit); t <= std::min<int64_t>(s, 2 * want); t += unit)
+            if (s % t == 0) return (int)t;
+        const int64_t t = round_up(want, unit);
+        if (t < s) return (int)t;
+    }
     for (int64_t t = round_up(want, mult); t <= std::min<int64_t>(s, 2 * want); t += mult)
         if (s % t == 0) return (int)t;
     for (int64_t t = (want / mult) * mult; t >= mult && 4 * t >= 3 * want; t -= mult)
@@ -139,7 +147,8 @@ static int pick_extent(int64_t s, int64_t want, int mult)
 
 // Leading indices of one tensor, in that tensor's order, until the contiguous run they
 // span reaches `target` elements.  All but the last are taken whole.
-static void build_group(const Problem& P, const int* order, int64_t target, int vec, int max_dims, int* t)
+static void build_group(const Problem& P, const int* order, int64_t target, int vec, int max_dims, int* t,
+                        int style = 0)
 {
     for (int k = 0; k < kMaxDim; ++k) t[k] = 1;
     int64_t run = 1;
@@ -150,7 +159,7 @@ static void build_group(const Problem& P, const int* order, int64_t target, int 
         const int mult = (i == 0) ? vec : 1;
         int ext;
         if (P.size[k] <= need + need / 2) ext = (int)P.size[k];
-        else ext = pick_extent(P.size[k], need, mult);
+        else ext = pick_extent(P.size[k], need, mult, style, 64 / P.elem_bytes);
         t[k] = ext;
         run *= ext;
         if (ext < P.size[k]) break;
@@ -244,21 +253,28 @@ static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int* n_iter_out
         int lanes = l0 / vec;
         int rem = kWave / std::max(lanes, 1);
         int64_t iters = ceil_div(t0, l0);
+        bool ragged = (t0 % l0) != 0;
         for (int i = 1; i < w->nd; ++i) {
             const int ti = w->d[i].tile;
             int l = 1;
             if (rem > 1) {
                 l = std::min(rem, ti);
-                l = (int)ceil_div(ti, ceil_div(ti, l));      // same count, less ragged
+                // prefer a divisor of the extent if it costs at most one position in four
+                int div = l;
+                while (div > 1 && ti % div != 0) --div;
+                if (4 * ceil_div(ti, div) <= 5 * ceil_div(ti, l)) l = div;
+                else l = (int)ceil_div(ti, ceil_div(ti, l));      // same count, less ragged
                 rem /= l;
                 lanes *= l;
             }
             lane[i] = l;
             iters *= ceil_div(ti, l);
+            if (ti % l != 0) ragged = true;
         }
-        // short segments along the stride-1 index cost coalescing: ask for a 128-byte line unless the tile is shorter
+        // short segments along the stride-1 index cost coalescing: ask for a 128-byte line unless the tile is
+        // shorter; an overhanging sub-box makes every position test its bounds
         const bool short_seg = (l0 < t0) && (l0 * P.elem_bytes < 128);
-        const int64_t cost = iters * (short_seg ? 2 : 1);
+        const int64_t cost = iters * (short_seg ? 8 : 4) * (ragged ? 5 : 4);
         if (cost < best_cost || (cost == best_cost && l0 > best_lane[0])) {
             best_cost = cost;
             for (int i = 0; i < kBoxDims; ++i) best_lane[i] = lane[i];
@@ -306,7 +322,8 @@ static bool fill_side(const Problem& P, const WalkSpec& w, int vec, const int* s
         d.gstride = follows_b ? P.stride_b[ds.first_dim] : P.stride_a[ds.first_dim];
         d.g2stride = P.stride_b[ds.first_dim];
         d.lstride = lds_stride ? lds_stride[ds.first_dim] : 0;
-        if (ds.tile % ds.lane != 0) s->exact = 0;
+        d.ragged = (ds.tile % ds.lane != 0) ? 1 : 0;
+        if (d.ragged) s->exact = 0;
         lane_below *= (uint32_t)cnt;
         iter_below *= (uint32_t)its;
         n_iter *= its;
@@ -592,56 +609,57 @@ void set_grid(KernelParams* kp, uint32_t grid)
 // remainder tiles, tile size, lane use and vector width.
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
+    // Weights fitted to timings of all candidates of the benchmark workloads on MI355X
+    // (log-linear least squares), rounded, with guard rails outside the measured range.
     const KernelParams& kp = C.kp;
     int order_a[kMaxDim], order_b[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < P.ndim) ? P.perm[k] : k; }
     const double eb = P.elem_bytes;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
-    // coalescing: length of the contiguous runs the box spans in each tensor
-    auto run_cost = [&](const int* order, int vec) {
-        const double run = (double)box_run(P, order, kp.tile) * eb;
-        double c = 1.0;
-        if (std::fmod(run, 128.0) != 0.0) c *= 1.0 + 32.0 / run;      // ragged ends share cache lines with a neighbour
-        if (run < 512.0) c *= 1.0 + 0.25 * (512.0 - run) / 512.0;
-        if (run < 128.0) c *= 1.0 + (128.0 - run) / 128.0;
-        const double vbytes = vec * eb;
-        c *= (vbytes >= 16 ? 1.0 : (vbytes >= 8 ? 1.04 : 1.12));
-        return c;
-    };
+    auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
     double volume = 1, padded = 1;
     for (int k = 0; k < P.ndim; ++k) {
         volume *= kp.tile[k];
         padded *= (double)ceil_div(P.size[k], kp.tile[k]) * kp.tile[k] / (double)P.size[k];
     }
     const double tile_bytes = volume * eb;
-    double cost = 0.5 * run_cost(order_a, kp.a.vec) + 0.5 * run_cost(order_b, direct ? kp.a.vec : kp.b.vec);
-    cost *= padded;                                                    // remainder tiles (paper Section 3.2, rule 2)
-    // tile size: measured optimum 8..16 KB for staged tiles, 16..64 KB for direct ones
+    const double run_a = (double)box_run(P, order_a, kp.tile) * eb;
+    const double run_b = (double)box_run(P, order_b, kp.tile) * eb;
+    const int vec_b = direct ? kp.a.vec : kp.b.vec;
+    double e = 0.0;
+    // coalescing: contiguous run per side; reads tolerate 64-byte runs, writes like 128 and more
+    e += 0.02 * oct_below(run_a, 512.0) + 0.03 * oct_below(run_b, 512.0);
+    e += 0.25 * oct_below(run_a, 64.0) + 0.10 * oct_below(run_b, 128.0) + 0.25 * oct_below(run_b, 64.0);
+    if (std::fmod(run_a, 128.0) != 0.0) e += 0.05 * 64.0 / run_a;      // ragged ends share lines with a neighbour
+    if (std::fmod(run_b, 128.0) != 0.0) e += 0.08 * 64.0 / run_b;
+    e += (kp.a.vec * eb >= 16 ? 0.0 : (kp.a.vec * eb >= 8 ? 0.04 : 0.08));
+    e += (vec_b * eb >= 16 ? 0.0 : (vec_b * eb >= 8 ? 0.02 : 0.12));
+    e += 2.0 * (padded - 1.0);                                          // remainder tiles
+    // tile size and occupancy
     const double lo = direct ? 16384.0 : 8192.0, hi = direct ? 65536.0 : 16384.0;
-    if (tile_bytes < lo) cost *= 1.0 + 0.45 * std::log2(lo / tile_bytes);
-    if (tile_bytes > hi) cost *= 1.0 + 0.06 * std::log2(tile_bytes / hi);
+    e += 0.19 * oct_below(tile_bytes, lo);
+    if (tile_bytes > hi) e += 0.03 * std::log2(tile_bytes / hi);
     const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
+    e += 0.13 * (lane_a - 1.0);
     if (!direct) {
-        // occupancy: workgroups of one CU share 160 KB of LDS
         const double resident_waves = std::min(32.0, std::floor(160.0 * 1024 / C.lds_bytes) * (C.threads / kWave));
-        if (resident_waves < 16.0) cost *= 1.0 + 0.03 * (16.0 - resident_waves);
+        if (resident_waves < 16.0) e += 0.20 * (16.0 - resident_waves) / 16.0;
         const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
-        cost *= 1.0 + 0.20 * (lane_a - 1.0) + 0.20 * (lane_b - 1.0);
-        cost *= 1.0 + 0.015 * (C.lds_conflict_a + C.lds_conflict_b - 4);
-        cost *= 1.06;                                                  // staging costs a barrier and LDS traffic
-    } else {
-        cost *= 1.0 + 0.20 * (lane_a - 1.0);
+        e += 0.10 * (lane_b - 1.0);
+        e += 0.006 * (C.lds_conflict_a + C.lds_conflict_b - 4);
+        e += 0.02;
+        if (!kp.a.exact) e += 0.02;
+        if (!kp.b.exact) e += 0.02;
     }
     // launch shape: measured preference
-    if (C.threads == 256 && C.wg_per_cu == 16) cost *= 1.00;
-    else if (C.threads == 128 && C.wg_per_cu == 8) cost *= 1.01;
-    else if (C.threads == 256 && C.wg_per_cu == 8) cost *= 1.02;
-    else cost *= 1.04;
+    if (C.threads == 128) e -= 0.02;
+    if (C.wg_per_cu == 4) e += 0.02;
+    else if (C.wg_per_cu == 8) e += 0.005;
     bool b_order = true;
     for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
-    if (!b_order) cost *= 1.005;
-    if (kp.num_tiles < 2048) cost *= 1.0 + 0.25 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
-    return cost;
+    if (!b_order) e += 0.015;
+    if (kp.num_tiles < 2048) e += 0.25 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
+    return std::exp(e);
 }
 
 static bool same_config(const Candidate& x, const Candidate& y)
@@ -694,11 +712,12 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
         for (int vsel = 0; vsel < 2; ++vsel) {
             if (vsel == 1 && vfull == 1) break;
             const int v = vsel == 0 ? vfull : 1;
+            for (int style = 0; style < 2; ++style)
             for (int64_t ra : chunk_bytes)
                 for (int64_t rb : chunk_bytes) {
                     int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                    build_group(P, order_a, ra / eb, v, kBoxDims, ta);
-                    build_group(P, order_b, rb / eb, v, kBoxDims, tb);
+                    build_group(P, order_a, ra / eb, v, kBoxDims, ta, style);
+                    build_group(P, order_b, rb / eb, v, kBoxDims, tb, style);
                     int64_t vol = 1;
                     int spanned = 0;
                     for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
@@ -726,11 +745,12 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
             const int vb = vsel == 0 ? vb_full : 1;
             const int vec_limit = vsel == 0 ? 16 : 1;
             for (int md = 3; md >= 1; --md)
+              for (int style = 0; style < 2; ++style)
                 for (int64_t ra : run_bytes)
                     for (int64_t rb : run_bytes) {
                         int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                        build_group(P, order_a, ra / eb, va, md, ta);
-                        build_group(P, order_b, rb / eb, vb, md, tb);
+                        build_group(P, order_a, ra / eb, va, md, ta, style);
+                        build_group(P, order_b, rb / eb, vb, md, tb, style);
                         int64_t vol = 1;
                         int spanned = 0;
                         for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
@@ -946,11 +966,11 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             const int64_t base_a = tb.a * eb, base_b = tb.b * eb;
             const TileLim tl = tile_lim(p, tile);
             const SideLim la = side_lim(p.a, tl);
-            const bool full_a = tl.whole && p.a.exact, full_b = tl.whole && p.b.exact;
             if (direct) {
                 for (uint32_t wave = 0; wave < nwave; ++wave)
                     for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                         const LaneState L = lane_setup<true>(p.a, lane, eb);
+                        const WalkMask wm = walk_mask(p.a, L, la);
                         auto st = [&](int, const PosEntry& e) {
                             const int64_t oa = base_a + e.g + L.g, ob = base_b + e.l_or_g2 + L.g2;
                             const int64_t w = (int64_t)p.a.vec * eb;
@@ -961,8 +981,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                                 b_from_a[ob / eb + j] = oa / eb + j;
                             }
                         };
-                        if (full_a) walk<4, true>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
-                        else walk<4, false>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
+                        walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
                     }
                 continue;
             }
@@ -970,6 +989,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.a, lane, eb);
+                    const WalkMask wm = walk_mask(p.a, L, la);
                     auto st = [&](int, const PosEntry& e) {
                         const int64_t oa = base_a + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
@@ -983,13 +1003,13 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                             lds[li] = oa / eb + j;
                         }
                     };
-                    if (full_a) walk<4, true>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
-                    else walk<4, false>(p.a, L, la, tab_a.data(), tabc_a.data(), wave, st, nop);
+                    walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
                 }
             const SideLim lb = side_lim(p.b, tl);
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.b, lane, eb);
+                    const WalkMask wm = walk_mask(p.b, L, lb);
                     auto st = [&](int, const PosEntry& e) {
                         const int64_t ob = base_b + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
@@ -1003,8 +1023,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                             b_from_a[ob / eb + j] = lds[li];
                         }
                     };
-                    if (full_b) walk<4, true>(p.b, L, lb, tab_b.data(), tabc_b.data(), wave, st, nop);
-                    else walk<4, false>(p.b, L, lb, tab_b.data(), tabc_b.data(), wave, st, nop);
+                    walk<4>(p.b, L, lb, wm, tab_b.data(), tabc_b.data(), wave, st, nop);
                 }
         }
     }

@@ -203,18 +203,42 @@ TTC_HD void walk_group(const LaneState& L, const SideLim& lim, const PosEntry* e
         if (ok[u]) stage2(u, e[u]);
 }
 
+// What a walk has to test per lane in one tile.  Digits with a single sub-box position are
+// tested once per tile (lane_ok); only digits that step AND are cut by the tensor's edge or
+// overhang the tile need the test at every position (dynamic, wave-uniform).
+struct WalkMask { bool lane_ok; bool dynamic; };
+
+TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
+{
+    WalkMask m;
+    m.lane_ok = L.active;
+    m.dynamic = false;
+#pragma unroll
+    for (int j = 0; j < kBoxDims; ++j) {
+        const Digit& d = s.d[j];
+        if (d.iters == 1) m.lane_ok = m.lane_ok & (L.c[j] < lim.lim[j]);
+        else m.dynamic = m.dynamic | (lim.lim[j] != d.tile) | (d.ragged != 0);
+    }
+    return m;
+}
+
 // Drive one wavefront through its share of a walk.   stage(u, entry): u = slot 0..U-1.
-template <int U, bool FULL, class Stage1, class Stage2>
-TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const PosEntry* tab,
+template <int U, class Stage1, class Stage2>
+TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const WalkMask& m, const PosEntry* tab,
                  const PosCoord* tabc, uint32_t wave, Stage1&& stage1, Stage2&& stage2)
 {
-    if (!L.active) return;
+    if (!m.lane_ok) return;
     const uint32_t cnt = wave_positions(s, wave);
     const PosEntry* my = tab + wave * (uint32_t)s.chunk;
     const PosCoord* myc = tabc + wave * (uint32_t)s.chunk;
     uint32_t k = 0;
-    for (; k + U <= cnt; k += U) walk_group<U, FULL>(L, lim, my + k, myc + k, stage1, stage2);
-    for (; k < cnt; ++k) walk_group<1, FULL>(L, lim, my + k, myc + k, stage1, stage2);
+    if (!m.dynamic) {
+        for (; k + U <= cnt; k += U) walk_group<U, true>(L, lim, my + k, myc + k, stage1, stage2);
+        for (; k < cnt; ++k) walk_group<1, true>(L, lim, my + k, myc + k, stage1, stage2);
+    } else {
+        for (; k + U <= cnt; k += U) walk_group<U, false>(L, lim, my + k, myc + k, stage1, stage2);
+        for (; k < cnt; ++k) walk_group<1, false>(L, lim, my + k, myc + k, stage1, stage2);
+    }
 }
 
 // Fill the two tables of one walk (all threads of the workgroup take part).
