@@ -91,6 +91,13 @@ template <int MODE> struct Epilogue<cfloat, MODE> {
 // ---------------------------------------------------------------------------------
 constexpr int kUnroll = 4;     // memory instructions a wavefront keeps in flight per walk step
 
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 template <typename T, int V>
 __device__ __forceinline__ Pack<T, V> load_pack(const unsigned char* base, int64_t off)
 {
@@ -105,7 +112,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
     constexpr int32_t kScale = (int32_t)sizeof(T);
     const uint32_t nwave = blockDim.x >> 6;
     const uint32_t n_a = nwave * (uint32_t)p.a.chunk, n_b = DIRECT ? 0u : nwave * (uint32_t)p.b.chunk;
-    PosEntry* tab_a = reinterpret_cast<PosEntry*>(smem);
+    TileShare* share = reinterpret_cast<TileShare*>(smem);            // two slots, kTileShareBytes in all
+    PosEntry* tab_a = reinterpret_cast<PosEntry*>(smem + kTileShareBytes);
     PosEntry* tab_b = tab_a + n_a;
     PosCoord* tabc_a = reinterpret_cast<PosCoord*>(tab_b + n_b);
     PosCoord* tabc_b = tabc_a + n_a;
@@ -117,17 +125,39 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
     if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, kScale, tab_b, tabc_b);
     const LaneState LA = lane_setup<DIRECT>(p.a, lane, kScale);
     const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, kScale);
-    __syncthreads();
-
     const Epilogue<T, MODE> epi(p);
     const TileSeq seq = tile_sequence(p, blockIdx.x);
+
+    // Staged kernel: the last wavefront works out where a tile lies (scalar divisions and
+    // multiplications) one tile ahead and leaves the result in LDS; the barrier that already
+    // separates the two walks of the current tile publishes it to the other wavefronts.
+    auto publish = [&](uint32_t tile, uint32_t slot) {
+        const TileBase tb = tile_base(p, tile);
+        const TileLim tl = tile_lim(p, tile);
+        TileShare v;
+        v.a = tb.a; v.b = tb.b;
+        v.lim[0] = tl.lim[0]; v.lim[1] = tl.lim[1]; v.lim[2] = tl.lim[2]; v.lim[3] = tl.lim[3];
+        share[slot] = v;
+    };
+    if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(seq.first, 0);
+    __syncthreads();
+
     uint32_t parity = 0;
     for (uint32_t tile = seq.first; tile < seq.end; tile += seq.step) {
-        const TileBase tb = tile_base(p, tile);
+        TileBase tb;
+        TileLim tl;
+        if (DIRECT) {
+            tb = tile_base(p, tile);
+            tl = tile_lim(p, tile);
+        } else {
+            const TileShare v = share[parity];
+            tb.a = uniform64(v.a); tb.b = uniform64(v.b);
+            tl.lim[0] = __builtin_amdgcn_readfirstlane(v.lim[0]); tl.lim[1] = __builtin_amdgcn_readfirstlane(v.lim[1]);
+            tl.lim[2] = __builtin_amdgcn_readfirstlane(v.lim[2]); tl.lim[3] = __builtin_amdgcn_readfirstlane(v.lim[3]);
+            tl.whole = false;
+        }
         const unsigned char* At = reinterpret_cast<const unsigned char*>(A + tb.a);
         unsigned char* Bt = reinterpret_cast<unsigned char*>(B + tb.b);
-
-        const TileLim tl = tile_lim(p, tile);
         const SideLim sla = side_lim(p.a, tl);
         const WalkMask wma = walk_mask(p.a, LA, sla);
         if (DIRECT) {
@@ -160,6 +190,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
             };
             walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, park);
         }
+        if (wave == nwave - 1 && tile + seq.step < seq.end) publish(tile + seq.step, parity);   // parity already flipped
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
         {

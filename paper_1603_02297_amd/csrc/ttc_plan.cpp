@@ -580,7 +580,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     set_chunks(&kp.a);
     set_chunks(&kp.b);
     const int64_t tab_entries = (int64_t)nwave * (kp.a.chunk + (direct ? 0 : kp.b.chunk));
-    const int tab_bytes = (int)round_up(24 * tab_entries, 16);
+    const int tab_bytes = (int)round_up(kTileShareBytes + 24 * tab_entries, 16);
     C.lds_bytes += tab_bytes - kp.lds_data_off;
     kp.lds_data_off = tab_bytes;
     if (C.lds_bytes > kMaxLdsBytes) return false;
@@ -936,7 +936,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
         return TTC_ERR_INTERNAL;
     // position tables, as a workgroup builds them
     const uint32_t ta = nwave * (uint32_t)p.a.chunk, tbn = direct ? 0u : nwave * (uint32_t)p.b.chunk;
-    if ((int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
+    if (kTileShareBytes + (int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
     if (p.a.chunk_rem < 1 || p.a.chunk_rem > (int)nwave || (p.a.chunk - 1) * (int)nwave + p.a.chunk_rem != p.a.n_iter)
         return TTC_ERR_INTERNAL;
     if (!direct && (p.b.chunk_rem < 1 || p.b.chunk_rem > (int)nwave ||

@@ -54,12 +54,16 @@ TTC_HD TileSeq tile_sequence(const KernelParams& p, uint32_t wg)
 
 // tile id -> element offsets of the box origin in A and in B
 struct TileBase { int64_t a, b; };
+// what one wavefront works out for the others about a tile (two of these sit at the start of LDS)
+struct alignas(16) TileShare { int64_t a, b; int32_t lim[kBoxDims]; };
+constexpr int kTileShareBytes = 2 * (int)sizeof(TileShare);
 
 TTC_HD TileBase tile_base(const KernelParams& p, uint32_t tile)
 {
     TileBase t;
     t.a = 0; t.b = 0;
     for (int k = 0; k < p.n; ++k) {
+        if (p.tile_cnt[k].div == 1) continue;
         const int64_t origin = (int64_t)fdigit(tile, p.tile_below[k], p.tile_cnt[k]) * p.tile[k];
         t.a += origin * p.stride_a[k];
         t.b += origin * p.stride_b[k];
