@@ -75,7 +75,8 @@ typedef struct {
     int     threads;                       /* workgroup size */
     int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles */
     int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
-    int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + two tile buffers */
+    int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + tile buffer(s) */
+    int     lds_buffers;                   /* 2: tile buffers alternate (one barrier per tile), 1: one buffer (two barriers) */
     int     lds_conflict_a, lds_conflict_b;/* modelled worst bank multiplicity of the LDS write / read instructions */
     int64_t num_tiles;                     /* tiles the tensor is cut into */
     int64_t elements;                      /* prod(sizes) */

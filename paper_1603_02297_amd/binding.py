@@ -36,7 +36,7 @@ class ttc_plan_info_t(ctypes.Structure):
         ("tile_order", ctypes.c_int * TTC_MAX_DIM),
         ("lds_stride", ctypes.c_int * TTC_MAX_DIM),
         ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
-        ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int),
+        ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("lds_buffers", ctypes.c_int),
         ("lds_conflict_a", ctypes.c_int), ("lds_conflict_b", ctypes.c_int),
         ("num_tiles", ctypes.c_int64), ("elements", ctypes.c_int64), ("bytes_moved", ctypes.c_int64),
         ("candidate_index", ctypes.c_int), ("candidate_count", ctypes.c_int), ("tuned_ms", ctypes.c_float), ("heuristic_cost", ctypes.c_double),

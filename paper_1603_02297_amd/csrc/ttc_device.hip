@@ -84,7 +84,7 @@ template <int MODE> struct Epilogue<cfloat, MODE> {
 };
 
 // ---------------------------------------------------------------------------------
-// The kernel.  Dynamic LDS: [position tables of both walks][tile buffer 0][tile buffer 1].
+// The kernel.  Dynamic LDS: [two shared tile records][position tables of both walks][tile buffer 0][tile buffer 1].
 // A workgroup walks several tiles; with two tile buffers one barrier per tile is enough: a
 // wavefront can only start filling buffer (t+1)%2 after it passed the barrier of tile t, and
 // every wavefront reached that barrier after it had finished reading that buffer for tile t-1.
@@ -176,7 +176,8 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
             continue;
         }
 
-        unsigned char* lds = smem + p.lds_data_off + parity * (uint32_t)(p.lds_tile_elems * kScale);
+        unsigned char* lds = smem + p.lds_data_off +
+                             (parity & (uint32_t)(p.lds_buffers - 1)) * (uint32_t)(p.lds_tile_elems * kScale);
         parity ^= 1u;
         // ---- walk 1: A order, global -> LDS
         {
@@ -212,6 +213,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
             };
             walk<kUnroll>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
         }
+        if (p.lds_buffers == 1) __syncthreads();      // the one buffer is refilled by the next tile
     }
 }
 

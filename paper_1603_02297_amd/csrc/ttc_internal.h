@@ -82,6 +82,8 @@ struct KernelParams {
     uint32_t grid_rem_xcd;           // grid % 8
     int32_t  lds_data_off;           // byte offset of the first data buffer in dynamic LDS
     int32_t  lds_tile_elems;         // elements per LDS data buffer (padded tile)
+    int32_t  lds_buffers;            // 2: tile buffers alternate, one barrier per tile; 1: one buffer, two barriers
+    int32_t  pad3;
     int32_t  nslots;                 // indices the box spans
     int32_t  pad2;
     Slot     slot[kBoxDims];

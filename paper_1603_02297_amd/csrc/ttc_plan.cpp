@@ -398,7 +398,7 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
             }
         }
         L.elems = (int)run;
-        if (2 * (int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
+        if ((int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
         Side sa, sb;
         if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &sa)) continue;
         if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &sb)) continue;
@@ -428,7 +428,7 @@ struct LayoutCache { std::vector<std::pair<LayoutKey, LdsLayout>> items; };
 
 static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, bool direct, int threads,
                            int wg_per_cu, const int* tile_order, int xcd_remap, Candidate* out,
-                           bool merge_a = true, bool merge_b = true, LayoutCache* cache = nullptr)
+                           bool merge_a = true, bool merge_b = true, LayoutCache* cache = nullptr, int nbuf = 2)
 {
     Candidate C;
     std::memset(&C, 0, sizeof(C));
@@ -509,6 +509,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         C.lds_bytes = (int)round_up(24 * (int64_t)kp.a.n_iter, 16);
         kp.lds_data_off = C.lds_bytes;
         kp.lds_tile_elems = 0;
+        kp.lds_buffers = 1;
         C.lds_conflict_a = C.lds_conflict_b = 0;
     } else {
         if (nslots == 0) return false;
@@ -558,7 +559,8 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         C.kernel_class = TTC_KERNEL_LDS;
         kp.lds_data_off = (int)round_up(24 * (int64_t)(kp.a.n_iter + kp.b.n_iter), 16);
         kp.lds_tile_elems = (int)round_up(L.elems, 16 / P.elem_bytes);
-        C.lds_bytes = kp.lds_data_off + 2 * kp.lds_tile_elems * P.elem_bytes;
+        kp.lds_buffers = nbuf;
+        C.lds_bytes = kp.lds_data_off + nbuf * kp.lds_tile_elems * P.elem_bytes;
         if (C.lds_bytes > kMaxLdsBytes) return false;
         C.lds_conflict_a = L.conflict_a;
         C.lds_conflict_b = L.conflict_b;
@@ -665,7 +667,7 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
 static bool same_config(const Candidate& x, const Candidate& y)
 {
     if (x.kernel_class != y.kernel_class || x.threads != y.threads || x.wg_per_cu != y.wg_per_cu) return false;
-    if (x.kp.a.vec != y.kp.a.vec || x.kp.b.vec != y.kp.b.vec) return false;
+    if (x.kp.a.vec != y.kp.a.vec || x.kp.b.vec != y.kp.b.vec || x.kp.lds_buffers != y.kp.lds_buffers) return false;
     for (int k = 0; k < kMaxDim; ++k) {
         if (x.tile[k] != y.tile[k]) return false;
         if (x.kp.tile_below[k].div != y.kp.tile_below[k].div) return false;
@@ -756,16 +758,19 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
                         for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
                         if (spanned > kBoxDims) continue;
-                        if (2 * vol * eb > kMaxLdsBytes - 1024) continue;
+                        if (vol * eb > kMaxLdsBytes - 2048) continue;
                         if (vol * eb < 2048 && md > 1 && vol < P.elements) continue;
-                        for (int mg = 0; mg < 4; ++mg)
-                            for (int o = 0; o < 2; ++o)
-                                for (const LaunchShape& ls : kLaunchShapes) {
-                                    Candidate c;
-                                    if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1, &c,
-                                                       (mg & 1) == 0, (mg & 2) == 0, &cache))
-                                        add_candidate(P, out, c);
-                                }
+                        for (int nbuf = 2; nbuf >= 1; --nbuf) {
+                            if (nbuf == 1 && vol * eb < 8192) continue;     // small tiles can afford two buffers
+                            for (int mg = 0; mg < 4; ++mg)
+                                for (int o = 0; o < 2; ++o)
+                                    for (const LaunchShape& ls : kLaunchShapes) {
+                                        Candidate c;
+                                        if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1,
+                                                           &c, (mg & 1) == 0, (mg & 2) == 0, &cache, nbuf))
+                                            add_candidate(P, out, c);
+                                    }
+                        }
                     }
         }
     }
@@ -798,7 +803,8 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
         // every candidate is vectorised: add the scalar variant of the best one
         const Candidate& b = plan->cands[0];
         Candidate c;
-        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c))
+        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c,
+                            true, true, nullptr, b.kp.lds_buffers))
             return TTC_ERR_OVERFLOW;
         c.score = heuristic_cost(P, c);
         plan->cands.push_back(c);
@@ -888,6 +894,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->wg_per_cu = C.wg_per_cu;
     out->xcd_remap = C.kp.xcd_remap;
     out->lds_bytes = C.lds_bytes;
+    out->lds_buffers = C.kp.lds_buffers;
     out->lds_conflict_a = C.lds_conflict_a;
     out->lds_conflict_b = C.lds_conflict_b;
     out->num_tiles = C.kp.num_tiles;
@@ -932,7 +939,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     const uint32_t nwave = (uint32_t)C.threads / kWave;
     if (nwave < 1 || C.threads % kWave) return TTC_ERR_INTERNAL;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
-    if (p.lds_data_off + 2 * (int64_t)p.lds_tile_elems * eb != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
+    if ((p.lds_buffers != 1 && p.lds_buffers != 2) ||
+        p.lds_data_off + p.lds_buffers * (int64_t)p.lds_tile_elems * eb != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
         return TTC_ERR_INTERNAL;
     // position tables, as a workgroup builds them
     const uint32_t ta = nwave * (uint32_t)p.a.chunk, tbn = direct ? 0u : nwave * (uint32_t)p.b.chunk;
