@@ -78,6 +78,9 @@ typedef struct {
     int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + tile buffer(s) */
     int     lds_buffers;                   /* 2: tile buffers alternate (one barrier per tile), 1: one buffer (two barriers) */
     int     lds_conflict_a, lds_conflict_b;/* modelled worst bank multiplicity of the LDS write / read instructions */
+    int     run_bytes_a, run_bytes_b;      /* contiguous bytes the tile spans in A / in B */
+    int     seg_bytes_a, seg_bytes_b;      /* contiguous bytes one wavefront instruction covers in A / in B */
+    int     align_a, align_b;              /* power of two (<= 128) dividing the byte offset of every run start */
     int64_t num_tiles;                     /* tiles the tensor is cut into */
     int64_t elements;                      /* prod(sizes) */
     int64_t bytes_moved;                   /* 2 or 3 x tensor bytes: read A, write B, read B iff beta != 0 (paper Eq. 2) */

@@ -38,6 +38,8 @@ class ttc_plan_info_t(ctypes.Structure):
         ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
         ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("lds_buffers", ctypes.c_int),
         ("lds_conflict_a", ctypes.c_int), ("lds_conflict_b", ctypes.c_int),
+        ("run_bytes_a", ctypes.c_int), ("run_bytes_b", ctypes.c_int), ("seg_bytes_a", ctypes.c_int),
+        ("seg_bytes_b", ctypes.c_int), ("align_a", ctypes.c_int), ("align_b", ctypes.c_int),
         ("num_tiles", ctypes.c_int64), ("elements", ctypes.c_int64), ("bytes_moved", ctypes.c_int64),
         ("candidate_index", ctypes.c_int), ("candidate_count", ctypes.c_int), ("tuned_ms", ctypes.c_float), ("heuristic_cost", ctypes.c_double),
     ]

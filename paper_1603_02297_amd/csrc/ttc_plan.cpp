@@ -609,13 +609,67 @@ void set_grid(KernelParams* kp, uint32_t grid)
 // estimate that admits candidates to the bounded queue; the paper does not define one, this
 // one prices coalescing (length and alignment of the contiguous runs on both sides),
 // remainder tiles, tile size, lane use and vector width.
+// How a candidate touches memory, in bytes per side: the contiguous run the tile spans, the
+// contiguous piece one wavefront instruction covers, and the power of two (up to 128) that
+// divides the byte offset of every run start.
+struct AccessShape { int run[2], seg[2], align[2]; };
+
+static int segment_elems(const Side& s, bool second)
+{
+    struct Item { int64_t stride; int lane, tile; } it[kBoxDims];
+    int n = 0;
+    for (int j = 0; j < kBoxDims; ++j)
+        if (s.d[j].tile > 1) { it[n].stride = second ? s.d[j].g2stride : s.d[j].gstride; it[n].lane = s.d[j].lane; it[n].tile = s.d[j].tile; ++n; }
+    std::sort(it, it + n, [](const Item& x, const Item& y) { return x.stride < y.stride; });
+    int64_t seg = 1, expect = 1;
+    for (int i = 0; i < n; ++i) {
+        if (it[i].stride != expect) break;
+        seg *= it[i].lane;
+        if (it[i].lane < it[i].tile) break;
+        expect = it[i].stride * it[i].tile;
+    }
+    return (int)std::min<int64_t>(seg, 1 << 20);
+}
+
+static AccessShape access_shape(const Problem& P, const Candidate& C)
+{
+    AccessShape r;
+    const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
+    for (int side = 0; side < 2; ++side) {
+        int order[kMaxDim];
+        for (int k = 0; k < kMaxDim; ++k) order[k] = side ? ((k < P.ndim) ? P.perm[k] : k) : k;
+        const int64_t* stride = side ? P.stride_b : P.stride_a;
+        int64_t run = 1, g = 0;
+        bool open = true;
+        for (int i = 0; i < P.ndim; ++i) {
+            const int k = order[i];
+            if (open) {
+                run *= C.kp.tile[k];
+                if (C.kp.tile[k] < P.size[k]) open = false;
+            } else if (P.size[k] > 1) {
+                int64_t a = stride[k] * P.elem_bytes, b = g;
+                while (b) { const int64_t t = a % b; a = b; b = t; }
+                g = a;
+            }
+        }
+        int64_t a = run * P.elem_bytes, b = g;
+        while (b) { const int64_t t = a % b; a = b; b = t; }
+        int al = 1;
+        while (al < 128 && a % (2 * al) == 0) al *= 2;
+        r.run[side] = (int)std::min<int64_t>(run * P.elem_bytes, INT32_MAX);
+        r.align[side] = al;
+        const Side& s = (side && !direct) ? C.kp.b : C.kp.a;
+        r.seg[side] = segment_elems(s, side && direct) * P.elem_bytes;
+    }
+    return r;
+}
+
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
-    // Weights fitted to timings of all candidates of the benchmark workloads on MI355X
-    // (log-linear least squares), rounded, with guard rails outside the measured range.
+    // Weights fitted to timings of every candidate of some forty problems on MI355X (the benchmark
+    // workloads plus 2-D to 6-D problems with odd, small and large extents; log-linear least squares
+    // weighted towards the fast candidates), rounded, with guard rails outside the measured range.
     const KernelParams& kp = C.kp;
-    int order_a[kMaxDim], order_b[kMaxDim];
-    for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < P.ndim) ? P.perm[k] : k; }
     const double eb = P.elem_bytes;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
     auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
@@ -625,42 +679,46 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
         padded *= (double)ceil_div(P.size[k], kp.tile[k]) * kp.tile[k] / (double)P.size[k];
     }
     const double tile_bytes = volume * eb;
-    const double run_a = (double)box_run(P, order_a, kp.tile) * eb;
-    const double run_b = (double)box_run(P, order_b, kp.tile) * eb;
+    const AccessShape sh = access_shape(P, C);
+    const double run_a = sh.run[0], run_b = sh.run[1], seg_a = sh.seg[0], seg_b = sh.seg[1];
     const int vec_b = direct ? kp.a.vec : kp.b.vec;
     double e = 0.0;
-    // coalescing: contiguous run per side; reads tolerate 64-byte runs, writes like 128 and more
-    e += 0.02 * oct_below(run_a, 512.0) + 0.03 * oct_below(run_b, 512.0);
-    e += 0.25 * oct_below(run_a, 64.0) + 0.10 * oct_below(run_b, 128.0) + 0.25 * oct_below(run_b, 64.0);
-    if (std::fmod(run_a, 128.0) != 0.0) e += 0.05 * 64.0 / run_a;      // ragged ends share lines with a neighbour
-    if (std::fmod(run_b, 128.0) != 0.0) e += 0.08 * 64.0 / run_b;
-    e += (kp.a.vec * eb >= 16 ? 0.0 : (kp.a.vec * eb >= 8 ? 0.04 : 0.08));
-    e += (vec_b * eb >= 16 ? 0.0 : (vec_b * eb >= 8 ? 0.02 : 0.12));
-    e += 2.0 * (padded - 1.0);                                          // remainder tiles
+    // coalescing: the contiguous run per tile and the contiguous piece per wavefront instruction; writes
+    // are the sensitive side, and runs that start off a 128-byte line pay for the lines they share
+    e += 0.003 * oct_below(run_a, 1024.0) + 0.006 * oct_below(run_b, 1024.0);
+    e += 0.25 * oct_below(run_a, 64.0) + 0.32 * oct_below(run_b, 64.0);
+    e += 0.03 * (1.0 - sh.align[0] / 128.0) * 128.0 / run_a + 0.09 * (1.0 - sh.align[1] / 128.0) * 128.0 / run_b;
+    e += 0.017 * oct_below(seg_a, 256.0) + 0.020 * oct_below(seg_b, 256.0);
+    e += 0.10 * oct_below(seg_a, 64.0) + 0.32 * oct_below(seg_b, 64.0);
+    e += (kp.a.vec * eb >= 16 ? 0.0 : (kp.a.vec * eb >= 8 ? 0.016 : 0.047));
+    e += (vec_b * eb >= 16 ? 0.0 : (vec_b * eb >= 8 ? 0.007 : 0.024));
+    e += 0.25 * (padded - 1.0);                                         // lanes idle in remainder tiles
     // tile size and occupancy
-    const double lo = direct ? 16384.0 : 8192.0, hi = direct ? 65536.0 : 16384.0;
-    e += 0.19 * oct_below(tile_bytes, lo);
-    if (tile_bytes > hi) e += 0.03 * std::log2(tile_bytes / hi);
+    const double lo = direct ? 16384.0 : 8192.0;
+    e += 0.18 * oct_below(tile_bytes, lo);
+    if (tile_bytes > 16384.0) e -= 0.025 * std::min(2.0, std::log2(tile_bytes / 16384.0));
     const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
-    e += 0.13 * (lane_a - 1.0);
-    if (!direct) {
+    e += 0.055 * (lane_a - 1.0);
+    if (direct) {
+        // no regrouping through LDS: every instruction's piece meets memory as it is
+        e += 0.15 * (1.0 - sh.align[0] / 128.0) * 128.0 / seg_a + 0.15 * (1.0 - sh.align[1] / 128.0) * 128.0 / seg_b;
+    } else {
         const double resident_waves = std::min(32.0, std::floor(160.0 * 1024 / C.lds_bytes) * (C.threads / kWave));
-        if (resident_waves < 16.0) e += 0.20 * (16.0 - resident_waves) / 16.0;
+        if (resident_waves < 16.0) e += 0.19 * (16.0 - resident_waves) / 16.0;
+        if (resident_waves < 8.0) e += 0.13 * (8.0 - resident_waves) / 8.0;
         const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
-        e += 0.10 * (lane_b - 1.0);
-        e += 0.006 * (C.lds_conflict_a + C.lds_conflict_b - 4);
-        e += 0.02;
-        if (!kp.a.exact) e += 0.02;
-        if (!kp.b.exact) e += 0.02;
+        e += 0.03 * (lane_b - 1.0);
+        e += 0.002 * (C.lds_conflict_a + C.lds_conflict_b - 4);
+        e += 0.024;
     }
     // launch shape: measured preference
-    if (C.threads == 128) e -= 0.02;
-    if (C.wg_per_cu == 4) e += 0.02;
-    else if (C.wg_per_cu == 8) e += 0.005;
+    if (C.threads == 128) e -= 0.03;
+    if (C.wg_per_cu == 4) e += 0.008;
+    else if (C.wg_per_cu == 8) e += 0.007;
     bool b_order = true;
     for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
-    if (!b_order) e += 0.015;
-    if (kp.num_tiles < 2048) e += 0.25 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
+    if (!b_order) e += 0.023;
+    if (kp.num_tiles < 2048) e += 0.39 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
     return std::exp(e);
 }
 
@@ -897,6 +955,12 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->lds_buffers = C.kp.lds_buffers;
     out->lds_conflict_a = C.lds_conflict_a;
     out->lds_conflict_b = C.lds_conflict_b;
+    {
+        const ttc::AccessShape sh = ttc::access_shape(P, C);
+        out->run_bytes_a = sh.run[0]; out->run_bytes_b = sh.run[1];
+        out->seg_bytes_a = sh.seg[0]; out->seg_bytes_b = sh.seg[1];
+        out->align_a = sh.align[0];   out->align_b = sh.align[1];
+    }
     out->num_tiles = C.kp.num_tiles;
     out->elements = P.elements;
     out->bytes_moved = (P.epilogue == TTC_EPI_AXPBY ? 3 : 2) * P.elements * P.elem_bytes;
