@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import F32, F64, C64, C128
+from oracle import F32, F64, C64, C128, F32_F64, F64_F32, C64_C128, C128_C64
 
 REAL = {F32: np.float32, F64: np.float64, C64: np.float32, C128: np.float64}
 COMPS = {F32: 1, F64: 1, C64: 2, C128: 2}
@@ -238,3 +238,153 @@ def test_rejects_what_the_definition_does_not_cover():
             oracle.transpose(F32, sizes, perm, 1.0, 0.0, A, np.zeros(6, np.float32))
     with pytest.raises(ValueError):
         oracle.transpose(F32, (2, 3), (1, 0), 1.0, 0.0, A, A)
+
+
+# ======================================================================================
+# Sub-tensors (paper Table 1, --lda / --ldb; Section 3: "a portion of larger tensors").
+# ======================================================================================
+
+def test_ld_pairs_by_hand():
+    # sizes 2x2 inside A of leading dimension 3 and B of leading dimension 4, matrix transpose:
+    # A offset i0 + 3*i1 goes to B offset i1 + 4*i0.
+    assert oracle.element_pairs((2, 2), (1, 0), lda=(3, 2), ldb=(4, 2)) == [(0, 0), (1, 4), (3, 1), (4, 5)]
+    assert oracle.strides((2, 5, 3), (4, 6, 3)) == [1, 4, 24]
+    assert oracle.span((2, 5, 3), (4, 6, 3)) == 1 + 1 + 4 * 4 + 2 * 24
+
+
+def test_ld_equal_to_size_is_the_dense_operation():
+    sizes, perm = (5, 3, 4), (2, 0, 1)
+    A, B0 = rand(F32, 60, 61), rand(F32, 60, 62)
+    dense = run(F32, sizes, perm, 0.75, 1.25, A, B0)
+    ld = oracle.transpose(F32, sizes, perm, 0.75, 1.25, A, B0.copy(), 1, lda=sizes, ldb=(4, 5, 3))
+    assert np.array_equal(dense, ld)
+
+
+def _random_ld_problem(seed, n=None):
+    rng = np.random.default_rng(seed)
+    n = n or int(rng.integers(2, 5))
+    sizes = tuple(int(x) for x in rng.integers(1, 6, n))
+    perm = tuple(int(x) for x in rng.permutation(n))
+    lda = tuple(s + int(x) for s, x in zip(sizes, rng.integers(0, 3, n)))
+    ldb = tuple(sizes[perm[j]] + int(x) for j, x in zip(range(n), rng.integers(0, 3, n)))
+    return sizes, perm, lda, ldb
+
+
+@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (2.0, -1.0)])
+def test_subtensor_matches_numpy_slicing(seed, alpha, beta):
+    # numpy does the addressing: the enclosing arrays are Fortran-ordered, the sub-tensors are slices of
+    # them.  alpha=2, beta=-1 has a single rounding, so the values are fixed bit for bit too.
+    sizes, perm, lda, ldb = _random_ld_problem(100 + seed)
+    n = len(sizes)
+    PA, PB0 = rand(F32, prod(lda), 200 + seed), rand(F32, prod(ldb), 300 + seed)
+    PB = oracle.transpose(F32, sizes, perm, alpha, beta, PA, PB0.copy(), 1, lda=lda, ldb=ldb)
+    want = PB0.reshape(ldb, order="F").copy(order="F")
+    sub_a = PA.reshape(lda, order="F")[tuple(slice(0, s) for s in sizes)]
+    sl_b = tuple(slice(0, sizes[perm[j]]) for j in range(n))
+    moved = np.transpose(sub_a, perm).astype(np.float64)
+    if beta == 0.0:
+        want[sl_b] = moved.astype(np.float32)
+    else:
+        want[sl_b] = (2.0 * moved - want[sl_b].astype(np.float64)).astype(np.float32)
+    assert np.array_equal(PB, want.reshape(-1, order="F"))      # inside AND outside the sub-tensor
+
+
+@pytest.mark.parametrize("n", [1, 2, 3])
+def test_walker_vs_strided_element_pairs(n):
+    for seed in range(4):
+        sizes, _, lda, _ = _random_ld_problem(400 + 10 * n + seed, n)
+        for perm in itertools.permutations(range(n)):
+            ldb = tuple(sizes[perm[j]] + (j + seed) % 3 for j in range(n))
+            PA = np.arange(prod(lda), dtype=np.float64)             # value = offset in A
+            PB = oracle.transpose(F64, sizes, perm, 1.0, 0.0, PA, np.full(prod(ldb), -1.0), 1, lda=lda, ldb=ldb)
+            want = np.full(prod(ldb), -1.0)
+            for off_a, off_b in oracle.element_pairs(sizes, perm, lda, ldb):
+                want[off_b] = off_a
+            assert np.array_equal(PB, want)
+
+
+def test_merge_condition_with_leading_dimensions():
+    # Footnote of Section 3, stage (1): indices m, m+1 may merge iff ld(m+1) = size(m) * ld(m), here
+    # in both tensors.  A: 4 x 3 x 5 inside 6 x 3 x 5 (index 1 is not padded, so 1 and 2 merge);
+    # B = (i1, i2, i0): 3 x 5 x 4 inside 3 x 7 x 4 (index i1 not padded).
+    sizes, perm = (4, 3, 5), (1, 2, 0)
+    lda, ldb = (6, 3, 5), (3, 7, 4)
+    PA = rand(F64, prod(lda), 71)
+    PB0 = rand(F64, prod(ldb), 72)
+    unfused = oracle.transpose(F64, sizes, perm, 0.75, 1.25, PA, PB0.copy(), 1, lda=lda, ldb=ldb)
+    # merged: A is 4 x 15 with leading dimension 6; B is 15 x 4 -- but B's i2 IS padded (7 > 5), so the
+    # merge is illegal in B: the merged call must differ, the legal variant (ldb not padded) must agree.
+    ldb_ok = (3, 5, 4)
+    PB0s = rand(F64, prod(ldb_ok), 73)
+    unfused_ok = oracle.transpose(F64, sizes, perm, 0.75, 1.25, PA, PB0s.copy(), 1, lda=lda, ldb=ldb_ok)
+    fused_ok = oracle.transpose(F64, (4, 15), (1, 0), 0.75, 1.25, PA, PB0s.copy(), 1, lda=(6, 15), ldb=(15, 4))
+    assert np.array_equal(unfused_ok, fused_ok)
+    touched = sorted(b for _, b in oracle.element_pairs(sizes, perm, lda, ldb))
+    touched_fused = sorted(b for _, b in oracle.element_pairs((4, 15), (1, 0), (6, 15), (15, 4)))
+    assert touched != touched_fused and not np.array_equal(unfused[:60], PB0[:60])
+
+
+def test_ld_smaller_than_size_is_rejected():
+    with pytest.raises(ValueError):
+        oracle.transpose(F32, (2, 3), (1, 0), 1.0, 0.0, np.zeros(6, np.float32), np.zeros(6, np.float32), 1,
+                         lda=(1, 3), ldb=(3, 2))
+
+
+# ======================================================================================
+# Mixed precision (paper Table 1, --dataType sd / ds / cz / zc; Section 3).
+# ======================================================================================
+
+A_REAL = {F32_F64: np.float32, F64_F32: np.float64, C64_C128: np.float32, C128_C64: np.float64}
+B_REAL = {F32_F64: np.float64, F64_F32: np.float32, C64_C128: np.float64, C128_C64: np.float32}
+MCOMPS = {F32_F64: 1, F64_F32: 1, C64_C128: 2, C128_C64: 2}
+WIDE = {F32_F64: F64, F64_F32: F64, C64_C128: C128, C128_C64: C128}
+
+
+def mrand(real, n, seed):
+    return np.random.default_rng(seed).uniform(-1, 1, n).astype(real)
+
+
+@pytest.mark.parametrize("dtype", [F32_F64, F64_F32, C64_C128, C128_C64])
+def test_mixed_pure_permutation_is_numpy_cast(dtype):
+    # alpha=1, beta=0: the element is moved and converted; numpy's astype rounds to nearest even.
+    sizes, perm = (3, 4, 2, 5), (2, 0, 3, 1)
+    c = MCOMPS[dtype]
+    A = mrand(A_REAL[dtype], prod(sizes) * c, 81)
+    B = oracle.transpose(dtype, sizes, perm, 1.0, 0.0, A, np.full(prod(sizes) * c, np.nan, B_REAL[dtype]))
+    if c == 1:
+        want = np.transpose(A.reshape(sizes, order="F"), perm).reshape(-1, order="F").astype(B_REAL[dtype])
+    else:
+        z = A.reshape(-1, 2)
+        zz = (z[:, 0] + 1j * z[:, 1]).reshape(sizes, order="F")
+        w = np.transpose(zz, perm).reshape(-1, order="F")
+        want = np.stack([w.real, w.imag], axis=1).reshape(-1).astype(B_REAL[dtype])
+    assert np.array_equal(B, want)
+
+
+@pytest.mark.parametrize("dtype,alpha,beta", [
+    (F32_F64, 0.75, 1.25), (F32_F64, 1.0 / 3.0, 0.0), (F64_F32, 0.75, 1.25), (F64_F32, 1.0 / 3.0, 0.0),
+    (C64_C128, 0.5 + 0.5j, 1.0 + 0.0j), (C128_C64, 0.1 + 0.7j, -0.3 + 0.9j), (C128_C64, 0.3 - 0.2j, 0.0),
+])
+def test_mixed_is_the_double_precision_operation_on_widened_data(dtype, alpha, beta):
+    # The reading: widen (exact), compute as the double-precision operation does, round once to B's type.
+    # The double-precision operation is pinned above; widening and rounding are numpy's.
+    sizes, perm = (4, 3, 5), (1, 2, 0)
+    c = MCOMPS[dtype]
+    A = mrand(A_REAL[dtype], prod(sizes) * c, 91)
+    B0 = mrand(B_REAL[dtype], prod(sizes) * c, 92)
+    got = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy())
+    wide = oracle.transpose(WIDE[dtype], sizes, perm, alpha, beta, A.astype(np.float64), B0.astype(np.float64))
+    assert np.array_equal(got, wide.astype(B_REAL[dtype]))
+
+
+@pytest.mark.parametrize("dtype", [F32_F64, F64_F32])
+def test_mixed_against_exact_rationals(dtype):
+    sizes, perm = (3, 2, 4), (2, 0, 1)
+    A, B0 = mrand(A_REAL[dtype], 24, 95), mrand(B_REAL[dtype], 24, 96)
+    got = oracle.transpose(dtype, sizes, perm, 0.3, -0.7, A, B0.copy())
+    exact = oracle.exact_expected(dtype, sizes, perm, 0.3, -0.7, A, B0)
+    eps64 = float(np.finfo(np.float64).eps)
+    for g, want in zip(got, exact):
+        err = abs(Fraction(float(g)) - want)
+        assert err <= Fraction(ulp(g, B_REAL[dtype])) / 2 + Fraction(eps64) * 4
