@@ -27,8 +27,10 @@ extern "C" {
 
 typedef struct ttc_plan_s* ttc_plan_t;
 
-/* Element types (paper Table 1, --dataType s/d/c; z is not built yet). */
-enum { TTC_F32 = 0, TTC_F64 = 1, TTC_C64 = 2 /* interleaved re,im fp32 */, TTC_C128 = 3 /* rejected */ };
+/* Element types (paper Table 1, --dataType s d c z and the mixed-precision sd ds cz zc, where the
+ * first letter is A's type and the second B's).  Complex elements are interleaved (re, im). */
+enum { TTC_F32 = 0, TTC_F64 = 1, TTC_C64 = 2, TTC_C128 = 3,
+       TTC_F32_F64 = 4, TTC_F64_F32 = 5, TTC_C64_C128 = 6, TTC_C128_C64 = 7 };
 
 enum {
     TTC_OK = 0,
@@ -83,7 +85,10 @@ typedef struct {
     int     align_a, align_b;              /* power of two (<= 128) dividing the byte offset of every run start */
     int64_t num_tiles;                     /* tiles the tensor is cut into */
     int64_t elements;                      /* prod(sizes) */
-    int64_t bytes_moved;                   /* 2 or 3 x tensor bytes: read A, write B, read B iff beta != 0 (paper Eq. 2) */
+    int64_t bytes_moved;                   /* bytes of A read + bytes of B written (+ bytes of B read iff beta != 0; paper Eq. 2) */
+    int64_t span_a, span_b;                /* elements from the first to the last element of A / of B, inclusive (= elements if dense) */
+    int64_t stride_a[TTC_MAX_DIM];         /* element stride of each fused index in A ... */
+    int64_t stride_b[TTC_MAX_DIM];         /* ... and in B */
     int     candidate_index;               /* which candidate is selected */
     int     candidate_count;               /* how many the plan holds (ranked by the heuristic, best first) */
     float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
@@ -105,10 +110,28 @@ ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int*
                            const void* alpha, const void* beta);
 
 /*
+ * The same for tensors that are parts of larger ones, and for every data type of Table 1.
+ *   lda   HOST array of length ndim or NULL: lda[k] >= sizes[k] is the extent of the enclosing tensor
+ *         along index k of A ("leading dimension of each index of A", Table 1 --lda), so A's element
+ *         strides are 1, lda[0], lda[0]*lda[1], ...  NULL = dense.  The sub-tensor starts at the pointer
+ *         later given to ttc_execute (the caller adds the offset of its corner).
+ *   ldb   likewise for B: ldb[j] >= sizes[perm[j]] belongs to index j of B.
+ * Two indices are merged only if they are contiguous in both tensors (footnote of Section 3, stage (1):
+ * ld(i_{m+1}) = size(i_m) * ld(i_m)).  Elements of B outside the sub-tensor are neither read nor written.
+ * Mixed precision (TTC_F32_F64 ...; the paper names the feature and no more): alpha and beta are HOST
+ * doubles (double[2] for the complex pairs), every element is widened to double, the arithmetic of the
+ * data type's epilogue runs in double, and the result is rounded once to B's precision.
+ * For the single types alpha and beta are one scalar of that type, as in ttc_plan_create.
+ */
+ttc_plan_t ttc_plan_create_ex(int dtype, int ndim, const int64_t* sizes, const int* perm,
+                              const int64_t* lda, const int64_t* ldb, const void* alpha, const void* beta);
+
+/*
  * Run the plan: B <- alpha * permute(A) + beta * B (paper Eq. 1).
- *   A, B    DEVICE pointers to prod(sizes) elements each, dense, column-major, aligned to
- *           the element size (vector accesses need no more than that).  They must not
- *           overlap (TTC_ERR_ALIAS).
+ *   A, B    DEVICE pointers to the first element of each tensor: prod(sizes) elements, dense and
+ *           column-major, or span_a / span_b elements for sub-tensors (ttc_plan_create_ex).
+ *           Aligned to the size of their real type (vector accesses need no more than that).
+ *           The two ranges must not overlap (TTC_ERR_ALIAS).
  *   stream  hipStream_t passed as void*; NULL is the default stream.
  * Asynchronous: enqueues one kernel on `stream`, allocates nothing, never synchronises.
  * With beta == 0, B is never read.  Returns the launch status.
@@ -175,10 +198,11 @@ int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src
  * Host-side bounds checker for the planner and the kernels' index arithmetic; it is a test
  * aid, never part of ttc_execute.  Replays the walk of the selected candidate lane by lane on
  * the host, with the index code the kernels are compiled from, and writes to b_from_a[o]
- * (HOST array of prod(sizes) entries) the element offset of A that the candidate moves to
- * element offset o of B (the element map of paper Eq. 1).  Returns TTC_ERR_INTERNAL if any
- * access would leave the tensors or the LDS tile, a vector access would be misaligned, or an
- * element of B would be written twice or not at all.  Cost grows with prod(sizes).
+ * (HOST array of span_b entries, see ttc_plan_info_t; prod(sizes) for dense tensors) the element
+ * offset of A that the candidate moves to element offset o of B (the element map of paper Eq. 1),
+ * -1 where B is not written.  Returns TTC_ERR_INTERNAL if any access would leave the (sub-)tensors
+ * or the LDS tile, or an element of B would be written twice or not at all.  Cost grows with
+ * prod(sizes).
  */
 int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a);
 

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(HERE, "libttc.so")
 
 TTC_MAX_DIM = 6
 TTC_F32, TTC_F64, TTC_C64, TTC_C128 = 0, 1, 2, 3
+TTC_F32_F64, TTC_F64_F32, TTC_C64_C128, TTC_C128_C64 = 4, 5, 6, 7      # A's type, then B's
 TTC_OK = 0
 (TTC_ERR_INVALID_VALUE, TTC_ERR_INVALID_PERM, TTC_ERR_UNSUPPORTED_DTYPE, TTC_ERR_NULL_POINTER,
  TTC_ERR_ALIAS, TTC_ERR_OVERFLOW, TTC_ERR_HIP, TTC_ERR_ALLOC, TTC_ERR_MISALIGNED, TTC_ERR_INTERNAL) = range(1, 11)
@@ -19,7 +20,7 @@ TTC_KERNEL_DIRECT, TTC_KERNEL_LDS = 0, 1
 TTC_EPI_COPY, TTC_EPI_SCALE, TTC_EPI_AXPBY = 0, 1, 2
 
 EXPORTS = (
-    "ttc_plan_create", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
+    "ttc_plan_create", "ttc_plan_create_ex", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
     "ttc_plan_get_info", "ttc_plan_candidate_count", "ttc_plan_select_candidate", "ttc_plan_tune",
     "ttc_plan_tune_pairs", "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
 )
@@ -41,6 +42,8 @@ class ttc_plan_info_t(ctypes.Structure):
         ("run_bytes_a", ctypes.c_int), ("run_bytes_b", ctypes.c_int), ("seg_bytes_a", ctypes.c_int),
         ("seg_bytes_b", ctypes.c_int), ("align_a", ctypes.c_int), ("align_b", ctypes.c_int),
         ("num_tiles", ctypes.c_int64), ("elements", ctypes.c_int64), ("bytes_moved", ctypes.c_int64),
+        ("span_a", ctypes.c_int64), ("span_b", ctypes.c_int64),
+        ("stride_a", ctypes.c_int64 * TTC_MAX_DIM), ("stride_b", ctypes.c_int64 * TTC_MAX_DIM),
         ("candidate_index", ctypes.c_int), ("candidate_count", ctypes.c_int), ("tuned_ms", ctypes.c_float), ("heuristic_cost", ctypes.c_double),
     ]
 
@@ -75,6 +78,8 @@ def lib() -> ctypes.CDLL:
         vp, i, i64p, ip = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)
         L.ttc_plan_create.restype = vp
         L.ttc_plan_create.argtypes = [i, i, i64p, ip, vp, vp]
+        L.ttc_plan_create_ex.restype = vp
+        L.ttc_plan_create_ex.argtypes = [i, i, i64p, ip, i64p, i64p, vp, vp]
         L.ttc_execute.restype = i
         L.ttc_execute.argtypes = [vp, vp, vp, vp]
         L.ttc_plan_destroy.restype = i
@@ -110,7 +115,7 @@ def _scalar(dtype: int, value):
         return None
     if dtype == TTC_F32:
         return ctypes.c_float(float(value))
-    if dtype == TTC_F64:
+    if dtype in (TTC_F64, TTC_F32_F64, TTC_F64_F32):
         return ctypes.c_double(float(value))
     z = complex(value)
     if dtype == TTC_C64:
@@ -139,6 +144,21 @@ def ttc_plan_create(dtype: int, ndim: int, sizes: Sequence[int], perm: Sequence[
     h = lib().ttc_plan_create(int(dtype), int(ndim), c_sizes, c_perm, _ref(a), _ref(b))
     if not h:
         raise TtcError(ttc_last_status(), "ttc_plan_create")
+    return h
+
+
+def ttc_plan_create_ex(dtype: int, ndim: int, sizes: Sequence[int], perm: Sequence[int],
+                       lda: Optional[Sequence[int]] = None, ldb: Optional[Sequence[int]] = None,
+                       alpha=None, beta=None) -> int:
+    """Plan for sub-tensors (leading dimensions per index of A / of B) and for every data type."""
+    c_sizes = (ctypes.c_int64 * max(len(sizes), 1))(*[int(s) for s in sizes])
+    c_perm = (ctypes.c_int * max(len(perm), 1))(*[int(p) for p in perm])
+    c_lda = None if lda is None else (ctypes.c_int64 * max(len(lda), 1))(*[int(x) for x in lda])
+    c_ldb = None if ldb is None else (ctypes.c_int64 * max(len(ldb), 1))(*[int(x) for x in ldb])
+    a, b = _scalar(dtype, alpha), _scalar(dtype, beta)
+    h = lib().ttc_plan_create_ex(int(dtype), int(ndim), c_sizes, c_perm, c_lda, c_ldb, _ref(a), _ref(b))
+    if not h:
+        raise TtcError(ttc_last_status(), "ttc_plan_create_ex")
     return h
 
 
@@ -213,9 +233,12 @@ def ttc_time_ceiling(kind: int, nbytes: int, src_list: Sequence[int], dst_list: 
     return ms.value
 
 
-def ttc_debug_emulate_map(plan: int, elements: int):
-    """Host replay of the selected candidate: list b_from_a of length `elements` (see ttc.h)."""
-    buf = (ctypes.c_int64 * max(int(elements), 1))()
+def ttc_debug_emulate_map(plan: int, elements: Optional[int] = None):
+    """Host replay of the selected candidate: array b_from_a of span_b entries (see ttc.h)."""
+    span = ttc_plan_get_info(plan)["span_b"]
+    if elements is not None and int(elements) < span:
+        raise ValueError("b_from_a needs span_b entries")
+    buf = (ctypes.c_int64 * max(int(span), 1))()
     st = lib().ttc_debug_emulate_map(plan, buf)
     if st != TTC_OK:
         raise TtcError(st, "ttc_debug_emulate_map")

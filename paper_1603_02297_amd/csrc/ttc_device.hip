@@ -29,57 +29,81 @@ namespace ttc {
 //   real:    copy: r = a | scale: r = alpha*a | axpby: t = beta*b, r = fma(alpha, a, t)
 //   complex: product z = s*x as z.re = fma(s.re, x.re, -(s.im*x.im)), z.im = fma(s.re, x.im, s.im*x.re);
 //            scale: r = alpha*a | axpby: r = alpha*a + beta*b componentwise
+// Mixed precision (A and B of different precision): elements are widened to double, the same
+// formulas run in double, the result is rounded once (to nearest even) to B's type.
 // ---------------------------------------------------------------------------------
 struct alignas(8) cfloat { float re, im; };
+struct alignas(8) cdouble { double re, im; };
 
 // Global vectors are only guaranteed element alignment (gfx950 global dwordx2/x4 accesses need
 // no more); the hardware runs them at full rate at any 4-byte boundary.
 template <typename T, int V> struct alignas(alignof(T)) Pack { T v[V]; };
 
-template <typename T, int MODE> struct Epilogue;
+template <typename To, typename From> struct Convert;
+template <typename T> struct Convert<T, T> { __device__ static __forceinline__ T go(T x) { return x; } };
+template <> struct Convert<double, float> { __device__ static __forceinline__ double go(float x) { return (double)x; } };
+template <> struct Convert<float, double> { __device__ static __forceinline__ float go(double x) { return (float)x; } };
+template <> struct Convert<cdouble, cfloat> {
+    __device__ static __forceinline__ cdouble go(cfloat x) { cdouble r; r.re = (double)x.re; r.im = (double)x.im; return r; }
+};
+template <> struct Convert<cfloat, cdouble> {
+    __device__ static __forceinline__ cfloat go(cdouble x) { cfloat r; r.re = (float)x.re; r.im = (float)x.im; return r; }
+};
 
-template <int MODE> struct Epilogue<float, MODE> {
-    float al, be;
-    __device__ explicit Epilogue(const KernelParams& p) : al((float)p.alpha[0]), be((float)p.beta[0]) {}
-    __device__ __forceinline__ float operator()(float a, float b) const
+__device__ __forceinline__ float fused(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fused(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// the arithmetic, in the type it runs in
+template <typename C, int MODE> struct Core {                    // C = float or double
+    C al, be;
+    __device__ explicit Core(const KernelParams& p) : al((C)p.alpha[0]), be((C)p.beta[0]) {}
+    __device__ __forceinline__ C operator()(C a, C b) const
     {
         if (MODE == TTC_EPI_COPY) return a;
         if (MODE == TTC_EPI_SCALE) return al * a;
-        const float t = be * b;
-        return __builtin_fmaf(al, a, t);
+        const C t = be * b;
+        return fused(al, a, t);
     }
 };
 
-template <int MODE> struct Epilogue<double, MODE> {
-    double al, be;
-    __device__ explicit Epilogue(const KernelParams& p) : al(p.alpha[0]), be(p.beta[0]) {}
-    __device__ __forceinline__ double operator()(double a, double b) const
+template <typename Z, typename R, int MODE> struct ComplexCore {  // Z = cfloat / cdouble over R = float / double
+    R ar, ai, br, bi;
+    __device__ explicit ComplexCore(const KernelParams& p)
+        : ar((R)p.alpha[0]), ai((R)p.alpha[1]), br((R)p.beta[0]), bi((R)p.beta[1]) {}
+    __device__ __forceinline__ Z operator()(Z a, Z b) const
     {
         if (MODE == TTC_EPI_COPY) return a;
-        if (MODE == TTC_EPI_SCALE) return al * a;
-        const double t = be * b;
-        return __builtin_fma(al, a, t);
-    }
-};
-
-template <int MODE> struct Epilogue<cfloat, MODE> {
-    float ar, ai, br, bi;
-    __device__ explicit Epilogue(const KernelParams& p)
-        : ar((float)p.alpha[0]), ai((float)p.alpha[1]), br((float)p.beta[0]), bi((float)p.beta[1]) {}
-    __device__ __forceinline__ cfloat operator()(cfloat a, cfloat b) const
-    {
-        if (MODE == TTC_EPI_COPY) return a;
-        cfloat p;
-        p.re = __builtin_fmaf(ar, a.re, -(ai * a.im));
-        p.im = __builtin_fmaf(ar, a.im, ai * a.re);
+        Z p;
+        p.re = fused(ar, a.re, -(ai * a.im));
+        p.im = fused(ar, a.im, ai * a.re);
         if (MODE == TTC_EPI_SCALE) return p;
-        cfloat q;
-        q.re = __builtin_fmaf(br, b.re, -(bi * b.im));
-        q.im = __builtin_fmaf(br, b.im, bi * b.re);
-        cfloat r;
+        Z q;
+        q.re = fused(br, b.re, -(bi * b.im));
+        q.im = fused(br, b.im, bi * b.re);
+        Z r;
         r.re = p.re + q.re;
         r.im = p.im + q.im;
         return r;
+    }
+};
+template <int MODE> struct Core<cfloat, MODE> : ComplexCore<cfloat, float, MODE> { using ComplexCore<cfloat, float, MODE>::ComplexCore; };
+template <int MODE> struct Core<cdouble, MODE> : ComplexCore<cdouble, double, MODE> { using ComplexCore<cdouble, double, MODE>::ComplexCore; };
+
+// type the arithmetic runs in: the common type, or the double-precision one when they differ
+template <typename TA, typename TB> struct Wider;
+template <typename T> struct Wider<T, T> { using type = T; };
+template <> struct Wider<float, double> { using type = double; };
+template <> struct Wider<double, float> { using type = double; };
+template <> struct Wider<cfloat, cdouble> { using type = cdouble; };
+template <> struct Wider<cdouble, cfloat> { using type = cdouble; };
+
+template <typename TA, typename TB, int MODE> struct Epilogue {
+    using C = typename Wider<TA, TB>::type;
+    Core<C, MODE> core;
+    __device__ explicit Epilogue(const KernelParams& p) : core(p) {}
+    __device__ __forceinline__ TB operator()(TA a, TB b) const
+    {
+        return Convert<TB, C>::go(core(Convert<C, TA>::go(a), Convert<C, TB>::go(b)));
     }
 };
 
@@ -104,12 +128,14 @@ __device__ __forceinline__ Pack<T, V> load_pack(const unsigned char* base, int64
     return *reinterpret_cast<const Pack<T, V>*>(base + off);
 }
 
-template <typename T, int MODE, int VA, int VB, bool DIRECT>
-__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const T* __restrict__ A,
-                                                          T* __restrict__ B)
+template <typename TA, typename TB, int MODE, int VA, int VB, bool DIRECT>
+__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const TA* __restrict__ A,
+                                                          TB* __restrict__ B)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int32_t kScale = (int32_t)sizeof(T);
+    constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
+    const Scales sc_a = {kScaleA, kScaleB, kScaleA};     // walk over A; the LDS tile holds elements of A
+    const Scales sc_b = {kScaleB, kScaleB, kScaleA};     // walk over B
     const uint32_t nwave = blockDim.x >> 6;
     const uint32_t n_a = nwave * (uint32_t)p.a.chunk, n_b = DIRECT ? 0u : nwave * (uint32_t)p.b.chunk;
     TileShare* share = reinterpret_cast<TileShare*>(smem);            // two slots, kTileShareBytes in all
@@ -121,11 +147,11 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    build_tables<DIRECT>(p.a, nwave, threadIdx.x, blockDim.x, kScale, tab_a, tabc_a);
-    if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, kScale, tab_b, tabc_b);
-    const LaneState LA = lane_setup<DIRECT>(p.a, lane, kScale);
-    const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, kScale);
-    const Epilogue<T, MODE> epi(p);
+    build_tables<DIRECT>(p.a, nwave, threadIdx.x, blockDim.x, sc_a, tab_a, tabc_a);
+    if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, sc_b, tab_b, tabc_b);
+    const LaneState LA = lane_setup<DIRECT>(p.a, lane, sc_a);
+    const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, sc_b);
+    const Epilogue<TA, TB, MODE> epi(p);
     const TileSeq seq = tile_sequence(p, blockIdx.x);
 
     // Staged kernel: the last wavefront works out where a tile lies (scalar divisions and
@@ -161,31 +187,36 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         const SideLim sla = side_lim(p.a, tl);
         const WalkMask wma = walk_mask(p.a, LA, sla);
         if (DIRECT) {
-            Pack<T, VA> ra[kUnroll], rb[kUnroll];
+            Pack<TA, VA> ra[kUnroll];
+            Pack<TB, VA> rb[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
-                ra[u] = load_pack<T, VA>(At, e.g + LA.g);
-                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<T, VA>(Bt, e.l_or_g2 + LA.g2);
+                ra[u] = load_pack<TA, VA>(At, e.g + LA.g);
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VA>(Bt, e.l_or_g2 + LA.g2);
             };
             auto store = [&](int u, const PosEntry& e) {
-                Pack<T, VA> out;
+                Pack<TB, VA> out;
 #pragma unroll
-                for (int j = 0; j < VA; ++j) out.v[j] = epi(ra[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : ra[u].v[j]);
-                *reinterpret_cast<Pack<T, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
+                for (int j = 0; j < VA; ++j) {
+                    TB old = TB();
+                    if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
+                    out.v[j] = epi(ra[u].v[j], old);
+                }
+                *reinterpret_cast<Pack<TB, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
             };
             walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, store);
             continue;
         }
 
         unsigned char* lds = smem + p.lds_data_off +
-                             (parity & (uint32_t)(p.lds_buffers - 1)) * (uint32_t)(p.lds_tile_elems * kScale);
+                             (parity & (uint32_t)(p.lds_buffers - 1)) * (uint32_t)(p.lds_tile_elems * kScaleA);
         parity ^= 1u;
         // ---- walk 1: A order, global -> LDS
         {
             const int32_t vs = p.a.vec_lds_stride;
-            Pack<T, VA> ra[kUnroll];
-            auto load = [&](int u, const PosEntry& e) { ra[u] = load_pack<T, VA>(At, e.g + LA.g); };
+            Pack<TA, VA> ra[kUnroll];
+            auto load = [&](int u, const PosEntry& e) { ra[u] = load_pack<TA, VA>(At, e.g + LA.g); };
             auto park = [&](int u, const PosEntry& e) {
-                T* dst = reinterpret_cast<T*>(lds + ((int32_t)e.l_or_g2 + LA.l));
+                TA* dst = reinterpret_cast<TA*>(lds + ((int32_t)e.l_or_g2 + LA.l));
 #pragma unroll
                 for (int j = 0; j < VA; ++j) dst[j * vs] = ra[u].v[j];
             };
@@ -198,18 +229,23 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
             const SideLim slb = side_lim(p.b, tl);
             const WalkMask wmb = walk_mask(p.b, LB, slb);
             const int32_t vs = p.b.vec_lds_stride;
-            Pack<T, VB> rb[kUnroll], rl[kUnroll];
+            Pack<TB, VB> rb[kUnroll];
+            Pack<TA, VB> rl[kUnroll];
             auto load = [&](int u, const PosEntry& e) {
-                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<T, VB>(Bt, e.g + LB.g);
-                const T* src = reinterpret_cast<const T*>(lds + ((int32_t)e.l_or_g2 + LB.l));
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VB>(Bt, e.g + LB.g);
+                const TA* src = reinterpret_cast<const TA*>(lds + ((int32_t)e.l_or_g2 + LB.l));
 #pragma unroll
                 for (int j = 0; j < VB; ++j) rl[u].v[j] = src[j * vs];
             };
             auto store = [&](int u, const PosEntry& e) {
-                Pack<T, VB> out;
+                Pack<TB, VB> out;
 #pragma unroll
-                for (int j = 0; j < VB; ++j) out.v[j] = epi(rl[u].v[j], MODE == TTC_EPI_AXPBY ? rb[u].v[j] : rl[u].v[j]);
-                *reinterpret_cast<Pack<T, VB>*>(Bt + (e.g + LB.g)) = out;
+                for (int j = 0; j < VB; ++j) {
+                    TB old = TB();
+                    if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
+                    out.v[j] = epi(rl[u].v[j], old);
+                }
+                *reinterpret_cast<Pack<TB, VB>*>(Bt + (e.g + LB.g)) = out;
             };
             walk<kUnroll>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
         }
@@ -236,46 +272,48 @@ static int device_cus()
 // ---------------------------------------------------------------------------------
 using KernelFn = void (*)(const KernelParams, const void*, void*);
 
-template <typename T, int MODE, int VA, int VB, bool DIRECT>
+template <typename TA, typename TB, int MODE, int VA, int VB, bool DIRECT>
 static hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uint32_t grid, int threads,
                              int lds_bytes, hipStream_t stream)
 {
     if (grid != kp.grid || grid < 1 || grid > kp.num_tiles) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((box_kernel<T, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
-                       kp, static_cast<const T*>(A), static_cast<T*>(B));
+    hipLaunchKernelGGL((box_kernel<TA, TB, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
+                       kp, static_cast<const TA*>(A), static_cast<TB*>(B));
     return hipGetLastError();
 }
 
-template <typename T, int MODE, int VMAX>
+// VMAXA / VMAXB: elements of each type in 16 bytes
+template <typename TA, typename TB, int MODE, int VMAXA, int VMAXB>
 static hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
 {
     KernelParams kp = c.kp;
     const uint32_t grid = launch_grid(c, device_cus());
     set_grid(&kp, grid);
     const int va = kp.a.vec, vb = kp.b.vec;
+    constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct kernel: one width for both sides
     if (c.kernel_class == TTC_KERNEL_DIRECT) {
-        if (va == 1) return launch_one<T, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
-        if (va == 2) return launch_one<T, MODE, 2, 2, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
-        if (va == 4 && VMAX >= 4) return launch_one<T, MODE, (VMAX >= 4 ? 4 : 1), (VMAX >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 1) return launch_one<TA, TB, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 2 && VD >= 2) return launch_one<TA, TB, MODE, (VD >= 2 ? 2 : 1), (VD >= 2 ? 2 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 4 && VD >= 4) return launch_one<TA, TB, MODE, (VD >= 4 ? 4 : 1), (VD >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
         return hipErrorInvalidValue;
     }
 #define TTC_CASE(VA_, VB_)                                                                                   \
-    if (va == VA_ && vb == VB_)                                                                              \
-        return launch_one<T, MODE, (VA_ <= VMAX ? VA_ : 1), (VB_ <= VMAX ? VB_ : 1), false>(kp, A, B, grid,    \
-                                                                                            c.threads, c.lds_bytes, s);
+    if (va == VA_ && vb == VB_ && VA_ <= VMAXA && VB_ <= VMAXB)                                              \
+        return launch_one<TA, TB, MODE, (VA_ <= VMAXA ? VA_ : 1), (VB_ <= VMAXB ? VB_ : 1), false>(          \
+            kp, A, B, grid, c.threads, c.lds_bytes, s);
     TTC_CASE(1, 1) TTC_CASE(1, 2) TTC_CASE(2, 1) TTC_CASE(2, 2)
-    if (VMAX >= 4) { TTC_CASE(1, 4) TTC_CASE(2, 4) TTC_CASE(4, 1) TTC_CASE(4, 2) TTC_CASE(4, 4) }
+    TTC_CASE(1, 4) TTC_CASE(2, 4) TTC_CASE(4, 1) TTC_CASE(4, 2) TTC_CASE(4, 4)
 #undef TTC_CASE
     return hipErrorInvalidValue;
 }
 
-template <typename T, int VMAX>
+template <typename TA, typename TB, int VMAXA, int VMAXB>
 static hipError_t launch_mode(const Problem& P, const Candidate& c, const void* A, void* B, hipStream_t s)
 {
     switch (P.epilogue) {
-    case TTC_EPI_COPY:  return launch_vec<T, TTC_EPI_COPY, VMAX>(c, A, B, s);
-    case TTC_EPI_SCALE: return launch_vec<T, TTC_EPI_SCALE, VMAX>(c, A, B, s);
-    default:            return launch_vec<T, TTC_EPI_AXPBY, VMAX>(c, A, B, s);
+    case TTC_EPI_COPY:  return launch_vec<TA, TB, TTC_EPI_COPY, VMAXA, VMAXB>(c, A, B, s);
+    case TTC_EPI_SCALE: return launch_vec<TA, TB, TTC_EPI_SCALE, VMAXA, VMAXB>(c, A, B, s);
+    default:            return launch_vec<TA, TB, TTC_EPI_AXPBY, VMAXA, VMAXB>(c, A, B, s);
     }
 }
 
@@ -284,9 +322,14 @@ static hipError_t launch(const Problem& P, const Candidate& c, const void* A, vo
     if (c.threads < kWave || c.threads > kMaxThreads || (c.threads % kWave) != 0) return hipErrorInvalidValue;
     if (c.lds_bytes > kMaxLdsBytes) return hipErrorInvalidValue;
     switch (P.dtype) {
-    case TTC_F32: return launch_mode<float, 4>(P, c, A, B, s);
-    case TTC_F64: return launch_mode<double, 2>(P, c, A, B, s);
-    case TTC_C64: return launch_mode<cfloat, 2>(P, c, A, B, s);
+    case TTC_F32:      return launch_mode<float, float, 4, 4>(P, c, A, B, s);
+    case TTC_F64:      return launch_mode<double, double, 2, 2>(P, c, A, B, s);
+    case TTC_C64:      return launch_mode<cfloat, cfloat, 2, 2>(P, c, A, B, s);
+    case TTC_C128:     return launch_mode<cdouble, cdouble, 1, 1>(P, c, A, B, s);
+    case TTC_F32_F64:  return launch_mode<float, double, 4, 2>(P, c, A, B, s);
+    case TTC_F64_F32:  return launch_mode<double, float, 2, 4>(P, c, A, B, s);
+    case TTC_C64_C128: return launch_mode<cfloat, cdouble, 2, 1>(P, c, A, B, s);
+    case TTC_C128_C64: return launch_mode<cdouble, cfloat, 1, 2>(P, c, A, B, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -296,11 +339,10 @@ static int check_buffers(const ttc_plan_s* plan, const void* A, const void* B)
     if (!plan || !A || !B) return TTC_ERR_NULL_POINTER;
     const Problem& P = plan->prob;
     const uintptr_t a = (uintptr_t)A, b = (uintptr_t)B;
-    const int align = (P.dtype == TTC_F32) ? 4 : (P.dtype == TTC_F64 ? 8 : 4);   // complex64: its real type
-    if (a % align || b % align) return TTC_ERR_MISALIGNED;
-    if (P.dtype == TTC_C64 && (a % 8 || b % 8)) return TTC_ERR_MISALIGNED;       // pairs are moved as 8-byte units
-    const uintptr_t bytes = (uintptr_t)P.elements * P.elem_bytes;
-    if (a < b + bytes && b < a + bytes) return TTC_ERR_ALIAS;
+    // element alignment; complex64 pairs move as 8-byte units, complex128 as two of them
+    if (a % (uintptr_t)std::min(P.eb_a, 8) || b % (uintptr_t)std::min(P.eb_b, 8)) return TTC_ERR_MISALIGNED;
+    const uintptr_t bytes_a = (uintptr_t)P.span_a * P.eb_a, bytes_b = (uintptr_t)P.span_b * P.eb_b;
+    if (a < b + bytes_b && b < a + bytes_a) return TTC_ERR_ALIAS;
     return TTC_OK;
 }
 

@@ -115,16 +115,21 @@ struct Candidate {
     KernelParams kp;
 };
 
+// Element kinds of one tensor (the two tensors of a mixed-precision problem differ).
+enum { kKindF32 = 0, kKindF64 = 1, kKindC64 = 2, kKindC128 = 3 };
+
 struct Problem {
-    int      dtype;
-    int      elem_bytes;
+    int      dtype;                  // TTC_* code the plan was created with
+    int      kind_a, kind_b;         // element kind of A and of B
+    int      eb_a, eb_b;             // element bytes of A (also the LDS tile's) and of B
     int      epilogue;               // TTC_EPI_*
     int      ndim;                   // fused
     int64_t  size[kMaxDim];
     int      perm[kMaxDim];
-    int64_t  stride_a[kMaxDim];      // by fused index of A
+    int64_t  stride_a[kMaxDim];      // by fused index of A; from the leading dimensions, dense if none were given
     int64_t  stride_b[kMaxDim];      // by fused index of A (stride it has in B)
     int64_t  elements;
+    int64_t  span_a, span_b;         // elements from the first to the last element of each (sub-)tensor, inclusive
     double   alpha[2], beta[2];
 };
 
@@ -140,7 +145,7 @@ struct ttc_plan_s {
 namespace ttc {
 
 // Host planner.  Returns TTC_OK and fills *out, or a status.
-int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
+int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const int64_t* lda, const int64_t* ldb,
                const void* alpha, const void* beta, ttc_plan_s* out);
 void set_last_status(int status);
 // Workgroups to launch for a candidate on a device with `cus` compute units.

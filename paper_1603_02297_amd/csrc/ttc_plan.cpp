@@ -31,48 +31,88 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
 
 // ---------------------------------------------------------------------------------
-// Normalisation: drop extents of 1, merge indices that stay adjacent and in order.
+// Normalisation: element kinds, strides from the leading dimensions, drop extents of 1, merge
+// indices that stay adjacent and in order and are contiguous in both tensors.
 // ---------------------------------------------------------------------------------
-static int normalise(int dtype, int ndim, const int64_t* sizes, const int* perm,
-                     const void* alpha, const void* beta, Problem* P)
+static int kind_bytes(int kind) { return kind == kKindF32 ? 4 : (kind == kKindC128 ? 16 : 8); }
+
+static bool dtype_kinds(int dtype, int* ka, int* kb)
+{
+    switch (dtype) {
+    case TTC_F32:      *ka = kKindF32;  *kb = kKindF32;  return true;
+    case TTC_F64:      *ka = kKindF64;  *kb = kKindF64;  return true;
+    case TTC_C64:      *ka = kKindC64;  *kb = kKindC64;  return true;
+    case TTC_C128:     *ka = kKindC128; *kb = kKindC128; return true;
+    case TTC_F32_F64:  *ka = kKindF32;  *kb = kKindF64;  return true;
+    case TTC_F64_F32:  *ka = kKindF64;  *kb = kKindF32;  return true;
+    case TTC_C64_C128: *ka = kKindC64;  *kb = kKindC128; return true;
+    case TTC_C128_C64: *ka = kKindC128; *kb = kKindC64;  return true;
+    default: return false;
+    }
+}
+
+static int normalise(int dtype, int ndim, const int64_t* sizes, const int* perm, const int64_t* lda,
+                     const int64_t* ldb, const void* alpha, const void* beta, Problem* P)
 {
     if (!sizes || !perm) return TTC_ERR_NULL_POINTER;
-    if (dtype == TTC_C128) return TTC_ERR_UNSUPPORTED_DTYPE;
-    if (dtype != TTC_F32 && dtype != TTC_F64 && dtype != TTC_C64) return TTC_ERR_UNSUPPORTED_DTYPE;
+    int ka, kb;
+    if (!dtype_kinds(dtype, &ka, &kb)) return TTC_ERR_UNSUPPORTED_DTYPE;
     if (ndim < 1 || ndim > kMaxDim) return TTC_ERR_INVALID_VALUE;
     bool seen[kMaxDim] = {false};
     for (int j = 0; j < ndim; ++j) {
         if (perm[j] < 0 || perm[j] >= ndim || seen[perm[j]]) return TTC_ERR_INVALID_PERM;
         seen[perm[j]] = true;
     }
-    const int elem = (dtype == TTC_F32) ? 4 : 8;
-    int64_t total = 1;
-    for (int k = 0; k < ndim; ++k) {
+    int64_t total = 1, alloc_a = 1, alloc_b = 1;
+    for (int k = 0; k < ndim; ++k)
         if (sizes[k] < 1) return TTC_ERR_INVALID_VALUE;
+    for (int k = 0; k < ndim; ++k) {
+        const int64_t la = lda ? lda[k] : sizes[k], lb = ldb ? ldb[k] : sizes[perm[k]];
+        if (la < sizes[k] || lb < sizes[perm[k]]) return TTC_ERR_INVALID_VALUE;
         if (total > (INT64_MAX / 16) / sizes[k]) return TTC_ERR_OVERFLOW;
+        if (alloc_a > (INT64_MAX / 16) / la || alloc_b > (INT64_MAX / 16) / lb) return TTC_ERR_OVERFLOW;
         total *= sizes[k];
+        alloc_a *= la;
+        alloc_b *= lb;
+    }
+    // strides in the caller's index space (paper Table 1, --lda / --ldb: the tensor may be a part of
+    // a larger one whose extents are the leading dimensions)
+    int64_t sa[kMaxDim], sb[kMaxDim];          // sa by index of A; sb by index (position) of B
+    sa[0] = 1; sb[0] = 1;
+    for (int k = 1; k < ndim; ++k) {
+        sa[k] = sa[k - 1] * (lda ? lda[k - 1] : sizes[k - 1]);
+        sb[k] = sb[k - 1] * (ldb ? ldb[k - 1] : sizes[perm[k - 1]]);
+    }
+    int64_t span_a = 1, span_b = 1;
+    for (int k = 0; k < ndim; ++k) {
+        span_a += (sizes[k] - 1) * sa[k];
+        span_b += (sizes[perm[k]] - 1) * sb[k];
     }
 
     // 1. drop size-1 extents (they contribute offset 0 on both sides)
     int newidx[kMaxDim], m = 0;
-    int64_t s1[kMaxDim];
+    int64_t s1[kMaxDim], sa1[kMaxDim];
     for (int k = 0; k < ndim; ++k) {
         newidx[k] = -1;
-        if (sizes[k] > 1) { newidx[k] = m; s1[m] = sizes[k]; ++m; }
+        if (sizes[k] > 1) { newidx[k] = m; s1[m] = sizes[k]; sa1[m] = sa[k]; ++m; }
     }
     int p1[kMaxDim], mp = 0;
+    int64_t sb1[kMaxDim];                      // by kept position of B
     for (int j = 0; j < ndim; ++j)
-        if (sizes[perm[j]] > 1) p1[mp++] = newidx[perm[j]];
-    if (m == 0) { m = 1; s1[0] = 1; p1[0] = 0; }
+        if (sizes[perm[j]] > 1) { p1[mp] = newidx[perm[j]]; sb1[mp] = sb[j]; ++mp; }
+    if (m == 0) { m = 1; s1[0] = 1; p1[0] = 0; sa1[0] = 1; sb1[0] = 1; }
 
-    // 2. merge: B positions j, j+1 holding A indices a, a+1 form one index (dense tensors
-    //    always satisfy the leading-dimension condition of the paper's footnote).
-    int group_start[kMaxDim], group_len[kMaxDim], ng = 0;     // groups in B order
+    // 2. merge: B positions j, j+1 holding A indices a, a+1 form one index if the pair is contiguous in
+    //    both tensors: ld(i_{m+1}) = size(i_m) * ld(i_m), the condition of the footnote in Section 3.
+    int group_start[kMaxDim], group_len[kMaxDim], group_pos[kMaxDim], ng = 0;     // groups in B order
     for (int j = 0; j < m;) {
         int len = 1;
-        while (j + len < m && p1[j + len] == p1[j + len - 1] + 1) ++len;
+        while (j + len < m && p1[j + len] == p1[j + len - 1] + 1 &&
+               sa1[p1[j + len]] == sa1[p1[j + len - 1]] * s1[p1[j + len - 1]] &&
+               sb1[j + len] == sb1[j + len - 1] * s1[p1[j + len - 1]]) ++len;
         group_start[ng] = p1[j];
         group_len[ng] = len;
+        group_pos[ng] = j;
         ++ng;
         j += len;
     }
@@ -84,33 +124,33 @@ static int normalise(int dtype, int ndim, const int64_t* sizes, const int* perm,
         rank_of_group[g] = r;
     }
     P->dtype = dtype;
-    P->elem_bytes = elem;
+    P->kind_a = ka; P->kind_b = kb;
+    P->eb_a = kind_bytes(ka); P->eb_b = kind_bytes(kb);
     P->ndim = ng;
     P->elements = total;
+    P->span_a = span_a; P->span_b = span_b;
     for (int k = 0; k < kMaxDim; ++k) { P->size[k] = 0; P->perm[k] = 0; P->stride_a[k] = 0; P->stride_b[k] = 0; }
     for (int g = 0; g < ng; ++g) {
         int64_t sz = 1;
         for (int i = 0; i < group_len[g]; ++i) sz *= s1[group_start[g] + i];
-        P->size[rank_of_group[g]] = sz;
-        P->perm[g] = rank_of_group[g];
+        const int r = rank_of_group[g];
+        P->size[r] = sz;
+        P->perm[g] = r;
+        P->stride_a[r] = sa1[group_start[g]];
+        P->stride_b[r] = sb1[group_pos[g]];
     }
-    int64_t st = 1;
-    for (int k = 0; k < ng; ++k) { P->stride_a[k] = st; st *= P->size[k]; }
-    st = 1;
-    for (int j = 0; j < ng; ++j) { P->stride_b[P->perm[j]] = st; st *= P->size[P->perm[j]]; }
 
-    // scalars (defaults of the paper's Table 1: alpha = 1, beta = 0)
+    // scalars (defaults of the paper's Table 1: alpha = 1, beta = 0), in the precision the arithmetic
+    // runs in: the data type's, or double for mixed precision
+    const bool wide = (ka == kKindF64 || ka == kKindC128 || kb == kKindF64 || kb == kKindC128);
+    const bool cplx = (ka == kKindC64 || ka == kKindC128);
+    auto read = [&](const void* src, double* dst) {
+        if (wide) { dst[0] = ((const double*)src)[0]; dst[1] = cplx ? ((const double*)src)[1] : 0.0; }
+        else      { dst[0] = ((const float*)src)[0];  dst[1] = cplx ? ((const float*)src)[1] : 0.0; }
+    };
     P->alpha[0] = 1.0; P->alpha[1] = 0.0; P->beta[0] = 0.0; P->beta[1] = 0.0;
-    if (alpha) {
-        if (dtype == TTC_F32) P->alpha[0] = *(const float*)alpha;
-        else if (dtype == TTC_F64) P->alpha[0] = *(const double*)alpha;
-        else { P->alpha[0] = ((const float*)alpha)[0]; P->alpha[1] = ((const float*)alpha)[1]; }
-    }
-    if (beta) {
-        if (dtype == TTC_F32) P->beta[0] = *(const float*)beta;
-        else if (dtype == TTC_F64) P->beta[0] = *(const double*)beta;
-        else { P->beta[0] = ((const float*)beta)[0]; P->beta[1] = ((const float*)beta)[1]; }
-    }
+    if (alpha) read(alpha, P->alpha);
+    if (beta) read(beta, P->beta);
     const bool beta0 = (P->beta[0] == 0.0 && P->beta[1] == 0.0);
     const bool alpha1 = (P->alpha[0] == 1.0 && P->alpha[1] == 0.0);
     P->epilogue = beta0 ? (alpha1 ? TTC_EPI_COPY : TTC_EPI_SCALE) : TTC_EPI_AXPBY;
@@ -147,7 +187,7 @@ static int pick_extent(int64_t s, int64_t want, int mult, int style = 0, int nic
 
 // Leading indices of one tensor, in that tensor's order, until the contiguous run they
 // span reaches `target` elements.  All but the last are taken whole.
-static void build_group(const Problem& P, const int* order, int64_t target, int vec, int max_dims, int* t,
+static void build_group(const Problem& P, const int* order, int eb, int64_t target, int vec, int max_dims, int* t,
                         int style = 0)
 {
     for (int k = 0; k < kMaxDim; ++k) t[k] = 1;
@@ -159,23 +199,11 @@ static void build_group(const Problem& P, const int* order, int64_t target, int 
         const int mult = (i == 0) ? vec : 1;
         int ext;
         if (P.size[k] <= need + need / 2) ext = (int)P.size[k];
-        else ext = pick_extent(P.size[k], need, mult, style, 64 / P.elem_bytes);
+        else ext = pick_extent(P.size[k], need, mult, style, std::max(1, 64 / eb));
         t[k] = ext;
         run *= ext;
         if (ext < P.size[k]) break;
     }
-}
-
-// Contiguous run (elements) the box spans in a tensor whose index order is `order`.
-static int64_t box_run(const Problem& P, const int* order, const int* t)
-{
-    int64_t run = 1;
-    for (int i = 0; i < P.ndim; ++i) {
-        const int k = order[i];
-        run *= t[k];
-        if (t[k] < P.size[k]) break;
-    }
-    return run;
 }
 
 // ---------------------------------------------------------------------------------
@@ -193,8 +221,8 @@ struct WalkSpec { int nd; DigitSpec d[kBoxDims]; };
 // Digits of one walk in the walk's own order.  With `merge`, the leading indices that lie whole
 // inside the box fuse with their successor into one flat digit (tile-level index fusion); an
 // index whose bit is set in `no_tail` may not be appended to a chain.
-static bool build_walk(const Problem& P, const int* order, const int* t, bool merge, unsigned no_tail,
-                       WalkSpec* w)
+static bool build_walk(const Problem& P, const int* order, const int64_t* stride, const int* t, bool merge,
+                       unsigned no_tail, WalkSpec* w)
 {
     w->nd = 0;
     bool leading = true;
@@ -205,7 +233,7 @@ static bool build_walk(const Problem& P, const int* order, const int* t, bool me
             DigitSpec& d = w->d[0];
             const int prev = d.outer_dim;
             if (i > 0 && order[i - 1] == prev && t[prev] == P.size[prev] && !(no_tail & (1u << k)) &&
-                (int64_t)d.tile * t[k] < 65536) {
+                stride[k] == stride[prev] * P.size[prev] && (int64_t)d.tile * t[k] < 65536) {
                 d.inner = d.tile;
                 d.tile *= t[k];
                 d.outer_dim = k;
@@ -226,9 +254,10 @@ static bool build_walk(const Problem& P, const int* order, const int* t, bool me
 
 // Largest vector width (elements) for a walk: vectors lie along the first digit and must not
 // straddle its end, in whole tiles and in the tiles the tensor's edge cuts.
-static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit)
+static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit, int eb, bool unit_stride)
 {
-    int v = std::min(limit, 16 / P.elem_bytes);
+    if (!unit_stride) return 1;      // a dropped size-1 index with a padded leading dimension: no stride-1 index
+    int v = std::min(limit, std::max(1, 16 / eb));
     const DigitSpec& d = w.d[0];
     const int64_t rest = P.size[d.outer_dim] % t[d.outer_dim];
     while (v > 1 && (d.tile % v != 0 || (rest * d.inner) % v != 0)) v /= 2;
@@ -236,7 +265,7 @@ static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit
 }
 
 // Lane mapping: which sub-box of the tile one wavefront instruction covers.
-static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int* n_iter_out, int* lanes_out)
+static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int eb, int* n_iter_out, int* lanes_out)
 {
     int best_lane[kBoxDims] = {1, 1, 1, 1};
     int64_t best_cost = INT64_MAX;
@@ -273,7 +302,7 @@ static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int* n_iter_out
         }
         // short segments along the stride-1 index cost coalescing: ask for a 128-byte line unless the tile is
         // shorter; an overhanging sub-box makes every position test its bounds
-        const bool short_seg = (l0 < t0) && (l0 * P.elem_bytes < 128);
+        const bool short_seg = (l0 < t0) && (l0 * eb < 128);
         const int64_t cost = iters * (short_seg ? 8 : 4) * (ragged ? 5 : 4);
         if (cost < best_cost || (cost == best_cost && l0 > best_lane[0])) {
             best_cost = cost;
@@ -343,7 +372,7 @@ static bool fill_side(const Problem& P, const WalkSpec& w, int vec, const int* s
 // ---------------------------------------------------------------------------------
 static int bank_multiplicity(const Problem& P, const Side& s, int banks)
 {
-    const int words = P.elem_bytes / 4;
+    const int words = P.eb_a / 4;               // the LDS tile holds elements of A
     int worst = 1;
     std::vector<int64_t> addr(kWave);
     for (int j = 0; j < s.vec; ++j) {
@@ -398,7 +427,7 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
             }
         }
         L.elems = (int)run;
-        if ((int64_t)L.elems * P.elem_bytes > kMaxLdsBytes) continue;
+        if ((int64_t)L.elems * P.eb_a > kMaxLdsBytes) continue;
         Side sa, sb;
         if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &sa)) continue;
         if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &sb)) continue;
@@ -498,10 +527,12 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     };
     if (direct) {
         if (nslots == 0) trivial_walk(&wa);
-        else if (!build_walk(P, order_a, t, false, 0u, &wa)) return false;
-        const int v = (nslots == 0) ? 1 : walk_vec(P, wa, t, vec_limit);
+        else if (!build_walk(P, order_a, P.stride_a, t, false, 0u, &wa)) return false;
+        const int eb_max = std::max(P.eb_a, P.eb_b);        // every lane stores what it loaded: one width for both
+        const int v = (nslots == 0) ? 1 : walk_vec(P, wa, t, vec_limit, eb_max,
+                                                  P.stride_a[wa.d[0].first_dim] == 1 && P.stride_b[wa.d[0].first_dim] == 1);
         int n_iter, lanes;
-        choose_lanes(P, &wa, v, &n_iter, &lanes);
+        choose_lanes(P, &wa, v, eb_max, &n_iter, &lanes);
         if (!fill_side(P, wa, v, slot_of_dim, nullptr, false, &kp.a)) return false;
         kp.b = kp.a;
         wb = wa;
@@ -513,7 +544,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         C.lds_conflict_a = C.lds_conflict_b = 0;
     } else {
         if (nslots == 0) return false;
-        if (!build_walk(P, order_a, t, merge_a, 0u, &wa)) return false;
+        if (!build_walk(P, order_a, P.stride_a, t, merge_a, 0u, &wa)) return false;
         // LDS chains from A's merged digit; B may chain its own leading indices only where that
         // does not give an index a second predecessor or a second successor
         int next_in_chain[kMaxDim];
@@ -526,7 +557,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
                 if (k < wa.d[0].outer_dim) { next_in_chain[k] = k + 1; is_head[k + 1] = false; a_nonlast |= 1u << k; }
             }
         const bool b_may_merge = merge_b && !(a_nonlast & (1u << order_b[0]));
-        if (!build_walk(P, order_b, t, b_may_merge, in_a_chain, &wb)) return false;
+        if (!build_walk(P, order_b, P.stride_b, t, b_may_merge, in_a_chain, &wb)) return false;
         if (wb.d[0].first_dim != wb.d[0].outer_dim) {
             int prev = -1;
             for (int i = 0; i < P.ndim; ++i) {
@@ -536,11 +567,11 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
                 if (k == wb.d[0].outer_dim) break;
             }
         }
-        const int va = walk_vec(P, wa, t, vec_limit);
-        const int vb = walk_vec(P, wb, t, vec_limit);
+        const int va = walk_vec(P, wa, t, vec_limit, P.eb_a, P.stride_a[wa.d[0].first_dim] == 1);
+        const int vb = walk_vec(P, wb, t, vec_limit, P.eb_b, P.stride_b[wb.d[0].first_dim] == 1);
         int ia, la_, ib, lb_;
-        choose_lanes(P, &wa, va, &ia, &la_);
-        choose_lanes(P, &wb, vb, &ib, &lb_);
+        choose_lanes(P, &wa, va, P.eb_a, &ia, &la_);
+        choose_lanes(P, &wb, vb, P.eb_b, &ib, &lb_);
         LdsLayout L;
         bool cached = false;
         LayoutKey key;
@@ -558,9 +589,9 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &kp.b)) return false;
         C.kernel_class = TTC_KERNEL_LDS;
         kp.lds_data_off = (int)round_up(24 * (int64_t)(kp.a.n_iter + kp.b.n_iter), 16);
-        kp.lds_tile_elems = (int)round_up(L.elems, 16 / P.elem_bytes);
+        kp.lds_tile_elems = (int)round_up(L.elems, std::max(1, 16 / P.eb_a));
         kp.lds_buffers = nbuf;
-        C.lds_bytes = kp.lds_data_off + nbuf * kp.lds_tile_elems * P.elem_bytes;
+        C.lds_bytes = kp.lds_data_off + nbuf * kp.lds_tile_elems * P.eb_a;
         if (C.lds_bytes > kMaxLdsBytes) return false;
         C.lds_conflict_a = L.conflict_a;
         C.lds_conflict_b = L.conflict_b;
@@ -639,27 +670,29 @@ static AccessShape access_shape(const Problem& P, const Candidate& C)
         int order[kMaxDim];
         for (int k = 0; k < kMaxDim; ++k) order[k] = side ? ((k < P.ndim) ? P.perm[k] : k) : k;
         const int64_t* stride = side ? P.stride_b : P.stride_a;
+        const int eb = side ? P.eb_b : P.eb_a;
         int64_t run = 1, g = 0;
         bool open = true;
         for (int i = 0; i < P.ndim; ++i) {
             const int k = order[i];
+            if (open && stride[k] != run) open = false;
             if (open) {
                 run *= C.kp.tile[k];
                 if (C.kp.tile[k] < P.size[k]) open = false;
             } else if (P.size[k] > 1) {
-                int64_t a = stride[k] * P.elem_bytes, b = g;
+                int64_t a = stride[k] * eb, b = g;
                 while (b) { const int64_t t = a % b; a = b; b = t; }
                 g = a;
             }
         }
-        int64_t a = run * P.elem_bytes, b = g;
+        int64_t a = run * eb, b = g;
         while (b) { const int64_t t = a % b; a = b; b = t; }
         int al = 1;
         while (al < 128 && a % (2 * al) == 0) al *= 2;
-        r.run[side] = (int)std::min<int64_t>(run * P.elem_bytes, INT32_MAX);
+        r.run[side] = (int)std::min<int64_t>(run * eb, INT32_MAX);
         r.align[side] = al;
         const Side& s = (side && !direct) ? C.kp.b : C.kp.a;
-        r.seg[side] = segment_elems(s, side && direct) * P.elem_bytes;
+        r.seg[side] = segment_elems(s, side && direct) * eb;
     }
     return r;
 }
@@ -670,7 +703,7 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
     // workloads plus 2-D to 6-D problems with odd, small and large extents; log-linear least squares
     // weighted towards the fast candidates), rounded, with guard rails outside the measured range.
     const KernelParams& kp = C.kp;
-    const double eb = P.elem_bytes;
+    const double eb = std::max(P.eb_a, P.eb_b), eb_a = P.eb_a, eb_b = P.eb_b;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
     auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
     double volume = 1, padded = 1;
@@ -690,8 +723,8 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
     e += 0.03 * (1.0 - sh.align[0] / 128.0) * 128.0 / run_a + 0.09 * (1.0 - sh.align[1] / 128.0) * 128.0 / run_b;
     e += 0.017 * oct_below(seg_a, 256.0) + 0.020 * oct_below(seg_b, 256.0);
     e += 0.10 * oct_below(seg_a, 64.0) + 0.32 * oct_below(seg_b, 64.0);
-    e += (kp.a.vec * eb >= 16 ? 0.0 : (kp.a.vec * eb >= 8 ? 0.016 : 0.047));
-    e += (vec_b * eb >= 16 ? 0.0 : (vec_b * eb >= 8 ? 0.007 : 0.024));
+    e += (kp.a.vec * eb_a >= 16 ? 0.0 : (kp.a.vec * eb_a >= 8 ? 0.016 : 0.047));
+    e += (vec_b * eb_b >= 16 ? 0.0 : (vec_b * eb_b >= 8 ? 0.007 : 0.024));
     e += 0.25 * (padded - 1.0);                                         // lanes idle in remainder tiles
     // tile size and occupancy
     const double lo = direct ? 16384.0 : 8192.0;
@@ -743,9 +776,9 @@ static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Can
     v.back().score = heuristic_cost(P, c);
 }
 
-static int max_vec(const Problem& P, int64_t extent)
+static int max_vec(int eb, int64_t extent)
 {
-    int v = 16 / P.elem_bytes;
+    int v = std::max(1, 16 / eb);
     while (v > 1 && extent % v != 0) v /= 2;
     return v;
 }
@@ -758,7 +791,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
 {
     LayoutCache cache;
     const int n = P.ndim;
-    const int eb = P.elem_bytes;
+    const int eb = std::max(P.eb_a, P.eb_b);
     int order_a[kMaxDim], order_b[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < n) ? P.perm[k] : k; }
     const bool stride1_fixed = (P.perm[0] == 0);
@@ -767,7 +800,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     // -- direct candidates: only when the stride-1 index keeps its place.  The box takes leading
     //    indices of A and of B so that both sides move a few long contiguous chunks per tile.
     if (stride1_fixed) {
-        const int vfull = max_vec(P, P.size[0]);
+        const int vfull = max_vec(eb, P.size[0]);
         const int64_t chunk_bytes[6] = {16384, 4096, 32768, 8192, 2048, 65536};
         for (int vsel = 0; vsel < 2; ++vsel) {
             if (vsel == 1 && vfull == 1) break;
@@ -776,8 +809,8 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
             for (int64_t ra : chunk_bytes)
                 for (int64_t rb : chunk_bytes) {
                     int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                    build_group(P, order_a, ra / eb, v, kBoxDims, ta, style);
-                    build_group(P, order_b, rb / eb, v, kBoxDims, tb, style);
+                    build_group(P, order_a, P.eb_a, ra / P.eb_a, v, kBoxDims, ta, style);
+                    build_group(P, order_b, P.eb_b, rb / P.eb_b, v, kBoxDims, tb, style);
                     int64_t vol = 1;
                     int spanned = 0;
                     for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
@@ -797,8 +830,8 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     // -- staged candidates: a box spanning the leading indices of A and of B
     if (n >= 2) {
         const int p0 = P.perm[0];
-        const int va_full = max_vec(P, P.size[0]);
-        const int vb_full = max_vec(P, P.size[p0]);
+        const int va_full = max_vec(P.eb_a, P.size[0]);
+        const int vb_full = max_vec(P.eb_b, P.size[p0]);
         const int64_t run_bytes[8] = {256, 512, 128, 1024, 64, 2048, 4096, 8192};
         for (int vsel = 0; vsel < 2; ++vsel) {
             const int va = vsel == 0 ? va_full : 1;       // multiples the group builder keeps on the stride-1 extents
@@ -809,14 +842,14 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                 for (int64_t ra : run_bytes)
                     for (int64_t rb : run_bytes) {
                         int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                        build_group(P, order_a, ra / eb, va, md, ta, style);
-                        build_group(P, order_b, rb / eb, vb, md, tb, style);
+                        build_group(P, order_a, P.eb_a, std::max<int64_t>(1, ra / P.eb_a), va, md, ta, style);
+                        build_group(P, order_b, P.eb_b, std::max<int64_t>(1, rb / P.eb_b), vb, md, tb, style);
                         int64_t vol = 1;
                         int spanned = 0;
                         for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
                         for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
                         if (spanned > kBoxDims) continue;
-                        if (vol * eb > kMaxLdsBytes - 2048) continue;
+                        if (vol * P.eb_a > kMaxLdsBytes - 2048) continue;
                         if (vol * eb < 2048 && md > 1 && vol < P.elements) continue;
                         for (int nbuf = 2; nbuf >= 1; --nbuf) {
                             if (nbuf == 1 && vol * eb < 8192) continue;     // small tiles can afford two buffers
@@ -836,17 +869,17 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     // -- last resort so that every problem has a candidate: scalar direct walk in A order
     if (out.empty() || n == 1) {
         int t[kMaxDim];
-        build_group(P, order_a, 16384 / eb, 1, kBoxDims, t);
+        build_group(P, order_a, P.eb_a, 16384 / eb, 1, kBoxDims, t);
         Candidate c;
         if (make_candidate(P, t, 1, true, 256, 8, order_a, 1, &c)) add_candidate(P, out, c);
     }
 }
 
-int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm,
+int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const int64_t* lda, const int64_t* ldb,
                const void* alpha, const void* beta, ttc_plan_s* plan)
 {
     Problem& P = plan->prob;
-    int st = normalise(dtype, ndim, sizes, perm, alpha, beta, &P);
+    int st = normalise(dtype, ndim, sizes, perm, lda, ldb, alpha, beta, &P);
     if (st != TTC_OK) return st;
     plan->cands.clear();
     enumerate(P, plan->cands);
@@ -881,11 +914,17 @@ extern "C" {
 ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int* perm,
                            const void* alpha, const void* beta)
 {
+    return ttc_plan_create_ex(dtype, ndim, sizes, perm, nullptr, nullptr, alpha, beta);
+}
+
+ttc_plan_t ttc_plan_create_ex(int dtype, int ndim, const int64_t* sizes, const int* perm,
+                              const int64_t* lda, const int64_t* ldb, const void* alpha, const void* beta)
+{
     ttc_plan_s* plan = new (std::nothrow) ttc_plan_s();
     if (!plan) { ttc::set_last_status(TTC_ERR_ALLOC); return nullptr; }
     int st;
     try {
-        st = ttc::build_plan(dtype, ndim, sizes, perm, alpha, beta, plan);
+        st = ttc::build_plan(dtype, ndim, sizes, perm, lda, ldb, alpha, beta, plan);
     } catch (const std::bad_alloc&) {
         st = TTC_ERR_ALLOC;
     } catch (...) {
@@ -963,7 +1002,10 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     }
     out->num_tiles = C.kp.num_tiles;
     out->elements = P.elements;
-    out->bytes_moved = (P.epilogue == TTC_EPI_AXPBY ? 3 : 2) * P.elements * P.elem_bytes;
+    out->bytes_moved = P.elements * (P.eb_a + (P.epilogue == TTC_EPI_AXPBY ? 2 : 1) * P.eb_b);
+    out->span_a = P.span_a;
+    out->span_b = P.span_b;
+    for (int k = 0; k < P.ndim; ++k) { out->stride_a[k] = P.stride_a[k]; out->stride_b[k] = P.stride_b[k]; }
     out->candidate_index = plan->selected;
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
@@ -987,8 +1029,9 @@ int ttc_plan_select_candidate(ttc_plan_t plan, int index)
 
 // Host-side bounds checker: replays the selected candidate's walk (the same index code the
 // kernels run) lane by lane and records, for every offset of B, the offset of A that lands
-// there.  Fails on any access outside the tensors or the LDS tile, any misaligned vector, any
-// element of B written twice or never, and any LDS slot read before it was written.
+// there.  Fails on any access outside the (sub-)tensors or the LDS tile, any access that is
+// not element-aligned, any element of B written twice or never, and any LDS slot read before
+// it was written.
 int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
 {
     using namespace ttc;
@@ -997,15 +1040,25 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     const Candidate& C = plan->cands[plan->selected];
     KernelParams p = C.kp;
     set_grid(&p, launch_grid(C, 256));
-    const int64_t total = P.elements, total_bytes = P.elements * P.elem_bytes;
-    const int32_t eb = P.elem_bytes;
-    for (int64_t i = 0; i < total; ++i) b_from_a[i] = -1;
+    const int32_t eba = P.eb_a, ebb = P.eb_b;
+    for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
     const uint32_t nwave = (uint32_t)C.threads / kWave;
     if (nwave < 1 || C.threads % kWave) return TTC_ERR_INTERNAL;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
     if ((p.lds_buffers != 1 && p.lds_buffers != 2) ||
-        p.lds_data_off + p.lds_buffers * (int64_t)p.lds_tile_elems * eb != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
+        p.lds_data_off + p.lds_buffers * (int64_t)p.lds_tile_elems * eba != C.lds_bytes || C.lds_bytes > kMaxLdsBytes)
         return TTC_ERR_INTERNAL;
+    // is this element offset an element of the sub-tensor?  (decode by strides, slowest index first)
+    auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
+        if (off < 0) return false;
+        for (int i = P.ndim - 1; i >= 0; --i) {
+            const int k = b_side ? P.perm[i] : i;
+            const int64_t c = off / stride[k];
+            if (c >= P.size[k]) return false;
+            off -= c * stride[k];
+        }
+        return off == 0;
+    };
     // position tables, as a workgroup builds them
     const uint32_t ta = nwave * (uint32_t)p.a.chunk, tbn = direct ? 0u : nwave * (uint32_t)p.b.chunk;
     if (kTileShareBytes + (int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
@@ -1013,44 +1066,48 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
         return TTC_ERR_INTERNAL;
     if (!direct && (p.b.chunk_rem < 1 || p.b.chunk_rem > (int)nwave ||
                     (p.b.chunk - 1) * (int)nwave + p.b.chunk_rem != p.b.n_iter)) return TTC_ERR_INTERNAL;
+    const Scales sc_a = {eba, ebb, eba};       // walk over A (direct: g2 addresses B)
+    const Scales sc_b = {ebb, ebb, eba};       // walk over B of the staged kernel
     std::vector<PosEntry> tab_a(ta), tab_b(tbn);
     std::vector<PosCoord> tabc_a(ta), tabc_b(tbn);
     for (uint32_t th = 0; th < (uint32_t)C.threads; ++th) {
-        if (direct) build_tables<true>(p.a, nwave, th, (uint32_t)C.threads, eb, tab_a.data(), tabc_a.data());
+        if (direct) build_tables<true>(p.a, nwave, th, (uint32_t)C.threads, sc_a, tab_a.data(), tabc_a.data());
         else {
-            build_tables<false>(p.a, nwave, th, (uint32_t)C.threads, eb, tab_a.data(), tabc_a.data());
-            build_tables<false>(p.b, nwave, th, (uint32_t)C.threads, eb, tab_b.data(), tabc_b.data());
+            build_tables<false>(p.a, nwave, th, (uint32_t)C.threads, sc_a, tab_a.data(), tabc_a.data());
+            build_tables<false>(p.b, nwave, th, (uint32_t)C.threads, sc_b, tab_b.data(), tabc_b.data());
         }
     }
 
-    const int64_t lds_bytes = (int64_t)p.lds_tile_elems * eb;
-    std::vector<int64_t> lds((size_t)p.lds_tile_elems);          // which byte offset of A each slot holds
+    const int64_t lds_bytes = (int64_t)p.lds_tile_elems * eba;
+    std::vector<int64_t> lds((size_t)p.lds_tile_elems);          // which element offset of A each slot holds
     std::vector<char> seen(p.num_tiles, 0);
     bool bad = false;
     auto fail = [&]() { bad = true; };
     auto nop = [](int, const PosEntry&) {};
+    int64_t written = 0;
     for (uint32_t wg = 0; wg < p.grid && !bad; ++wg) {
         const TileSeq seq = tile_sequence(p, wg);
         for (uint32_t tile = seq.first; tile < seq.end && !bad; tile += seq.step) {
             if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
             seen[tile] = 1;
             const TileBase tb = tile_base(p, tile);
-            const int64_t base_a = tb.a * eb, base_b = tb.b * eb;
+            const int64_t base_a = tb.a * eba, base_b = tb.b * ebb;
             const TileLim tl = tile_lim(p, tile);
             const SideLim la = side_lim(p.a, tl);
             if (direct) {
                 for (uint32_t wave = 0; wave < nwave; ++wave)
                     for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                        const LaneState L = lane_setup<true>(p.a, lane, eb);
+                        const LaneState L = lane_setup<true>(p.a, lane, sc_a);
                         const WalkMask wm = walk_mask(p.a, L, la);
                         auto st = [&](int, const PosEntry& e) {
                             const int64_t oa = base_a + e.g + L.g, ob = base_b + e.l_or_g2 + L.g2;
-                            const int64_t w = (int64_t)p.a.vec * eb;
-                            if (oa % w || ob % w) return fail();
-                            if (oa < 0 || oa + w > total_bytes || ob < 0 || ob + w > total_bytes) return fail();
+                            if (oa % eba || ob % ebb) return fail();
                             for (int j = 0; j < p.a.vec; ++j) {
-                                if (b_from_a[ob / eb + j] != -1) return fail();
-                                b_from_a[ob / eb + j] = oa / eb + j;
+                                const int64_t ea = oa / eba + j, eo = ob / ebb + j;
+                                if (!inside(ea, P.stride_a, false) || !inside(eo, P.stride_b, true)) return fail();
+                                if (b_from_a[eo] != -1) return fail();
+                                b_from_a[eo] = ea;
+                                ++written;
                             }
                         };
                         walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
@@ -1060,19 +1117,20 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             std::fill(lds.begin(), lds.end(), (int64_t)-1);
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                    const LaneState L = lane_setup<false>(p.a, lane, eb);
+                    const LaneState L = lane_setup<false>(p.a, lane, sc_a);
                     const WalkMask wm = walk_mask(p.a, L, la);
                     auto st = [&](int, const PosEntry& e) {
                         const int64_t oa = base_a + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
-                        const int64_t w = (int64_t)p.a.vec * eb;
-                        if (oa % w || lo % eb) return fail();
-                        if (oa < 0 || oa + w > total_bytes || lo < 0 || lo >= lds_bytes) return fail();
+                        if (oa % eba || lo % eba) return fail();
+                        if (lo < 0 || lo >= lds_bytes) return fail();
                         for (int j = 0; j < p.a.vec; ++j) {
-                            const int64_t li = lo / eb + (int64_t)j * p.a.vec_lds_stride;
+                            const int64_t ea = oa / eba + j;
+                            if (!inside(ea, P.stride_a, false)) return fail();
+                            const int64_t li = lo / eba + (int64_t)j * p.a.vec_lds_stride;
                             if (li < 0 || li >= p.lds_tile_elems) return fail();
                             if (lds[li] != -1) return fail();
-                            lds[li] = oa / eb + j;
+                            lds[li] = ea;
                         }
                     };
                     walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
@@ -1080,19 +1138,20 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             const SideLim lb = side_lim(p.b, tl);
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
-                    const LaneState L = lane_setup<false>(p.b, lane, eb);
+                    const LaneState L = lane_setup<false>(p.b, lane, sc_b);
                     const WalkMask wm = walk_mask(p.b, L, lb);
                     auto st = [&](int, const PosEntry& e) {
                         const int64_t ob = base_b + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
-                        const int64_t w = (int64_t)p.b.vec * eb;
-                        if (ob % w || lo % eb) return fail();
-                        if (ob < 0 || ob + w > total_bytes) return fail();
+                        if (ob % ebb || lo % eba) return fail();
                         for (int j = 0; j < p.b.vec; ++j) {
-                            const int64_t li = lo / eb + (int64_t)j * p.b.vec_lds_stride;
+                            const int64_t eo = ob / ebb + j;
+                            if (!inside(eo, P.stride_b, true)) return fail();
+                            const int64_t li = lo / eba + (int64_t)j * p.b.vec_lds_stride;
                             if (li < 0 || li >= p.lds_tile_elems) return fail();
-                            if (lds[li] == -1 || b_from_a[ob / eb + j] != -1) return fail();
-                            b_from_a[ob / eb + j] = lds[li];
+                            if (lds[li] == -1 || b_from_a[eo] != -1) return fail();
+                            b_from_a[eo] = lds[li];
+                            ++written;
                         }
                     };
                     walk<4>(p.b, L, lb, wm, tab_b.data(), tabc_b.data(), wave, st, nop);
@@ -1100,7 +1159,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
         }
     }
     if (bad) return TTC_ERR_INTERNAL;
-    for (int64_t i = 0; i < total; ++i) if (b_from_a[i] < 0) return TTC_ERR_INTERNAL;
+    if (written != P.elements) return TTC_ERR_INTERNAL;
     return TTC_OK;
 }
 

@@ -104,7 +104,10 @@ TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
 }
 
 // ---- lane entry ------------------------------------------------------------------------------
-// Offsets are in BYTES (element offsets times `scale`, the element size).
+// Offsets are in BYTES.  A walk has three element sizes: of the tensor it follows (g), of B in
+// the direct kernel (g2), and of the LDS tile, which holds elements of A (l).
+struct Scales { int32_t g, g2, l; };
+
 struct LaneState {
     int64_t g;                 // byte offset into the tensor the walk follows
     int64_t g2;                // direct kernel: byte offset into B
@@ -114,7 +117,7 @@ struct LaneState {
 };
 
 template <bool DIRECT>
-TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, int32_t scale)
+TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, const Scales& scale)
 {
     LaneState L;
     L.g = 0; L.g2 = 0; L.l = 0;
@@ -131,7 +134,7 @@ TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, int32_t scale)
             else L.l += c * d.lstride;
         }
     }
-    L.g *= scale; L.g2 *= scale; L.l *= scale;
+    L.g *= scale.g; L.g2 *= scale.g2; L.l *= scale.l;
     return L;
 }
 
@@ -145,7 +148,7 @@ struct alignas(16) PosEntry {
 struct alignas(8) PosCoord { uint32_t c01, c23; };
 
 template <bool DIRECT>
-TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e, PosCoord* c)
+TTC_HD void make_position(const Side& s, uint32_t it, const Scales& scale, PosEntry* e, PosCoord* c)
 {
     int64_t g = 0, x = 0;
     uint32_t pc[kBoxDims];
@@ -160,8 +163,8 @@ TTC_HD void make_position(const Side& s, uint32_t it, int32_t scale, PosEntry* e
             x += (int64_t)q * (DIRECT ? d.g2stride : (int64_t)d.lstride);
         }
     }
-    e->g = g * scale;
-    e->l_or_g2 = x * scale;
+    e->g = g * scale.g;
+    e->l_or_g2 = x * (DIRECT ? scale.g2 : scale.l);
     c->c01 = pc[0] | (pc[1] << 16);
     c->c23 = pc[2] | (pc[3] << 16);
 }
@@ -247,7 +250,7 @@ TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const Wa
 
 // Fill the two tables of one walk (all threads of the workgroup take part).
 template <bool DIRECT>
-TTC_HD void build_tables(const Side& s, uint32_t nwave, uint32_t thread, uint32_t nthreads, int32_t scale,
+TTC_HD void build_tables(const Side& s, uint32_t nwave, uint32_t thread, uint32_t nthreads, const Scales& scale,
                          PosEntry* tab, PosCoord* tabc)
 {
     const uint32_t total = nwave * (uint32_t)s.chunk;

@@ -21,10 +21,16 @@ from typing import Tuple
 import numpy as np
 
 F32, F64, C64, C128 = 0, 1, 2, 3
-DTYPE_NAME = {F32: "f32", F64: "f64", C64: "c64", C128: "c128"}
-REAL_DTYPE = {F32: np.float32, F64: np.float64, C64: np.float32, C128: np.float64}
-COMPONENTS = {F32: 1, F64: 1, C64: 2, C128: 2}
-ELEM_BYTES = {F32: 4, F64: 8, C64: 8, C128: 16}
+F32_F64, F64_F32, C64_C128, C128_C64 = 4, 5, 6, 7          # A's type, then B's (paper Table 1: sd ds cz zc)
+DTYPE_NAME = {F32: "f32", F64: "f64", C64: "c64", C128: "c128",
+              F32_F64: "f32f64", F64_F32: "f64f32", C64_C128: "c64c128", C128_C64: "c128c64"}
+REAL_DTYPE = {F32: np.float32, F64: np.float64, C64: np.float32, C128: np.float64,          # of A
+              F32_F64: np.float32, F64_F32: np.float64, C64_C128: np.float32, C128_C64: np.float64}
+REAL_DTYPE_B = {F32: np.float32, F64: np.float64, C64: np.float32, C128: np.float64,
+                F32_F64: np.float64, F64_F32: np.float32, C64_C128: np.float64, C128_C64: np.float32}
+COMPONENTS = {F32: 1, F64: 1, C64: 2, C128: 2, F32_F64: 1, F64_F32: 1, C64_C128: 2, C128_C64: 2}
+ELEM_BYTES = {F32: 4, F64: 8, C64: 8, C128: 16, F32_F64: 4, F64_F32: 8, C64_C128: 8, C128_C64: 16}        # of A
+ELEM_BYTES_B = {F32: 4, F64: 8, C64: 8, C128: 16, F32_F64: 8, F64_F32: 4, C64_C128: 16, C128_C64: 8}
 
 SEED_BASE = 16030229700
 
@@ -84,11 +90,12 @@ def _cases():
 CASES = _cases()          # the 15 cases the headline median is taken over
 
 
-def uniform_tensor(dtype: int, elements: int, seed: int) -> np.ndarray:
-    """Flat array of the real component type, uniform on [-1, 1)."""
+def uniform_tensor(dtype: int, elements: int, seed: int, side: str = "a") -> np.ndarray:
+    """Flat array of the real component type of A (side "a") or of B (side "b"), uniform on [-1, 1)."""
     n = elements * COMPONENTS[dtype]
     rng = np.random.default_rng(seed)
-    return rng.uniform(-1.0, 1.0, n).astype(REAL_DTYPE[dtype], copy=False)
+    real = REAL_DTYPE[dtype] if side == "a" else REAL_DTYPE_B[dtype]
+    return rng.uniform(-1.0, 1.0, n).astype(real, copy=False)
 
 
 def case_inputs(case: Case):

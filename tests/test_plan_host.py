@@ -32,8 +32,8 @@ def info_of(dtype, sizes, perm, alpha=None, beta=None):
     ((ttc.TTC_F32, 2, (4, 4), (1, 1)), ttc.TTC_ERR_INVALID_PERM),
     ((ttc.TTC_F32, 2, (4, 4), (0, 2)), ttc.TTC_ERR_INVALID_PERM),
     ((ttc.TTC_F32, 2, (4, 4), (-1, 0)), ttc.TTC_ERR_INVALID_PERM),
-    ((ttc.TTC_C128, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
-    ((17, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
+    ((8, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
+    ((-1, 2, (4, 4), (1, 0)), ttc.TTC_ERR_UNSUPPORTED_DTYPE),
     ((ttc.TTC_F64, 3, (2 ** 31, 2 ** 31, 2 ** 10), (2, 1, 0)), ttc.TTC_ERR_OVERFLOW),
 ])
 def test_create_rejects(args, status):
@@ -41,6 +41,17 @@ def test_create_rejects(args, status):
         ttc.ttc_plan_create(*args)
     assert e.value.status == status
     assert ttc.ttc_last_status() == status
+
+
+def test_create_ex_rejects_short_leading_dimensions():
+    for lda, ldb in [((3, 5), None), (None, (4, 4)), ((4, 5), (5, 3))]:
+        with pytest.raises(ttc.TtcError) as e:
+            ttc.ttc_plan_create_ex(ttc.TTC_F32, 2, (4, 5), (1, 0), lda, ldb)
+        assert e.value.status == ttc.TTC_ERR_INVALID_VALUE
+    p = ttc.ttc_plan_create_ex(ttc.TTC_F32, 2, (4, 5), (1, 0), (4, 5), (5, 4))
+    i = ttc.ttc_plan_get_info(p)
+    assert i["span_a"] == 20 and i["span_b"] == 20
+    ttc.ttc_plan_destroy(p)
 
 
 def test_destroy_null_is_noop():
@@ -100,6 +111,32 @@ def test_fusion_is_maximal_and_consistent():
             assert oracle.element_map(sizes, perm) == oracle.element_map(tuple(fs), tuple(fp))
 
 
+def test_fusion_respects_leading_dimensions():
+    # footnote of Section 3 stage (1): i_m, i_{m+1} merge only if ld(i_{m+1}) = size(i_m) * ld(i_m), in A and in B
+    def fused(lda, ldb):
+        p = ttc.ttc_plan_create_ex(ttc.TTC_F32, 3, (5, 6, 7), (1, 2, 0), lda, ldb)
+        try:
+            return ttc.ttc_plan_get_info(p)
+        finally:
+            ttc.ttc_plan_destroy(p)
+    i = fused(None, None)
+    assert i["ndim"] == 2 and i["sizes"] == [5, 42]
+    i = fused((8, 6, 7), (6, 7, 9))                # padding only on indices that do not sit inside the merged pair
+    assert i["ndim"] == 2 and i["sizes"] == [5, 42] and i["stride_a"] == [1, 8] and i["stride_b"] == [42, 1]
+    i = fused((5, 9, 7), None)                     # A's index 1 is padded: 1 and 2 are not contiguous in A
+    assert i["ndim"] == 3 and i["stride_a"] == [1, 5, 45]
+    i = fused(None, (8, 7, 5))                     # B's index 0 (= i1) is padded: not contiguous in B
+    assert i["ndim"] == 3 and i["stride_b"] == [56, 1, 8]
+    assert i["span_b"] == 1 + 5 * 1 + 6 * 8 + 4 * 56
+
+
+def test_size_one_extent_with_padding_keeps_the_strides():
+    p = ttc.ttc_plan_create_ex(ttc.TTC_F32, 3, (4, 1, 6), (2, 1, 0), (5, 3, 6), (7, 2, 4))
+    i = ttc.ttc_plan_get_info(p)
+    ttc.ttc_plan_destroy(p)
+    assert i["ndim"] == 2 and i["sizes"] == [4, 6] and i["stride_a"] == [1, 15] and i["stride_b"] == [14, 1]
+
+
 # ---- case split (paper Section 3.1) ------------------------------------------------------
 def test_case_split_on_the_benchmark_cases():
     for c in wl.CASES:
@@ -132,12 +169,12 @@ def test_candidates_are_ranked_and_have_a_scalar_fallback():
 
 
 # ---- every candidate's walk, replayed on the host, is the element map of Eq. 1 ----------------
-def check_all_candidates(dtype, sizes, perm, max_candidates=None):
-    p = plan(dtype, sizes, perm)
-    total = int(np.prod(sizes))
-    emap = oracle.element_map(sizes, perm)
-    want = [0] * total
-    for off_a, off_b in enumerate(emap):
+def check_all_candidates(dtype, sizes, perm, max_candidates=None, lda=None, ldb=None):
+    p = ttc.ttc_plan_create_ex(dtype, len(sizes), sizes, perm, lda, ldb)
+    total = oracle.span([sizes[perm[j]] for j in range(len(sizes))], ldb)
+    assert total == ttc.ttc_plan_get_info(p)["span_b"]
+    want = [-1] * total
+    for off_a, off_b in oracle.element_pairs(sizes, perm, lda, ldb):
         want[off_b] = off_a
     n = ttc.ttc_plan_candidate_count(p)
     idx = range(n) if max_candidates is None or n <= max_candidates else \
@@ -158,7 +195,8 @@ def test_walks_all_perms_small_odd_extents(n):
         check_all_candidates(ttc.TTC_F32, sizes, perm, max_candidates=12)
 
 
-@pytest.mark.parametrize("dtype", [ttc.TTC_F32, ttc.TTC_F64, ttc.TTC_C64])
+@pytest.mark.parametrize("dtype", [ttc.TTC_F32, ttc.TTC_F64, ttc.TTC_C64, ttc.TTC_C128, ttc.TTC_F32_F64,
+                                   ttc.TTC_F64_F32, ttc.TTC_C64_C128, ttc.TTC_C128_C64])
 @pytest.mark.parametrize("sizes,perm", [
     ((70, 66), (1, 0)),                 # several tiles, ragged tails on both indices
     ((64, 64), (1, 0)),
@@ -181,3 +219,32 @@ def test_walks_random_5d_6d():
         n = int(rng.integers(5, 7))
         sizes, perm = wl.random_problem(rng, n, 20000, 12)
         check_all_candidates(ttc.TTC_F32, sizes, perm, max_candidates=6)
+
+
+# ---- sub-tensors (paper Table 1, --lda / --ldb) ------------------------------------------------
+@pytest.mark.parametrize("dtype", [ttc.TTC_F32, ttc.TTC_F64, ttc.TTC_C128_C64])
+@pytest.mark.parametrize("sizes,perm,lda,ldb", [
+    ((70, 66), (1, 0), (75, 66), (67, 70)),
+    ((64, 64), (1, 0), (64, 64), (96, 64)),
+    ((33, 5, 40), (2, 1, 0), (36, 5, 41), (40, 7, 33)),
+    ((40, 36, 5), (0, 2, 1), (43, 36, 5), (40, 6, 36)),          # stride-1 index fixed
+    ((4, 50, 30), (0, 2, 1), (4, 51, 30), (5, 30, 50)),
+    ((6, 5, 4, 7, 3), (4, 1, 3, 0, 2), (7, 5, 5, 7, 3), (3, 6, 8, 6, 4)),
+    ((12, 10, 9, 11), (0, 1, 3, 2), (13, 10, 9, 11), (12, 10, 11, 9)),   # indices 0,1 adjacent but A padded
+    ((500,), (0,), (700,), (512,)),
+    ((9, 1, 8), (2, 1, 0), (9, 4, 8), (8, 3, 10)),
+    ((1, 8, 6, 10), (1, 2, 0, 3), (2, 9, 8, 10), (9, 7, 3, 14)),     # size-1 first index, padded: no stride-1 index in A
+    ((8, 1, 6), (1, 0, 2), (8, 3, 6), (2, 9, 6)),                    # the same in B
+])
+def test_walks_subtensors(dtype, sizes, perm, lda, ldb):
+    check_all_candidates(dtype, sizes, perm, max_candidates=16, lda=lda, ldb=ldb)
+
+
+def test_walks_random_subtensors():
+    rng = np.random.default_rng(23)
+    for i in range(48):
+        n = int(rng.integers(1, 7))
+        sizes, perm = wl.random_problem(rng, n, 12000, 14)
+        lda = tuple(s + int(x) for s, x in zip(sizes, rng.integers(0, 4, n)))
+        ldb = tuple(sizes[perm[j]] + int(x) for j, x in zip(range(n), rng.integers(0, 4, n)))
+        check_all_candidates(i % 8, sizes, perm, max_candidates=5, lda=lda, ldb=ldb)
