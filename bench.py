@@ -39,6 +39,8 @@ def parse():
                     help="plan search cap: 0 = library default (200), 1 = heuristic only, -1 = all")
     ap.add_argument("--cases", type=str, default="", help="comma-separated substrings of case names (default: all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--plan-cache", type=str, default="",
+                    help="file of stored search results (TTC_PLAN_CACHE): cases found there are not searched again")
     return ap.parse_args()
 
 
@@ -110,6 +112,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.plan_cache:
+        os.environ["TTC_PLAN_CACHE"] = os.path.abspath(args.plan_cache)
     ttc.lib()                                   # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream().cuda_stream

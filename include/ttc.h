@@ -43,7 +43,9 @@ enum {
     TTC_ERR_HIP = 7,               /* a HIP runtime call failed */
     TTC_ERR_ALLOC = 8,
     TTC_ERR_MISALIGNED = 9,        /* pointer not aligned to the element size */
-    TTC_ERR_INTERNAL = 10          /* a candidate failed the host-side bounds check */
+    TTC_ERR_INTERNAL = 10,         /* a candidate failed the host-side bounds check */
+    TTC_ERR_NOT_FOUND = 11,        /* the plan store holds no usable entry for this problem */
+    TTC_ERR_IO = 12                /* the plan store could not be written */
 };
 
 /* Kernel families (paper Section 3.1: the stride-1 index keeps its place, or not). */
@@ -172,6 +174,21 @@ int ttc_plan_tune(ttc_plan_t plan, const void* A_scratch, void* B_scratch, void*
  */
 int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
                         void* stream, int max_candidates);
+
+/*
+ * Persistent store of search results (paper Section 3: solutions of previous searches are kept in a
+ * local database and returned without a new search).  `path` names a text file, one line per problem;
+ * the key is the fused problem (data type, extents, permutation, strides, whether beta is 0) on gfx950.
+ *   ttc_plan_cache_store   appends the plan's selected candidate (normally after ttc_plan_tune).
+ *   ttc_plan_cache_lookup  selects the stored candidate if the file has one for this problem and the
+ *                          library still builds that configuration: TTC_OK; otherwise TTC_ERR_NOT_FOUND
+ *                          and the plan is unchanged.  A missing file is "not found", not an error.
+ * Host only.  When the environment variable TTC_PLAN_CACHE names a file, ttc_plan_tune and
+ * ttc_plan_tune_pairs look the problem up there first (a hit skips the search) and store what a
+ * search selects.
+ */
+int ttc_plan_cache_store(ttc_plan_t plan, const char* path);
+int ttc_plan_cache_lookup(ttc_plan_t plan, const char* path);
 
 /*
  * Measurement helper: enqueue `warmup` untimed and `iters` timed ttc_execute calls on

@@ -15,7 +15,8 @@ TTC_F32, TTC_F64, TTC_C64, TTC_C128 = 0, 1, 2, 3
 TTC_F32_F64, TTC_F64_F32, TTC_C64_C128, TTC_C128_C64 = 4, 5, 6, 7      # A's type, then B's
 TTC_OK = 0
 (TTC_ERR_INVALID_VALUE, TTC_ERR_INVALID_PERM, TTC_ERR_UNSUPPORTED_DTYPE, TTC_ERR_NULL_POINTER,
- TTC_ERR_ALIAS, TTC_ERR_OVERFLOW, TTC_ERR_HIP, TTC_ERR_ALLOC, TTC_ERR_MISALIGNED, TTC_ERR_INTERNAL) = range(1, 11)
+ TTC_ERR_ALIAS, TTC_ERR_OVERFLOW, TTC_ERR_HIP, TTC_ERR_ALLOC, TTC_ERR_MISALIGNED, TTC_ERR_INTERNAL,
+ TTC_ERR_NOT_FOUND, TTC_ERR_IO) = range(1, 13)
 TTC_KERNEL_DIRECT, TTC_KERNEL_LDS = 0, 1
 TTC_EPI_COPY, TTC_EPI_SCALE, TTC_EPI_AXPBY = 0, 1, 2
 
@@ -23,6 +24,7 @@ EXPORTS = (
     "ttc_plan_create", "ttc_plan_create_ex", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
     "ttc_plan_get_info", "ttc_plan_candidate_count", "ttc_plan_select_candidate", "ttc_plan_tune",
     "ttc_plan_tune_pairs", "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
+    "ttc_plan_cache_store", "ttc_plan_cache_lookup",
 )
 
 
@@ -103,6 +105,10 @@ def lib() -> ctypes.CDLL:
         L.ttc_time_execute.argtypes = [vp, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
         L.ttc_time_ceiling.restype = i
         L.ttc_time_ceiling.argtypes = [i, ctypes.c_int64, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
+        L.ttc_plan_cache_store.restype = i
+        L.ttc_plan_cache_store.argtypes = [vp, ctypes.c_char_p]
+        L.ttc_plan_cache_lookup.restype = i
+        L.ttc_plan_cache_lookup.argtypes = [vp, ctypes.c_char_p]
         L.ttc_debug_emulate_map.restype = i
         L.ttc_debug_emulate_map.argtypes = [vp, i64p]
         _lib = L
@@ -231,6 +237,22 @@ def ttc_time_ceiling(kind: int, nbytes: int, src_list: Sequence[int], dst_list: 
     if st != TTC_OK:
         raise TtcError(st, "ttc_time_ceiling")
     return ms.value
+
+
+def ttc_plan_cache_store(plan: int, path: str) -> None:
+    st = lib().ttc_plan_cache_store(plan, os.fsencode(path))
+    if st != TTC_OK:
+        raise TtcError(st, "ttc_plan_cache_store")
+
+
+def ttc_plan_cache_lookup(plan: int, path: str) -> bool:
+    """True if the store held a usable entry (now selected), False if it did not."""
+    st = lib().ttc_plan_cache_lookup(plan, os.fsencode(path))
+    if st == TTC_OK:
+        return True
+    if st == TTC_ERR_NOT_FOUND:
+        return False
+    raise TtcError(st, "ttc_plan_cache_lookup")
 
 
 def ttc_debug_emulate_map(plan: int, elements: Optional[int] = None):

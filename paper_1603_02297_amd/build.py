@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libttc.so")
-SOURCES = ["ttc_plan.cpp", "ttc_device.hip"]
+SOURCES = ["ttc_plan.cpp", "ttc_cache.cpp", "ttc_device.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -423,6 +423,8 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
     const int total = (int)plan->cands.size();
     if (cap < 0 || cap > total) cap = total;
     if (cap == 1) { plan->selected = 0; return TTC_OK; }
+    const char* store = std::getenv("TTC_PLAN_CACHE");
+    if (store && *store && ttc::cache_lookup(plan, store) == TTC_OK) return TTC_OK;     // solved before
     ttc::EventPair ev;
     if (!ev.ok) return TTC_ERR_HIP;
     int turn = 0;
@@ -462,6 +464,7 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         if (best < 0 || ms < best_ms) { best = i; best_ms = ms; }
     }
     if (best >= 0) plan->selected = best;
+    if (store && *store) (void)ttc::cache_store(plan, store);       // a store that cannot be written costs a later search, no more
     return TTC_OK;
 }
 

@@ -27,6 +27,7 @@ FastDiv make_fastdiv(uint32_t d);
 
 constexpr int kBoxDims = 4;               // a box spans at most this many indices
 constexpr int kMaxIters = 2048;           // sub-box positions per tile and walk (size of the position table)
+constexpr int kMaxDigitExtent = 32000;    // flat extent of one digit of a walk: coordinates are compared 16 bits at a time
 
 // A box spans at most kBoxDims indices of the tensor; "slot" j is the j-th of them in A order.
 // Each walk ("side") sees the box as up to kBoxDims digits.  A digit is one index, or -- when
@@ -148,6 +149,9 @@ namespace ttc {
 int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const int64_t* lda, const int64_t* ldb,
                const void* alpha, const void* beta, ttc_plan_s* out);
 void set_last_status(int status);
+// Plan store (ttc_cache.cpp).
+int cache_store(const ttc_plan_s* plan, const char* path);
+int cache_lookup(ttc_plan_s* plan, const char* path);
 // Workgroups to launch for a candidate on a device with `cus` compute units.
 uint32_t launch_grid(const Candidate& c, int cus);
 void set_grid(KernelParams* kp, uint32_t grid);

@@ -233,7 +233,7 @@ static bool build_walk(const Problem& P, const int* order, const int64_t* stride
             DigitSpec& d = w->d[0];
             const int prev = d.outer_dim;
             if (i > 0 && order[i - 1] == prev && t[prev] == P.size[prev] && !(no_tail & (1u << k)) &&
-                stride[k] == stride[prev] * P.size[prev] && (int64_t)d.tile * t[k] < 65536) {
+                stride[k] == stride[prev] * P.size[prev] && (int64_t)d.tile * t[k] <= kMaxDigitExtent) {
                 d.inner = d.tile;
                 d.tile *= t[k];
                 d.outer_dim = k;
@@ -247,7 +247,7 @@ static bool build_walk(const Problem& P, const int* order, const int64_t* stride
         d.tile = t[k];
         d.inner = 1;
         d.lane = 1;
-        if (t[k] >= 65536) return false;
+        if (t[k] > kMaxDigitExtent) return false;
     }
     return w->nd >= 1;
 }
@@ -795,7 +795,19 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     int order_a[kMaxDim], order_b[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) { order_a[k] = k; order_b[k] = (k < n) ? P.perm[k] : k; }
     const bool stride1_fixed = (P.perm[0] == 0);
-    const int* orders[2] = {order_b, order_a};
+    // Tile orders (which index varies fastest from one tile id to the next): B's index order, A's, and the
+    // two mixed ones that put the other tensor's stride-1 index first, so that tiles sharing a cache line
+    // at the end of a run are in flight together on BOTH sides.
+    int order_ab[kMaxDim], order_ba[kMaxDim];
+    {
+        int na = 0, nb = 0;
+        order_ab[na++] = 0;
+        for (int i = 0; i < kMaxDim; ++i) if (order_b[i] != 0) order_ab[na++] = order_b[i];
+        order_ba[nb++] = order_b[0];
+        for (int i = 0; i < kMaxDim; ++i) if (order_a[i] != order_b[0]) order_ba[nb++] = order_a[i];
+    }
+    const int* orders[4] = {order_b, order_a, order_ab, order_ba};
+    const int norders = stride1_fixed ? 2 : 4;
 
     // -- direct candidates: only when the stride-1 index keeps its place.  The box takes leading
     //    indices of A and of B so that both sides move a few long contiguous chunks per tile.
@@ -817,7 +829,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                     for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
                     if (spanned > kBoxDims || vol * eb > 128 * 1024) continue;
                     if (vol * eb < 4096 && vol < P.elements) continue;
-                    for (int o = 0; o < 2; ++o)
+                    for (int o = 0; o < norders; ++o)
                         for (const LaunchShape& ls : kLaunchShapes) {
                             Candidate c;
                             if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
@@ -854,7 +866,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         for (int nbuf = 2; nbuf >= 1; --nbuf) {
                             if (nbuf == 1 && vol * eb < 8192) continue;     // small tiles can afford two buffers
                             for (int mg = 0; mg < 4; ++mg)
-                                for (int o = 0; o < 2; ++o)
+                                for (int o = 0; o < norders; ++o)
                                     for (const LaunchShape& ls : kLaunchShapes) {
                                         Candidate c;
                                         if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1,
@@ -957,6 +969,8 @@ const char* ttc_status_string(int status)
     case TTC_ERR_ALLOC: return "allocation failed";
     case TTC_ERR_MISALIGNED: return "pointer not aligned to the element size";
     case TTC_ERR_INTERNAL: return "internal error: a candidate's walk is not a bijection in bounds";
+    case TTC_ERR_NOT_FOUND: return "no stored plan for this problem";
+    case TTC_ERR_IO: return "the plan store could not be written";
     default: return "unknown status";
     }
 }

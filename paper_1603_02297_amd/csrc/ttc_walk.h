@@ -92,14 +92,23 @@ TTC_HD TileLim tile_lim(const KernelParams& p, uint32_t tile)
     return t;
 }
 
-// The same limits in the flat units of one walk's digits.
-struct SideLim { int32_t lim[kBoxDims]; };
+// The same limits in the flat units of one walk's digits, and packed for the bounds test.
+//
+// The test "coordinate of the lane + coordinate of the sub-box < limit" runs on all four digits
+// at once, 16 bits per digit: with g = 0x8000 a guard bit per field,
+//     x = (g + limit - 1)  -  position  -  lane        (field by field; no field can borrow from its
+//                                                      neighbour because extents stay below 32000)
+// keeps its guard bit exactly where the element lies inside the limit.
+constexpr uint32_t kGuard = 0x80008000u;
+struct SideLim { int32_t lim[kBoxDims]; uint32_t t01, t23; };
 
 TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
 {
     SideLim r;
 #pragma unroll
     for (int j = 0; j < kBoxDims; ++j) r.lim[j] = t.lim[j] * s.d[j].slot_mul;
+    r.t01 = (kGuard + (uint32_t)(r.lim[0] - 1)) + ((uint32_t)(r.lim[1] - 1) << 16);
+    r.t23 = (kGuard + (uint32_t)(r.lim[2] - 1)) + ((uint32_t)(r.lim[3] - 1) << 16);
     return r;
 }
 
@@ -113,6 +122,7 @@ struct LaneState {
     int64_t g2;                // direct kernel: byte offset into B
     int32_t l;                 // byte offset into the LDS tile
     int32_t c[kBoxDims];       // flat coordinate along each digit, in elements
+    uint32_t c01, c23;         // the same, 16 bits per digit
     bool    active;
 };
 
@@ -135,12 +145,14 @@ TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, const Scales& scale)
         }
     }
     L.g *= scale.g; L.g2 *= scale.g2; L.l *= scale.l;
+    L.c01 = (uint32_t)L.c[0] | ((uint32_t)L.c[1] << 16);
+    L.c23 = (uint32_t)L.c[2] | ((uint32_t)L.c[3] << 16);
     return L;
 }
 
 // ---- position entry --------------------------------------------------------------------------
 // 16 + 8 bytes per sub-box position: offsets of the sub-box origin, and its coordinates inside
-// the tile packed 16 bits per digit (tile extents stay below 65536).
+// the tile packed 16 bits per digit (flat extents of a digit stay below 32000).
 struct alignas(16) PosEntry {
     int64_t g;                 // byte offset in the tensor the walk follows
     int64_t l_or_g2;           // staged kernel: LDS byte offset; direct kernel: byte offset in B
@@ -169,15 +181,21 @@ TTC_HD void make_position(const Side& s, uint32_t it, const Scales& scale, PosEn
     c->c23 = pc[2] | (pc[3] << 16);
 }
 
-// does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
-// (bitwise and: no short-circuit branches between the comparisons)
-TTC_HD bool lane_valid(const LaneState& L, const SideLim& lim, const PosCoord& pc)
+// Limits of one tile as one lane sees them: the lane's own coordinates already taken off.
+struct LaneLim { uint32_t x01, x23; };
+
+TTC_HD LaneLim lane_lim(const LaneState& L, const SideLim& lim)
 {
-    const int32_t p0 = (int32_t)(pc.c01 & 0xffffu), p1 = (int32_t)(pc.c01 >> 16);
-    const int32_t p2 = (int32_t)(pc.c23 & 0xffffu), p3 = (int32_t)(pc.c23 >> 16);
-    const int ok = (int)(L.c[0] < lim.lim[0] - p0) & (int)(L.c[1] < lim.lim[1] - p1) &
-                   (int)(L.c[2] < lim.lim[2] - p2) & (int)(L.c[3] < lim.lim[3] - p3);
-    return ok != 0;
+    LaneLim r;
+    r.x01 = lim.t01 - L.c01;
+    r.x23 = lim.t23 - L.c23;
+    return r;
+}
+
+// does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
+TTC_HD bool lane_valid(const LaneLim& x, const PosCoord& pc)
+{
+    return (((x.x01 - pc.c01) & (x.x23 - pc.c23)) & kGuard) == kGuard;
 }
 
 // Which sub-box positions a wavefront takes, and where their table entries sit.  Wavefront w of
@@ -192,7 +210,7 @@ TTC_HD uint32_t wave_positions(const Side& s, uint32_t wave)
 // U positions at a time: stage1 for all U (issue the loads), then stage2 for all U (consume
 // them), so that U memory instructions are in flight per wavefront.
 template <int U, bool FULL, class Stage1, class Stage2>
-TTC_HD void walk_group(const LaneState& L, const SideLim& lim, const PosEntry* e_ptr, const PosCoord* c_ptr,
+TTC_HD void walk_group(const LaneLim& x, const PosEntry* e_ptr, const PosCoord* c_ptr,
                        Stage1&& stage1, Stage2&& stage2)
 {
     PosEntry e[U];
@@ -200,7 +218,7 @@ TTC_HD void walk_group(const LaneState& L, const SideLim& lim, const PosEntry* e
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         e[u] = e_ptr[u];
-        ok[u] = FULL ? true : lane_valid(L, lim, c_ptr[u]);
+        ok[u] = FULL ? true : lane_valid(x, c_ptr[u]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -238,13 +256,14 @@ TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const Wa
     const uint32_t cnt = wave_positions(s, wave);
     const PosEntry* my = tab + wave * (uint32_t)s.chunk;
     const PosCoord* myc = tabc + wave * (uint32_t)s.chunk;
+    const LaneLim x = lane_lim(L, lim);
     uint32_t k = 0;
     if (!m.dynamic) {
-        for (; k + U <= cnt; k += U) walk_group<U, true>(L, lim, my + k, myc + k, stage1, stage2);
-        for (; k < cnt; ++k) walk_group<1, true>(L, lim, my + k, myc + k, stage1, stage2);
+        for (; k + U <= cnt; k += U) walk_group<U, true>(x, my + k, myc + k, stage1, stage2);
+        for (; k < cnt; ++k) walk_group<1, true>(x, my + k, myc + k, stage1, stage2);
     } else {
-        for (; k + U <= cnt; k += U) walk_group<U, false>(L, lim, my + k, myc + k, stage1, stage2);
-        for (; k < cnt; ++k) walk_group<1, false>(L, lim, my + k, myc + k, stage1, stage2);
+        for (; k + U <= cnt; k += U) walk_group<U, false>(x, my + k, myc + k, stage1, stage2);
+        for (; k < cnt; ++k) walk_group<1, false>(x, my + k, myc + k, stage1, stage2);
     }
 }
 

@@ -31,7 +31,7 @@ def test_binding_covers_the_header():
 
 def test_status_strings():
     assert ttc.ttc_status_string(0) == "ok"
-    for st in range(1, 11):
+    for st in range(1, 13):
         assert ttc.ttc_status_string(st) not in ("ok", "unknown status")
     assert ttc.ttc_status_string(99) == "unknown status"
 

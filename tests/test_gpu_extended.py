@@ -197,3 +197,33 @@ def test_new_types_reject_misaligned_and_alias():
     ttc.ttc_execute(plan, buf.data_ptr(), buf.data_ptr() + 8 * 1024, s)
     torch.cuda.synchronize()
     ttc.ttc_plan_destroy(plan)
+
+
+def test_search_results_persist_through_the_plan_store(tmp_path, monkeypatch):
+    """With TTC_PLAN_CACHE set, a search stores what it selected and the next plan for the same
+    problem takes it from the store without timing anything (paper Section 3)."""
+    path = tmp_path / "plans.txt"
+    monkeypatch.setenv("TTC_PLAN_CACHE", str(path))
+    dev = torch.device("cuda:0")
+    sizes, perm = (96, 40, 24), (2, 0, 1)
+    n = prod(sizes)
+    A = wl.uniform_tensor(wl.F32, n, 7)
+    dA = torch.from_numpy(A).to(dev)
+    dB = torch.zeros(n, dtype=torch.float32, device=dev)
+    s = torch.cuda.current_stream().cuda_stream
+    p = ttc.ttc_plan_create(wl.F32, 3, sizes, perm, 1.5, 0.0)
+    ttc.ttc_plan_tune(p, dA.data_ptr(), dB.data_ptr(), s, 0)
+    first = ttc.ttc_plan_get_info(p)
+    ttc.ttc_plan_destroy(p)
+    assert path.exists() and len(path.read_text().splitlines()) == 1
+    q = ttc.ttc_plan_create(wl.F32, 3, sizes, perm, 1.5, 0.0)
+    ttc.ttc_plan_tune(q, dA.data_ptr(), dB.data_ptr(), s, 0)
+    second = ttc.ttc_plan_get_info(q)
+    assert len(path.read_text().splitlines()) == 1                      # a hit stores nothing new
+    assert second["candidate_index"] == first["candidate_index"]
+    assert abs(second["tuned_ms"] - first["tuned_ms"]) < 1e-3           # the stored time, not a new measurement
+    ttc.ttc_execute(q, dA.data_ptr(), dB.data_ptr(), s)
+    torch.cuda.synchronize()
+    ttc.ttc_plan_destroy(q)
+    want = oracle.transpose(wl.F32, sizes, perm, 1.5, 0.0, A, np.zeros(n, np.float32))
+    assert np.array_equal(dB.cpu().numpy(), want)

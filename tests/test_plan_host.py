@@ -248,3 +248,75 @@ def test_walks_random_subtensors():
         lda = tuple(s + int(x) for s, x in zip(sizes, rng.integers(0, 4, n)))
         ldb = tuple(sizes[perm[j]] + int(x) for j, x in zip(range(n), rng.integers(0, 4, n)))
         check_all_candidates(i % 8, sizes, perm, max_candidates=5, lda=lda, ldb=ldb)
+
+
+# ---- persistent store of search results (paper Section 3: the database of previous solutions) --------
+CONFIG_FIELDS = ("kernel_class", "tile", "tile_order", "vec_a", "vec_b", "threads", "wg_per_cu", "lds_buffers",
+                 "digit_tile_a", "digit_lane_a", "digit_tile_b", "digit_lane_b", "lds_bytes")
+
+
+def config_of(p):
+    i = ttc.ttc_plan_get_info(p)
+    return {k: i[k] for k in CONFIG_FIELDS}
+
+
+def test_plan_store_round_trip(tmp_path):
+    path = str(tmp_path / "plans.txt")
+    sizes, perm = (48, 36, 20), (2, 0, 1)
+    p = plan(ttc.TTC_F32, sizes, perm, 1.5, 0.0)
+    assert ttc.ttc_plan_cache_lookup(p, path) is False                 # no file yet
+    n = ttc.ttc_plan_candidate_count(p)
+    ttc.ttc_plan_select_candidate(p, n // 3)
+    chosen = config_of(p)
+    ttc.ttc_plan_cache_store(p, path)
+    ttc.ttc_plan_destroy(p)
+
+    q = plan(ttc.TTC_F32, sizes, perm, 1.5, 0.0)
+    assert ttc.ttc_plan_get_info(q)["candidate_index"] == 0
+    assert ttc.ttc_plan_cache_lookup(q, path) is True
+    assert config_of(q) == chosen and ttc.ttc_plan_get_info(q)["candidate_index"] == n // 3
+    ttc.ttc_plan_destroy(q)
+
+    # alpha does not enter the key, beta == 0 does; neither do unrelated problems match
+    q = plan(ttc.TTC_F32, sizes, perm, 1.0, 0.0)
+    assert ttc.ttc_plan_cache_lookup(q, path) is True
+    ttc.ttc_plan_destroy(q)
+    for other in [plan(ttc.TTC_F32, sizes, perm, 1.5, 0.5), plan(ttc.TTC_F64, sizes, perm, 1.5, 0.0),
+                  plan(ttc.TTC_F32, sizes, (1, 0, 2), 1.5, 0.0), plan(ttc.TTC_F32, (48, 36, 21), perm, 1.5, 0.0),
+                  ttc.ttc_plan_create_ex(ttc.TTC_F32, 3, sizes, perm, (50, 36, 20), None, 1.5, 0.0)]:
+        assert ttc.ttc_plan_cache_lookup(other, path) is False
+        assert ttc.ttc_plan_get_info(other)["candidate_index"] == 0
+        ttc.ttc_plan_destroy(other)
+
+
+def test_plan_store_later_entry_wins_and_damage_is_ignored(tmp_path):
+    path = str(tmp_path / "plans.txt")
+    p = plan(ttc.TTC_F64, (40, 30), (1, 0))
+    ttc.ttc_plan_select_candidate(p, 5)
+    ttc.ttc_plan_cache_store(p, path)
+    ttc.ttc_plan_select_candidate(p, 9)
+    second = config_of(p)
+    ttc.ttc_plan_cache_store(p, path)
+    ttc.ttc_plan_select_candidate(p, 0)
+    assert ttc.ttc_plan_cache_lookup(p, path) is True and config_of(p) == second
+    # an entry naming a configuration this library does not build is skipped
+    lines = open(path).read().splitlines()
+    key, sig, us = lines[-1].split("|")
+    broken = sig.split()
+    broken[1] = "192"                                                  # a workgroup size no candidate has
+    with open(path, "w") as f:
+        f.write(key + "| " + " ".join(broken) + " |" + us + "\n")
+    ttc.ttc_plan_select_candidate(p, 0)
+    assert ttc.ttc_plan_cache_lookup(p, path) is False
+    with open(path, "w") as f:
+        f.write(key + "| 1 2 x |" + us + "\n")
+    assert ttc.ttc_plan_cache_lookup(p, path) is False
+    assert ttc.ttc_plan_get_info(p)["candidate_index"] == 0
+    ttc.ttc_plan_destroy(p)
+    with pytest.raises(ttc.TtcError) as e:
+        q = plan(ttc.TTC_F64, (40, 30), (1, 0))
+        try:
+            ttc.ttc_plan_cache_store(q, str(tmp_path / "no_such_dir" / "plans.txt"))
+        finally:
+            ttc.ttc_plan_destroy(q)
+    assert e.value.status == ttc.TTC_ERR_IO
