@@ -76,6 +76,8 @@ typedef struct {
     int     tile_order[TTC_MAX_DIM];       /* fused indices from fastest to slowest in the workgroup-id -> tile map */
     int     lds_stride[TTC_MAX_DIM];       /* element stride of each fused index inside the LDS tile (0 = unused) */
     int     vec_a, vec_b;                  /* elements per lane per global access on the A side / B side */
+    int     partial_a, partial_b;          /* 1: runs are not a multiple of the vector: the last vector of a run is moved
+                                              back to end with the run and overlaps its neighbour */
     int     threads;                       /* workgroup size */
     int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles */
     int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
@@ -218,8 +220,9 @@ int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src
  * (HOST array of span_b entries, see ttc_plan_info_t; prod(sizes) for dense tensors) the element
  * offset of A that the candidate moves to element offset o of B (the element map of paper Eq. 1),
  * -1 where B is not written.  Returns TTC_ERR_INTERNAL if any access would leave the (sub-)tensors
- * or the LDS tile, or an element of B would be written twice or not at all.  Cost grows with
- * prod(sizes).
+ * or the LDS tile, or an element of B would not be written at all or be written twice from different
+ * sources (overlapping vectors write an element twice with the same value; if beta != 0 they must
+ * belong to one instruction).  Cost grows with prod(sizes).
  */
 int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a);
 

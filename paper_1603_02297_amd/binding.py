@@ -38,7 +38,8 @@ class ttc_plan_info_t(ctypes.Structure):
         ("digit_tile_b", ctypes.c_int * 4), ("digit_lane_b", ctypes.c_int * 4),
         ("tile_order", ctypes.c_int * TTC_MAX_DIM),
         ("lds_stride", ctypes.c_int * TTC_MAX_DIM),
-        ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
+        ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("partial_a", ctypes.c_int), ("partial_b", ctypes.c_int),
+        ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
         ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("lds_buffers", ctypes.c_int),
         ("lds_conflict_a", ctypes.c_int), ("lds_conflict_b", ctypes.c_int),
         ("run_bytes_a", ctypes.c_int), ("run_bytes_b", ctypes.c_int), ("seg_bytes_a", ctypes.c_int),

@@ -109,11 +109,17 @@ template <typename TA, typename TB, int MODE> struct Epilogue {
 
 // ---------------------------------------------------------------------------------
 // The kernel.  Dynamic LDS: [two shared tile records][position tables of both walks][tile buffer 0][tile buffer 1].
+// Cut vectors: where a run is not a multiple of the vector width, the lane that would overhang moves its
+// vector back so that it ends with the run (`back` elements, handed to the stages).  It then repeats what
+// its neighbour does for those elements, with the same values, so nothing diverges and every access stays a
+// full vector.
 // A workgroup walks several tiles; with two tile buffers one barrier per tile is enough: a
 // wavefront can only start filling buffer (t+1)%2 after it passed the barrier of tile t, and
 // every wavefront reached that barrier after it had finished reading that buffer for tile t-1.
 // ---------------------------------------------------------------------------------
-constexpr int kUnroll = 4;     // memory instructions a wavefront keeps in flight per walk step
+// memory instructions a wavefront keeps in flight per walk step: four 16-byte accesses per lane, more of the
+// narrow ones (the bytes in flight per wavefront are what hides the memory latency)
+template <typename T, int V> struct Unroll { static constexpr int value = (V * sizeof(T) >= 16) ? 4 : 8; };
 
 __device__ __forceinline__ int64_t uniform64(int64_t v)
 {
@@ -187,13 +193,14 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         const SideLim sla = side_lim(p.a, tl);
         const WalkMask wma = walk_mask(p.a, LA, sla);
         if (DIRECT) {
+            constexpr int kUnroll = Unroll<TA, VA>::value;
             Pack<TA, VA> ra[kUnroll];
             Pack<TB, VA> rb[kUnroll];
-            auto load = [&](int u, const PosEntry& e) {
-                ra[u] = load_pack<TA, VA>(At, e.g + LA.g);
-                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VA>(Bt, e.l_or_g2 + LA.g2);
+            auto load = [&](int u, const PosEntry& e, int back) {
+                ra[u] = load_pack<TA, VA>(At, e.g + LA.g - back * kScaleA);
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VA>(Bt, e.l_or_g2 + LA.g2 - back * kScaleB);
             };
-            auto store = [&](int u, const PosEntry& e) {
+            auto store = [&](int u, const PosEntry& e, int back) {
                 Pack<TB, VA> out;
 #pragma unroll
                 for (int j = 0; j < VA; ++j) {
@@ -201,9 +208,9 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                     if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
                     out.v[j] = epi(ra[u].v[j], old);
                 }
-                *reinterpret_cast<Pack<TB, VA>*>(Bt + (e.l_or_g2 + LA.g2)) = out;
+                *reinterpret_cast<Pack<TB, VA>*>(Bt + (e.l_or_g2 + LA.g2 - back * kScaleB)) = out;
             };
-            walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, store);
+            walk<kUnroll, VA>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, store);
             continue;
         }
 
@@ -213,14 +220,15 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         // ---- walk 1: A order, global -> LDS
         {
             const int32_t vs = p.a.vec_lds_stride;
+            constexpr int kUnroll = Unroll<TA, VA>::value;
             Pack<TA, VA> ra[kUnroll];
-            auto load = [&](int u, const PosEntry& e) { ra[u] = load_pack<TA, VA>(At, e.g + LA.g); };
-            auto park = [&](int u, const PosEntry& e) {
-                TA* dst = reinterpret_cast<TA*>(lds + ((int32_t)e.l_or_g2 + LA.l));
+            auto load = [&](int u, const PosEntry& e, int back) { ra[u] = load_pack<TA, VA>(At, e.g + LA.g - back * kScaleA); };
+            auto park = [&](int u, const PosEntry& e, int back) {
+                TA* dst = reinterpret_cast<TA*>(lds + ((int32_t)e.l_or_g2 + LA.l - back * vs * kScaleA));
 #pragma unroll
                 for (int j = 0; j < VA; ++j) dst[j * vs] = ra[u].v[j];
             };
-            walk<kUnroll>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, park);
+            walk<kUnroll, VA>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, park);
         }
         if (wave == nwave - 1 && tile + seq.step < seq.end) publish(tile + seq.step, parity);   // parity already flipped
         __syncthreads();
@@ -229,15 +237,16 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
             const SideLim slb = side_lim(p.b, tl);
             const WalkMask wmb = walk_mask(p.b, LB, slb);
             const int32_t vs = p.b.vec_lds_stride;
+            constexpr int kUnroll = Unroll<TB, VB>::value;
             Pack<TB, VB> rb[kUnroll];
             Pack<TA, VB> rl[kUnroll];
-            auto load = [&](int u, const PosEntry& e) {
-                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VB>(Bt, e.g + LB.g);
-                const TA* src = reinterpret_cast<const TA*>(lds + ((int32_t)e.l_or_g2 + LB.l));
+            auto load = [&](int u, const PosEntry& e, int back) {
+                if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VB>(Bt, e.g + LB.g - back * kScaleB);
+                const TA* src = reinterpret_cast<const TA*>(lds + ((int32_t)e.l_or_g2 + LB.l - back * vs * kScaleA));
 #pragma unroll
                 for (int j = 0; j < VB; ++j) rl[u].v[j] = src[j * vs];
             };
-            auto store = [&](int u, const PosEntry& e) {
+            auto store = [&](int u, const PosEntry& e, int back) {
                 Pack<TB, VB> out;
 #pragma unroll
                 for (int j = 0; j < VB; ++j) {
@@ -245,9 +254,9 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
                     if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
                     out.v[j] = epi(rl[u].v[j], old);
                 }
-                *reinterpret_cast<Pack<TB, VB>*>(Bt + (e.g + LB.g)) = out;
+                *reinterpret_cast<Pack<TB, VB>*>(Bt + (e.g + LB.g - back * kScaleB)) = out;
             };
-            walk<kUnroll>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
+            walk<kUnroll, VB>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
         }
         if (p.lds_buffers == 1) __syncthreads();      // the one buffer is refilled by the next tile
     }

@@ -59,7 +59,8 @@ struct Side {
     int32_t  exact;                  // 1: lane divides tile on every digit (no ragged sub-boxes)
     int32_t  chunk;                  // positions per wavefront, rounded up: ceil(n_iter / waves)
     int32_t  chunk_rem;              // wavefronts that really have `chunk` positions (the others have one less)
-    int32_t  pad;
+    int32_t  partial;                // 1: the first digit's extent is not a multiple of vec: the last vector of a run is cut
+    int32_t  vec_slot;               // slot (0..3) that holds the walk's first digit, the one vectors run along
     FastDiv  chunk_div;
     Digit    d[kBoxDims];
 };

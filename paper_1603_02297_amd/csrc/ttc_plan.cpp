@@ -3,6 +3,7 @@
 // 3.3 and the candidate queue of Section 3).  Pure host C++: no device is touched here.
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -254,14 +255,26 @@ static bool build_walk(const Problem& P, const int* order, const int64_t* stride
 
 // Largest vector width (elements) for a walk: vectors lie along the first digit and must not
 // straddle its end, in whole tiles and in the tiles the tensor's edge cuts.
-static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit, int eb, bool unit_stride)
+// A limit above 16 also admits vectors that do not divide the run (*partial = true): the last vector of every
+// run is then moved back to end with the run and overlaps its neighbour.  That needs every run, also the
+// shortened ones of the tiles the tensor's edge cuts, to hold at least one vector, and pays only for runs of
+// several vectors.
+static int walk_vec(const Problem& P, const WalkSpec& w, const int* t, int limit, int eb, bool unit_stride,
+                    bool* partial)
 {
+    *partial = false;
     if (!unit_stride) return 1;      // a dropped size-1 index with a padded leading dimension: no stride-1 index
-    int v = std::min(limit, std::max(1, 16 / eb));
+    const int widest = std::max(1, std::min(std::min(limit, 16), std::max(1, 16 / eb)));
     const DigitSpec& d = w.d[0];
     const int64_t rest = P.size[d.outer_dim] % t[d.outer_dim];
+    int v = widest;
     while (v > 1 && (d.tile % v != 0 || (rest * d.inner) % v != 0)) v /= 2;
-    return std::max(v, 1);
+    v = std::max(v, 1);
+    if (limit > 16 && v < widest && d.tile >= 4 * widest && (rest == 0 || rest * d.inner >= widest)) {
+        *partial = true;
+        return widest;
+    }
+    return v;
 }
 
 // Lane mapping: which sub-box of the tile one wavefront instruction covers.
@@ -272,7 +285,7 @@ static void choose_lanes(const Problem& P, WalkSpec* w, int vec, int eb, int* n_
     int best_iter = 1, best_lanes = 1;
     const int t0 = w->d[0].tile;
     std::vector<int> opts;
-    const int cap = std::min(t0, kWave * vec);
+    const int cap = (int)std::min<int64_t>(round_up(t0, vec), kWave * vec);
     for (int l = vec; l <= cap; l += vec)
         if (t0 % l == 0 || l == cap) opts.push_back(l);
     if (opts.empty()) opts.push_back(vec);
@@ -361,6 +374,7 @@ static bool fill_side(const Problem& P, const WalkSpec& w, int vec, const int* s
     s->lanes = (int)lane_below;
     s->n_iter = (int)n_iter;
     s->vec_lds_stride = lds_stride ? lds_stride[w.d[0].first_dim] : 0;
+    s->vec_slot = slot_of_dim[w.d[0].outer_dim];
     return true;
 }
 
@@ -529,11 +543,16 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         if (nslots == 0) trivial_walk(&wa);
         else if (!build_walk(P, order_a, P.stride_a, t, false, 0u, &wa)) return false;
         const int eb_max = std::max(P.eb_a, P.eb_b);        // every lane stores what it loaded: one width for both
+        // overlapping vectors would read elements of B that a neighbour may already have updated
+        if (P.epilogue == TTC_EPI_AXPBY) vec_limit = std::min(vec_limit, 16);
+        bool part = false;
         const int v = (nslots == 0) ? 1 : walk_vec(P, wa, t, vec_limit, eb_max,
-                                                  P.stride_a[wa.d[0].first_dim] == 1 && P.stride_b[wa.d[0].first_dim] == 1);
+                                                  P.stride_a[wa.d[0].first_dim] == 1 && P.stride_b[wa.d[0].first_dim] == 1,
+                                                  &part);
         int n_iter, lanes;
         choose_lanes(P, &wa, v, eb_max, &n_iter, &lanes);
         if (!fill_side(P, wa, v, slot_of_dim, nullptr, false, &kp.a)) return false;
+        kp.a.partial = part ? 1 : 0;
         kp.b = kp.a;
         wb = wa;
         C.kernel_class = TTC_KERNEL_DIRECT;
@@ -567,8 +586,10 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
                 if (k == wb.d[0].outer_dim) break;
             }
         }
-        const int va = walk_vec(P, wa, t, vec_limit, P.eb_a, P.stride_a[wa.d[0].first_dim] == 1);
-        const int vb = walk_vec(P, wb, t, vec_limit, P.eb_b, P.stride_b[wb.d[0].first_dim] == 1);
+        bool part_a = false, part_b = false;
+        const int va = walk_vec(P, wa, t, vec_limit, P.eb_a, P.stride_a[wa.d[0].first_dim] == 1, &part_a);
+        const int vb = walk_vec(P, wb, t, P.epilogue == TTC_EPI_AXPBY ? std::min(vec_limit, 16) : vec_limit, P.eb_b,
+                                P.stride_b[wb.d[0].first_dim] == 1, &part_b);     // see the direct case
         int ia, la_, ib, lb_;
         choose_lanes(P, &wa, va, P.eb_a, &ia, &la_);
         choose_lanes(P, &wb, vb, P.eb_b, &ib, &lb_);
@@ -587,6 +608,8 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         for (int k = 0; k < kMaxDim; ++k) C.lds_stride[k] = L.stride[k];
         if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &kp.a)) return false;
         if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &kp.b)) return false;
+        kp.a.partial = part_a ? 1 : 0;
+        kp.b.partial = part_b ? 1 : 0;
         C.kernel_class = TTC_KERNEL_LDS;
         kp.lds_data_off = (int)round_up(24 * (int64_t)(kp.a.n_iter + kp.b.n_iter), 16);
         kp.lds_tile_elems = (int)round_up(L.elems, std::max(1, 16 / P.eb_a));
@@ -814,15 +837,19 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     if (stride1_fixed) {
         const int vfull = max_vec(eb, P.size[0]);
         const int64_t chunk_bytes[6] = {16384, 4096, 32768, 8192, 2048, 65536};
-        for (int vsel = 0; vsel < 2; ++vsel) {
-            if (vsel == 1 && vfull == 1) break;
-            const int v = vsel == 0 ? vfull : 1;
+        const int vwide = std::max(1, 16 / eb);
+        for (int vsel = 0; vsel < 3; ++vsel) {
+            if (vsel == 1 && vfull == 1) continue;
+            if (vsel == 2 && (vfull == vwide || P.stride_a[0] != 1 || P.stride_b[0] != 1)) continue;
+            // 0: the widest vector that divides the rows; 1: scalar; 2: the widest vector, cut at the end of a run
+            const int v = vsel == 0 ? vfull : (vsel == 1 ? 1 : 32);
+            const int vmult = vsel == 0 ? vfull : 1;
             for (int style = 0; style < 2; ++style)
             for (int64_t ra : chunk_bytes)
                 for (int64_t rb : chunk_bytes) {
                     int ta[kMaxDim], tb[kMaxDim], t[kMaxDim];
-                    build_group(P, order_a, P.eb_a, ra / P.eb_a, v, kBoxDims, ta, style);
-                    build_group(P, order_b, P.eb_b, rb / P.eb_b, v, kBoxDims, tb, style);
+                    build_group(P, order_a, P.eb_a, ra / P.eb_a, vmult, kBoxDims, ta, style);
+                    build_group(P, order_b, P.eb_b, rb / P.eb_b, vmult, kBoxDims, tb, style);
                     int64_t vol = 1;
                     int spanned = 0;
                     for (int k = 0; k < kMaxDim; ++k) t[k] = std::max(ta[k], tb[k]);
@@ -845,10 +872,13 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
         const int va_full = max_vec(P.eb_a, P.size[0]);
         const int vb_full = max_vec(P.eb_b, P.size[p0]);
         const int64_t run_bytes[8] = {256, 512, 128, 1024, 64, 2048, 4096, 8192};
-        for (int vsel = 0; vsel < 2; ++vsel) {
+        const bool odd_rows = va_full < std::max(1, 16 / P.eb_a) || vb_full < std::max(1, 16 / P.eb_b);
+        for (int vsel = 0; vsel < 3; ++vsel) {
+            if (vsel == 2 && !odd_rows) continue;
+            // 0: the widest vectors that divide the runs; 1: scalar; 2: the widest vectors, cut at the end of a run
             const int va = vsel == 0 ? va_full : 1;       // multiples the group builder keeps on the stride-1 extents
             const int vb = vsel == 0 ? vb_full : 1;
-            const int vec_limit = vsel == 0 ? 16 : 1;
+            const int vec_limit = vsel == 0 ? 16 : (vsel == 1 ? 1 : 32);
             for (int md = 3; md >= 1; --md)
               for (int style = 0; style < 2; ++style)
                 for (int64_t ra : run_bytes)
@@ -917,6 +947,18 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
 }
 
 }  // namespace ttc
+
+// The kernels instantiate a walk for a compile-time vector width; the replay picks the same one.
+template <class S1, class S2>
+static void emu_walk(const ttc::Side& s, const ttc::LaneState& L, const ttc::SideLim& lim, const ttc::WalkMask& m,
+                     const ttc::PosEntry* tab, const ttc::PosCoord* tabc, uint32_t wave, S1&& s1, S2&& s2)
+{
+    switch (s.vec) {
+    case 1: ttc::walk<4, 1>(s, L, lim, m, tab, tabc, wave, s1, s2); break;
+    case 2: ttc::walk<4, 2>(s, L, lim, m, tab, tabc, wave, s1, s2); break;
+    default: ttc::walk<4, 4>(s, L, lim, m, tab, tabc, wave, s1, s2); break;
+    }
+}
 
 // ---------------------------------------------------------------------------------
 // Host-only part of the C ABI
@@ -1001,6 +1043,8 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->epilogue = P.epilogue;
     out->vec_a = C.kp.a.vec;
     out->vec_b = C.kp.b.vec;
+    out->partial_a = C.kp.a.partial;
+    out->partial_b = C.kp.b.partial;
     out->threads = C.threads;
     out->wg_per_cu = C.wg_per_cu;
     out->xcd_remap = C.kp.xcd_remap;
@@ -1096,8 +1140,12 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     std::vector<int64_t> lds((size_t)p.lds_tile_elems);          // which element offset of A each slot holds
     std::vector<char> seen(p.num_tiles, 0);
     bool bad = false;
-    auto fail = [&]() { bad = true; };
-    auto nop = [](int, const PosEntry&) {};
+    int fail_line = 0;
+    auto fail_at = [&](int line) { if (!bad) fail_line = line; bad = true; };
+#define fail() fail_at(__LINE__)
+    auto nop = [](int, const PosEntry&, int) {};
+    const bool axpby = (P.epilogue == TTC_EPI_AXPBY);
+    std::vector<int64_t> writer((size_t)P.span_b, -1);      // which instruction wrote an element of B
     int64_t written = 0;
     for (uint32_t wg = 0; wg < p.grid && !bad; ++wg) {
         const TileSeq seq = tile_sequence(p, wg);
@@ -1113,18 +1161,22 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                     for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                         const LaneState L = lane_setup<true>(p.a, lane, sc_a);
                         const WalkMask wm = walk_mask(p.a, L, la);
-                        auto st = [&](int, const PosEntry& e) {
+                        auto st = [&](int, const PosEntry& e, int back) {
                             const int64_t oa = base_a + e.g + L.g, ob = base_b + e.l_or_g2 + L.g2;
-                            if (oa % eba || ob % ebb) return fail();
-                            for (int j = 0; j < p.a.vec; ++j) {
+                            if (oa % eba || ob % ebb || back < 0 || back >= p.a.vec) return fail();
+                            const int64_t who = ((int64_t)tile << 32) | (wave << 16) | (uint32_t)(&e - tab_a.data());
+                            for (int j = -back; j < p.a.vec - back; ++j) {
                                 const int64_t ea = oa / eba + j, eo = ob / ebb + j;
                                 if (!inside(ea, P.stride_a, false) || !inside(eo, P.stride_b, true)) return fail();
-                                if (b_from_a[eo] != -1) return fail();
+                                // a moved-back vector repeats its neighbour's elements: same source, same instruction
+                                // if B is read as well as written
+                                if (b_from_a[eo] != -1 && (b_from_a[eo] != ea || (axpby && writer[eo] != who))) return fail();
+                                if (b_from_a[eo] == -1) ++written;
                                 b_from_a[eo] = ea;
-                                ++written;
+                                writer[eo] = who;
                             }
                         };
-                        walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
+                        emu_walk(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
                     }
                 continue;
             }
@@ -1133,47 +1185,53 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.a, lane, sc_a);
                     const WalkMask wm = walk_mask(p.a, L, la);
-                    auto st = [&](int, const PosEntry& e) {
+                    auto st = [&](int, const PosEntry& e, int back) {
                         const int64_t oa = base_a + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
-                        if (oa % eba || lo % eba) return fail();
+                        if (oa % eba || lo % eba || back < 0 || back >= p.a.vec) return fail();
                         if (lo < 0 || lo >= lds_bytes) return fail();
-                        for (int j = 0; j < p.a.vec; ++j) {
+                        for (int j = -back; j < p.a.vec - back; ++j) {
                             const int64_t ea = oa / eba + j;
                             if (!inside(ea, P.stride_a, false)) return fail();
                             const int64_t li = lo / eba + (int64_t)j * p.a.vec_lds_stride;
                             if (li < 0 || li >= p.lds_tile_elems) return fail();
-                            if (lds[li] != -1) return fail();
+                            if (lds[li] != -1 && lds[li] != ea) return fail();
                             lds[li] = ea;
                         }
                     };
-                    walk<4>(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
+                    emu_walk(p.a, L, la, wm, tab_a.data(), tabc_a.data(), wave, st, nop);
                 }
             const SideLim lb = side_lim(p.b, tl);
             for (uint32_t wave = 0; wave < nwave; ++wave)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.b, lane, sc_b);
                     const WalkMask wm = walk_mask(p.b, L, lb);
-                    auto st = [&](int, const PosEntry& e) {
+                    auto st = [&](int, const PosEntry& e, int back) {
                         const int64_t ob = base_b + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
-                        if (ob % ebb || lo % eba) return fail();
-                        for (int j = 0; j < p.b.vec; ++j) {
+                        if (ob % ebb || lo % eba || back < 0 || back >= p.b.vec) return fail();
+                        const int64_t who = ((int64_t)tile << 32) | (wave << 16) | (uint32_t)(&e - tab_b.data());
+                        for (int j = -back; j < p.b.vec - back; ++j) {
                             const int64_t eo = ob / ebb + j;
                             if (!inside(eo, P.stride_b, true)) return fail();
                             const int64_t li = lo / eba + (int64_t)j * p.b.vec_lds_stride;
                             if (li < 0 || li >= p.lds_tile_elems) return fail();
-                            if (lds[li] == -1 || b_from_a[eo] != -1) return fail();
+                            if (lds[li] == -1) return fail();
+                            if (b_from_a[eo] != -1 && (b_from_a[eo] != lds[li] || (axpby && writer[eo] != who))) return fail();
+                            if (b_from_a[eo] == -1) ++written;
                             b_from_a[eo] = lds[li];
-                            ++written;
+                            writer[eo] = who;
                         }
                     };
-                    walk<4>(p.b, L, lb, wm, tab_b.data(), tabc_b.data(), wave, st, nop);
+                    emu_walk(p.b, L, lb, wm, tab_b.data(), tabc_b.data(), wave, st, nop);
                 }
         }
     }
-    if (bad) return TTC_ERR_INTERNAL;
-    if (written != P.elements) return TTC_ERR_INTERNAL;
+#undef fail
+    if (bad || written != P.elements) {
+        if (std::getenv("TTC_EMU_DEBUG")) std::fprintf(stderr, "ttc_debug_emulate_map: check at line %d failed, %lld of %lld elements written\n", fail_line, (long long)written, (long long)P.elements);
+        return TTC_ERR_INTERNAL;
+    }
     return TTC_OK;
 }
 

@@ -192,10 +192,25 @@ TTC_HD LaneLim lane_lim(const LaneState& L, const SideLim& lim)
     return r;
 }
 
-// does this lane's element (vector) at this sub-box position lie inside the box and the tensor?
+// does this lane's element (the first one of its vector) at this sub-box position lie inside the
+// box and the tensor?
 TTC_HD bool lane_valid(const LaneLim& x, const PosCoord& pc)
 {
     return (((x.x01 - pc.c01) & (x.x23 - pc.c23)) & kGuard) == kGuard;
+}
+
+// Vectors of V elements along the walk's first digit whose extent is not a multiple of V: by how many
+// elements must the lane's vector move back so that it ends inside the limit?  0 .. V-1, or -1 if not
+// even its first element lies inside (the limit is at least V, so a moved vector never starts before 0).
+template <int V>
+TTC_HD int lane_back(const LaneLim& x, const PosCoord& pc, int vec_slot)
+{
+    const uint32_t a = x.x01 - pc.c01, b = x.x23 - pc.c23;
+    if (((a & b) & kGuard) != kGuard) return -1;
+    const uint32_t w = (vec_slot & 2) ? b : a;
+    const uint32_t f = (vec_slot & 1) ? (w >> 16) : w;
+    const int left = (int)(f & 0x7fffu) + 1;          // the field holds limit - 1 - coordinate
+    return left < V ? V - left : 0;
 }
 
 // Which sub-box positions a wavefront takes, and where their table entries sit.  Wavefront w of
@@ -207,25 +222,32 @@ TTC_HD uint32_t wave_positions(const Side& s, uint32_t wave)
     return (uint32_t)s.chunk - (wave >= (uint32_t)s.chunk_rem ? 1u : 0u);
 }
 
+// How a group of positions treats the bounds: no test at all, whole vectors tested, or vectors
+// that are moved back where the run ends inside them.
+enum { kWalkFull = 0, kWalkMasked = 1, kWalkPartial = 2 };
+
 // U positions at a time: stage1 for all U (issue the loads), then stage2 for all U (consume
-// them), so that U memory instructions are in flight per wavefront.
-template <int U, bool FULL, class Stage1, class Stage2>
-TTC_HD void walk_group(const LaneLim& x, const PosEntry* e_ptr, const PosCoord* c_ptr,
+// them), so that U memory instructions are in flight per wavefront.  stage(u, entry, back):
+// u = slot 0..U-1, back = elements the lane's vector is moved back by (0 unless the walk is partial).
+template <int U, int V, int MODE, class Stage1, class Stage2>
+TTC_HD void walk_group(const LaneLim& x, int vec_slot, const PosEntry* e_ptr, const PosCoord* c_ptr,
                        Stage1&& stage1, Stage2&& stage2)
 {
     PosEntry e[U];
-    bool ok[U];
+    int back[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         e[u] = e_ptr[u];
-        ok[u] = FULL ? true : lane_valid(x, c_ptr[u]);
+        if (MODE == kWalkFull) back[u] = 0;
+        else if (MODE == kWalkMasked) back[u] = lane_valid(x, c_ptr[u]) ? 0 : -1;
+        else back[u] = lane_back<V>(x, c_ptr[u], vec_slot);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (ok[u]) stage1(u, e[u]);
+        if (back[u] >= 0) stage1(u, e[u], MODE == kWalkPartial ? back[u] : 0);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (ok[u]) stage2(u, e[u]);
+        if (back[u] >= 0) stage2(u, e[u], MODE == kWalkPartial ? back[u] : 0);
 }
 
 // What a walk has to test per lane in one tile.  Digits with a single sub-box position are
@@ -237,7 +259,7 @@ TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
 {
     WalkMask m;
     m.lane_ok = L.active;
-    m.dynamic = false;
+    m.dynamic = (s.partial != 0);
 #pragma unroll
     for (int j = 0; j < kBoxDims; ++j) {
         const Digit& d = s.d[j];
@@ -247,8 +269,17 @@ TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
     return m;
 }
 
-// Drive one wavefront through its share of a walk.   stage(u, entry): u = slot 0..U-1.
-template <int U, class Stage1, class Stage2>
+template <int U, int V, int MODE, class Stage1, class Stage2>
+TTC_HD void walk_mode(const LaneLim& x, int vec_slot, const PosEntry* my, const PosCoord* myc, uint32_t cnt,
+                      Stage1&& stage1, Stage2&& stage2)
+{
+    uint32_t k = 0;
+    for (; k + U <= cnt; k += U) walk_group<U, V, MODE>(x, vec_slot, my + k, myc + k, stage1, stage2);
+    for (; k < cnt; ++k) walk_group<1, V, MODE>(x, vec_slot, my + k, myc + k, stage1, stage2);
+}
+
+// Drive one wavefront through its share of a walk with V elements per lane and access.
+template <int U, int V, class Stage1, class Stage2>
 TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const WalkMask& m, const PosEntry* tab,
                  const PosCoord* tabc, uint32_t wave, Stage1&& stage1, Stage2&& stage2)
 {
@@ -257,14 +288,9 @@ TTC_HD void walk(const Side& s, const LaneState& L, const SideLim& lim, const Wa
     const PosEntry* my = tab + wave * (uint32_t)s.chunk;
     const PosCoord* myc = tabc + wave * (uint32_t)s.chunk;
     const LaneLim x = lane_lim(L, lim);
-    uint32_t k = 0;
-    if (!m.dynamic) {
-        for (; k + U <= cnt; k += U) walk_group<U, true>(x, my + k, myc + k, stage1, stage2);
-        for (; k < cnt; ++k) walk_group<1, true>(x, my + k, myc + k, stage1, stage2);
-    } else {
-        for (; k + U <= cnt; k += U) walk_group<U, false>(x, my + k, myc + k, stage1, stage2);
-        for (; k < cnt; ++k) walk_group<1, false>(x, my + k, myc + k, stage1, stage2);
-    }
+    if (!m.dynamic) walk_mode<U, V, kWalkFull>(x, 0, my, myc, cnt, stage1, stage2);
+    else if (V == 1 || !s.partial) walk_mode<U, V, kWalkMasked>(x, 0, my, myc, cnt, stage1, stage2);
+    else walk_mode<U, V, kWalkPartial>(x, s.vec_slot, my, myc, cnt, stage1, stage2);
 }
 
 // Fill the two tables of one walk (all threads of the workgroup take part).

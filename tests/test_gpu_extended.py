@@ -227,3 +227,24 @@ def test_search_results_persist_through_the_plan_store(tmp_path, monkeypatch):
     ttc.ttc_plan_destroy(q)
     want = oracle.transpose(wl.F32, sizes, perm, 1.5, 0.0, A, np.zeros(n, np.float32))
     assert np.array_equal(dB.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("dtype,sizes,perm", [
+    (wl.F32, (135, 137), (1, 0)), (wl.F32, (19, 19, 19, 19), (3, 2, 1, 0)), (wl.F64, (21, 5, 33, 9), (2, 0, 3, 1)),
+    (wl.F32, (45, 9, 37), (0, 2, 1)), (wl.C64, (27, 31, 5), (1, 2, 0)), (wl.F64_F32, (17, 3, 23, 11), (3, 1, 0, 2)),
+    (wl.F32_F64, (85, 85, 7), (1, 0, 2)),
+], ids=["f32-2d", "f32-4d", "f64-4d", "f32-fixed", "c64-3d", "f64f32-4d", "f32f64-3d"])
+def test_cut_vectors(dtype, sizes, perm):
+    """Odd extents: the candidates that keep full-width vectors and cut the last one of every run."""
+    p = ttc.ttc_plan_create_ex(dtype, len(sizes), sizes, perm)
+    picks = []
+    for k in range(ttc.ttc_plan_candidate_count(p)):
+        ttc.ttc_plan_select_candidate(p, k)
+        i = ttc.ttc_plan_get_info(p)
+        if i["partial_a"] or i["partial_b"]:
+            picks.append(k)
+    ttc.ttc_plan_destroy(p)
+    assert picks
+    for n, k in enumerate(picks[::max(1, len(picks) // 24)]):
+        al, be = scalars(dtype, n)
+        check(dtype, sizes, perm, al, be, seed=n, candidate=k)

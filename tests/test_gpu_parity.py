@@ -40,8 +40,8 @@ def gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate=None, tune=False):
     dB = torch.from_numpy(B0).to(dev)
     plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
     try:
-        if candidate is not None:
-            ttc.ttc_plan_select_candidate(plan, candidate)
+        if candidate is not None:       # the list depends on whether beta is 0: wrap
+            ttc.ttc_plan_select_candidate(plan, candidate % ttc.ttc_plan_candidate_count(plan))
         if tune:
             scratch = torch.empty_like(dB)
             ttc.ttc_plan_tune(plan, dA.data_ptr(), scratch.data_ptr(), torch.cuda.current_stream().cuda_stream, 0)

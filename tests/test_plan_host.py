@@ -320,3 +320,46 @@ def test_plan_store_later_entry_wins_and_damage_is_ignored(tmp_path):
         finally:
             ttc.ttc_plan_destroy(q)
     assert e.value.status == ttc.TTC_ERR_IO
+
+
+def test_walks_with_cut_vectors():
+    """Odd extents: candidates that use full-width vectors and cut the last one of every run."""
+    seen = 0
+    for dtype, sizes, perm in [(ttc.TTC_F32, (35, 37), (1, 0)), (ttc.TTC_F32, (19, 19, 19), (2, 1, 0)),
+                               (ttc.TTC_F64, (21, 5, 33), (2, 0, 1)), (ttc.TTC_F32, (45, 9, 7), (0, 2, 1)),
+                               (ttc.TTC_C64, (27, 31), (1, 0)), (ttc.TTC_F64_F32, (17, 3, 23), (2, 1, 0))]:
+        p = plan(dtype, sizes, perm)
+        want = [-1] * int(np.prod(sizes))
+        for off_a, off_b in oracle.element_pairs(sizes, perm):
+            want[off_b] = off_a
+        for k in range(ttc.ttc_plan_candidate_count(p)):
+            ttc.ttc_plan_select_candidate(p, k)
+            i = ttc.ttc_plan_get_info(p)
+            if not (i["partial_a"] or i["partial_b"]) or seen % 7:
+                seen += bool(i["partial_a"] or i["partial_b"])
+                continue
+            seen += 1
+            assert list(ttc.ttc_debug_emulate_map(p)) == want, (sizes, perm, k, i)
+        ttc.ttc_plan_destroy(p)
+    assert seen > 50
+
+
+def test_cut_vectors_never_overlap_where_b_is_read():
+    """beta != 0: an overlapping vector would read elements of B its neighbour may already have updated."""
+    for dtype, sizes, perm in [(ttc.TTC_F32, (35, 37), (1, 0)), (ttc.TTC_F32, (45, 9, 7), (0, 2, 1)),
+                               (ttc.TTC_F64, (21, 5, 33), (2, 0, 1))]:
+        p = plan(dtype, sizes, perm, 0.75, 1.25)
+        want = [-1] * int(np.prod(sizes))
+        for off_a, off_b in oracle.element_pairs(sizes, perm):
+            want[off_b] = off_a
+        cut_a = 0
+        for k in range(ttc.ttc_plan_candidate_count(p)):
+            ttc.ttc_plan_select_candidate(p, k)
+            i = ttc.ttc_plan_get_info(p)
+            assert i["partial_b"] == 0
+            if i["kernel_class"] == ttc.TTC_KERNEL_DIRECT:
+                assert i["partial_a"] == 0
+            if i["partial_a"] and cut_a % 5 == 0:
+                assert list(ttc.ttc_debug_emulate_map(p)) == want, (sizes, perm, k, i)
+            cut_a += i["partial_a"]
+        ttc.ttc_plan_destroy(p)
