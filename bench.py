@@ -39,6 +39,8 @@ def parse():
                     help="plan search cap: 0 = library default (200), 1 = heuristic only, -1 = all")
     ap.add_argument("--cases", type=str, default="", help="comma-separated substrings of case names (default: all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-heuristic", action="store_true",
+                    help="do not time the heuristic's first candidate separately (keeps a profile to one configuration)")
     ap.add_argument("--plan-cache", type=str, default="",
                     help="file of stored search results (TTC_PLAN_CACHE): cases found there are not searched again")
     return ap.parse_args()
@@ -152,13 +154,13 @@ def main() -> int:
 
         plan = ttc.ttc_plan_create(c.dtype, len(c.sizes), c.sizes, c.perm, c.alpha, c.beta)
         heur = ttc.ttc_plan_get_info(plan)
-        ms_heur = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, K)
+        ms_heur = None if args.no_heuristic else ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, K)
         t0 = time.perf_counter()
         ttc.ttc_plan_tune_pairs(plan, a_ptrs, b_ptrs, stream, args.max_candidates)
         tune_s = time.perf_counter() - t0
         info = ttc.ttc_plan_get_info(plan)
         ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, K)
-        if ms_heur < ms:                           # the search is noisy: never do worse than the heuristic
+        if ms_heur is not None and ms_heur < ms:   # the search is noisy: never do worse than the heuristic
             ttc.ttc_plan_select_candidate(plan, 0)
             info = ttc.ttc_plan_get_info(plan)
             ms = ms_heur
@@ -171,7 +173,7 @@ def main() -> int:
             "frac_axpby_stream": round(gbps / axpby, 4) if not c.beta_is_zero else None,
             "d2d_copy_GBps": round(d2d, 1), "copy_kernel_GBps": round(copy_k, 1),
             "memcpy_GBps": round(copy_m, 1), "axpby_stream_GBps": round(axpby, 1),
-            "heuristic_GBps": round(c.traffic_bytes / ms_heur / 1e6, 1),
+            "heuristic_GBps": round(c.traffic_bytes / ms_heur / 1e6, 1) if ms_heur is not None else None,
             "candidate": info["candidate_index"], "candidates": info["candidate_count"],
             "tune_s": round(tune_s, 2),
             "kernel_class": "direct" if info["kernel_class"] == ttc.TTC_KERNEL_DIRECT else "lds",
@@ -180,7 +182,7 @@ def main() -> int:
         }
         results.append(r)
         log(f"[gpu] {c.name}: {gbps:.0f} GB/s = {100 * r['frac_d2d_copy']:.1f}% of D2D copy ({d2d:.0f}), "
-            f"heuristic {r['heuristic_GBps']:.0f}, cand {r['candidate']}/{r['candidates']}, "
+            f"heuristic {r['heuristic_GBps'] or 0:.0f}, cand {r['candidate']}/{r['candidates']}, "
             f"{r['kernel_class']} tile {r['tile']} vec {r['vec']} thr {r['threads']}")
         del A_dev, B_dev
         torch.cuda.empty_cache()
