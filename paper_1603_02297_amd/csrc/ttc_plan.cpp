@@ -808,7 +808,7 @@ static int max_vec(int eb, int64_t extent)
 
 // Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
 struct LaunchShape { int threads, wg_per_cu; };
-static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}};
+static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}, {512, 8}};
 
 static void enumerate(const Problem& P, std::vector<Candidate>& out)
 {

@@ -121,8 +121,7 @@ struct LaneState {
     int64_t g;                 // byte offset into the tensor the walk follows
     int64_t g2;                // direct kernel: byte offset into B
     int32_t l;                 // byte offset into the LDS tile
-    int32_t c[kBoxDims];       // flat coordinate along each digit, in elements
-    uint32_t c01, c23;         // the same, 16 bits per digit
+    uint32_t c01, c23;         // flat coordinate along each digit, in elements, 16 bits per digit
     bool    active;
 };
 
@@ -132,21 +131,22 @@ TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, const Scales& scale)
     LaneState L;
     L.g = 0; L.g2 = 0; L.l = 0;
     L.active = lane < (uint32_t)s.lanes;
+    uint32_t cs[kBoxDims];
 #pragma unroll
     for (int j = 0; j < kBoxDims; ++j) {
-        L.c[j] = 0;
+        cs[j] = 0;
         if (s.d[j].lane > 1) {
             const Digit& d = s.d[j];
             const int32_t c = (int32_t)fdigit(lane, d.lane_below, d.lane_cnt) * d.lane_mul;
-            L.c[j] = c;
+            cs[j] = (uint32_t)c;
             L.g += (int64_t)c * d.gstride;
             if (DIRECT) L.g2 += (int64_t)c * d.g2stride;
             else L.l += c * d.lstride;
         }
     }
     L.g *= scale.g; L.g2 *= scale.g2; L.l *= scale.l;
-    L.c01 = (uint32_t)L.c[0] | ((uint32_t)L.c[1] << 16);
-    L.c23 = (uint32_t)L.c[2] | ((uint32_t)L.c[3] << 16);
+    L.c01 = cs[0] | (cs[1] << 16);
+    L.c23 = cs[2] | (cs[3] << 16);
     return L;
 }
 
@@ -263,7 +263,8 @@ TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
 #pragma unroll
     for (int j = 0; j < kBoxDims; ++j) {
         const Digit& d = s.d[j];
-        if (d.iters == 1) m.lane_ok = m.lane_ok & (L.c[j] < lim.lim[j]);
+        const int32_t c = (int32_t)(((j & 2) ? L.c23 : L.c01) >> ((j & 1) ? 16 : 0)) & 0xffff;
+        if (d.iters == 1) m.lane_ok = m.lane_ok & (c < lim.lim[j]);
         else m.dynamic = m.dynamic | (lim.lim[j] != d.tile) | (d.ragged != 0);
     }
     return m;
