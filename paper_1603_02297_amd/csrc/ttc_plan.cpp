@@ -722,11 +722,11 @@ static AccessShape access_shape(const Problem& P, const Candidate& C)
 
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
-    // Weights fitted to timings of every candidate of some forty problems on MI355X (the benchmark
-    // workloads plus 2-D to 6-D problems with odd, small and large extents; log-linear least squares
-    // weighted towards the fast candidates), rounded, with guard rails outside the measured range.
+    // Weights fitted to timings of every candidate of thirty problems on MI355X (the benchmark workloads
+    // plus 3-D and 5-D problems with odd extents in two shapes; log-linear least squares weighted towards
+    // the fast candidates), rounded, with guard rails outside the measured range.
     const KernelParams& kp = C.kp;
-    const double eb = std::max(P.eb_a, P.eb_b), eb_a = P.eb_a, eb_b = P.eb_b;
+    const double eb_a = P.eb_a, eb_b = P.eb_b;
     const bool direct = (C.kernel_class == TTC_KERNEL_DIRECT);
     auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
     double volume = 1, padded = 1;
@@ -734,47 +734,51 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
         volume *= kp.tile[k];
         padded *= (double)ceil_div(P.size[k], kp.tile[k]) * kp.tile[k] / (double)P.size[k];
     }
-    const double tile_bytes = volume * eb;
+    const double tile_bytes = volume * eb_a;
     const AccessShape sh = access_shape(P, C);
     const double run_a = sh.run[0], run_b = sh.run[1], seg_a = sh.seg[0], seg_b = sh.seg[1];
     const int vec_b = direct ? kp.a.vec : kp.b.vec;
     double e = 0.0;
     // coalescing: the contiguous run per tile and the contiguous piece per wavefront instruction; writes
     // are the sensitive side, and runs that start off a 128-byte line pay for the lines they share
-    e += 0.003 * oct_below(run_a, 1024.0) + 0.006 * oct_below(run_b, 1024.0);
-    e += 0.25 * oct_below(run_a, 64.0) + 0.32 * oct_below(run_b, 64.0);
-    e += 0.03 * (1.0 - sh.align[0] / 128.0) * 128.0 / run_a + 0.09 * (1.0 - sh.align[1] / 128.0) * 128.0 / run_b;
-    e += 0.017 * oct_below(seg_a, 256.0) + 0.020 * oct_below(seg_b, 256.0);
-    e += 0.10 * oct_below(seg_a, 64.0) + 0.32 * oct_below(seg_b, 64.0);
-    e += (kp.a.vec * eb_a >= 16 ? 0.0 : (kp.a.vec * eb_a >= 8 ? 0.016 : 0.047));
-    e += (vec_b * eb_b >= 16 ? 0.0 : (vec_b * eb_b >= 8 ? 0.007 : 0.024));
-    e += 0.25 * (padded - 1.0);                                         // lanes idle in remainder tiles
+    e += 0.010 * oct_below(run_a, 1024.0) + 0.009 * oct_below(run_b, 1024.0);
+    e += 0.15 * oct_below(run_a, 64.0) + 0.20 * oct_below(run_b, 64.0);
+    e += 0.025 * (1.0 - sh.align[0] / 128.0) * 128.0 / run_a + 0.10 * (1.0 - sh.align[1] / 128.0) * 128.0 / run_b;
+    e += 0.024 * oct_below(seg_a, 256.0) + 0.023 * oct_below(seg_b, 256.0);
+    e += 0.066 * oct_below(seg_a, 64.0) + 0.10 * oct_below(seg_b, 64.0);
+    e += (kp.a.vec * eb_a >= 16 ? 0.0 : (kp.a.vec * eb_a >= 8 ? 0.044 : 0.068));
+    e += (vec_b * eb_b >= 16 ? 0.0 : (vec_b * eb_b >= 8 ? 0.0 : 0.003));
+    if (kp.a.partial) e += 0.075;                                       // every position of the walk tests its bounds
+    e += 0.21 * (padded - 1.0);                                         // lanes idle in remainder tiles
     // tile size and occupancy
     const double lo = direct ? 16384.0 : 8192.0;
-    e += 0.18 * oct_below(tile_bytes, lo);
-    if (tile_bytes > 16384.0) e -= 0.025 * std::min(2.0, std::log2(tile_bytes / 16384.0));
+    e += 0.20 * oct_below(tile_bytes, lo);
+    if (tile_bytes > 16384.0) e -= 0.07 * std::min(1.0, std::log2(tile_bytes / 16384.0));
+    if (tile_bytes > 32768.0) e -= 0.017 * std::min(1.0, std::log2(tile_bytes / 32768.0));
     const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
-    e += 0.055 * (lane_a - 1.0);
+    e += 0.09 * (lane_a - 1.0);
     if (direct) {
         // no regrouping through LDS: every instruction's piece meets memory as it is
-        e += 0.15 * (1.0 - sh.align[0] / 128.0) * 128.0 / seg_a + 0.15 * (1.0 - sh.align[1] / 128.0) * 128.0 / seg_b;
+        e += 0.07 * (1.0 - sh.align[0] / 128.0) * 128.0 / seg_a + 0.07 * (1.0 - sh.align[1] / 128.0) * 128.0 / seg_b;
     } else {
-        const double resident_waves = std::min(32.0, std::floor(160.0 * 1024 / C.lds_bytes) * (C.threads / kWave));
-        if (resident_waves < 16.0) e += 0.19 * (16.0 - resident_waves) / 16.0;
-        if (resident_waves < 8.0) e += 0.13 * (8.0 - resident_waves) / 8.0;
+        const double groups = std::min(16.0, std::floor(160.0 * 1024 / C.lds_bytes));
+        const double resident_waves = std::min(32.0, groups * (C.threads / kWave));
+        if (resident_waves < 16.0) e += 0.27 * (16.0 - resident_waves) / 16.0;
+        if (resident_waves < 8.0) e += 0.12 * (8.0 - resident_waves) / 8.0;
+        if (groups < 4.0) e += 0.047 * (4.0 - groups) / 4.0;
         const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
-        e += 0.03 * (lane_b - 1.0);
-        e += 0.002 * (C.lds_conflict_a + C.lds_conflict_b - 4);
-        e += 0.024;
+        e += 0.02 * (lane_b - 1.0);
     }
-    // launch shape: measured preference
-    if (C.threads == 128) e -= 0.03;
-    if (C.wg_per_cu == 4) e += 0.008;
-    else if (C.wg_per_cu == 8) e += 0.007;
-    bool b_order = true;
-    for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
-    if (!b_order) e += 0.023;
-    if (kp.num_tiles < 2048) e += 0.39 * (2048.0 - kp.num_tiles) / 2048.0;   // too few tiles to fill the chip
+    // launch shape and tile order: measured preference
+    if (C.threads == 128) e -= 0.048;
+    else if (C.threads == 512) e += 0.093;
+    bool b_order = true, a_order = true;
+    for (int i = 0; i < P.ndim; ++i) {
+        if (C.tile_order[i] != P.perm[i]) b_order = false;
+        if (C.tile_order[i] != i) a_order = false;
+    }
+    if (!b_order) e += a_order ? 0.033 : 0.004;
+    if (kp.num_tiles < 2048) e += 0.6 * (2048.0 - kp.num_tiles) / 2048.0;    // too few tiles to fill the chip
     return std::exp(e);
 }
 

@@ -124,8 +124,9 @@ def d2d_copy_gbps(nbytes, a_ptrs, b_ptrs, stream):
 
 
 # ---- study 1: reduction of the search space -------------------------------------------------------
-def study_search(out):
+def study_search(out, dump=None):
     import torch
+    import json
     stream = torch.cuda.current_stream().cuda_stream
     bufs = Buffers()
     caps = (1, 10, 100, 200)
@@ -142,6 +143,8 @@ def study_search(out):
         rows = retime_best(plan, time_candidates(plan, a_ptrs, b_ptrs, stream), a_ptrs, b_ptrs, stream)
         ttc.ttc_plan_destroy(plan)
         ms = np.array([r[1] for r in rows])
+        if dump is not None:        # every candidate's configuration and time, one JSON line per problem
+            dump.write(json.dumps({"problem": name, "rows": [dict(r[0], ms=r[1]) for r in rows]}) + "\n")
         best = ms.min()
         frac = [best / ms[:k].min() for k in caps]
         table.append((name, len(rows), rows[0][0]["bytes_moved"] / best / 1e6, frac))
@@ -241,6 +244,7 @@ def main(argv=None):
     ap.add_argument("study", choices=("search", "sweep"))
     ap.add_argument("--out", default="", help="write the table to this file (default: stdout)")
     ap.add_argument("--limit", type=int, default=0, help="sweep: only the first LIMIT cases")
+    ap.add_argument("--dump", default="", help="search: also write every candidate's configuration and time (JSON lines)")
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
@@ -251,7 +255,13 @@ def main(argv=None):
     t0 = time.time()
     print(f"# python -m paper_1603_02297_amd.studies {args.study}" + (f" --limit {args.limit}" if args.limit else ""), file=out)
     if args.study == "search":
-        study_search(out)
+        dump = None
+        if args.dump:
+            import gzip
+            dump = gzip.open(args.dump, "wt") if args.dump.endswith(".gz") else open(args.dump, "w")
+        study_search(out, dump)
+        if dump:
+            dump.close()
     else:
         study_sweep(out, args.limit or None)
     print(f"# {time.time() - t0:.0f} s", file=out)
