@@ -248,3 +248,22 @@ def test_cut_vectors(dtype, sizes, perm):
     for n, k in enumerate(picks[::max(1, len(picks) // 24)]):
         al, be = scalars(dtype, n)
         check(dtype, sizes, perm, al, be, seed=n, candidate=k)
+
+
+def test_tensor_beyond_4_gib():
+    """Byte offsets past 2^32: a 4.5 GB fp32 tensor, every element compared."""
+    sizes, perm = (1040, 1024, 1056), (2, 1, 0)
+    n = prod(sizes)
+    assert n * 4 > 2 ** 32
+    A = np.random.default_rng(2 ** 32 + 1).random(n, dtype=np.float32)
+    want = oracle.transpose(wl.F32, sizes, perm, 1.0, 0.0, A, np.empty(n, np.float32), 16)
+    dev = torch.device("cuda:0")
+    dA = torch.from_numpy(A).to(dev)
+    dB = torch.empty(n, dtype=torch.float32, device=dev)
+    plan = ttc.ttc_plan_create(wl.F32, 3, sizes, perm, None, None)
+    ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ttc.ttc_plan_destroy(plan)
+    got = dB.cpu().numpy()
+    del dA, dB
+    assert np.array_equal(got, want)

@@ -33,6 +33,20 @@ def ulp(x, real):
     return float(np.spacing(np.abs(real(x))))
 
 
+def test_listing_address_map_golden_file():
+    """tests/golden/listing_address_map_2x3x4.txt: the address map of the paper's Section 3.5 listing for
+    permutation (i3,i2,i1), written by a script that evaluates the printed formula only."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "listing_address_map_2x3x4.txt")
+    pairs = [tuple(int(x) for x in line.split()) for line in open(path) if not line.startswith("#")]
+    assert len(pairs) == 24 and sorted(a for a, _ in pairs) == list(range(24))
+    assert sorted(oracle.element_pairs((2, 3, 4), (2, 1, 0))) == sorted(pairs)
+    A = np.arange(24, dtype=np.float32)
+    B = run(F32, (2, 3, 4), (2, 1, 0), 1.0, 0.0, A)
+    for off_a, off_b in pairs:
+        assert B[off_b] == off_a
+
+
 # -- pin 1: closed-form address map printed in the paper's parallel-code listing (Section 3.5):
 #    permutation (i3,i2,i1) reads A[i1 + i2*lda1 + i3*lda2] and writes B[i1*ldb2 + i2*ldb1 + i3].
 @pytest.mark.parametrize("sizes", [(2, 3, 4), (5, 1, 3), (7, 6, 5)])

@@ -221,6 +221,21 @@ def test_walks_random_5d_6d():
         check_all_candidates(ttc.TTC_F32, sizes, perm, max_candidates=6)
 
 
+def test_library_walks_realise_the_listing_address_map():
+    """The golden address map of the paper's Section 3.5 listing, against every candidate's replayed walk."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "listing_address_map_2x3x4.txt")
+    pairs = [tuple(int(x) for x in line.split()) for line in open(path) if not line.startswith("#")]
+    want = [-1] * 24
+    for off_a, off_b in pairs:
+        want[off_b] = off_a
+    p = plan(ttc.TTC_F32, (2, 3, 4), (2, 1, 0))
+    for k in range(ttc.ttc_plan_candidate_count(p)):
+        ttc.ttc_plan_select_candidate(p, k)
+        assert list(ttc.ttc_debug_emulate_map(p)) == want
+    ttc.ttc_plan_destroy(p)
+
+
 # ---- sub-tensors (paper Table 1, --lda / --ldb) ------------------------------------------------
 @pytest.mark.parametrize("dtype", [ttc.TTC_F32, ttc.TTC_F64, ttc.TTC_C128_C64])
 @pytest.mark.parametrize("sizes,perm,lda,ldb", [
