@@ -267,3 +267,36 @@ def test_tensor_beyond_4_gib():
     got = dB.cpu().numpy()
     del dA, dB
     assert np.array_equal(got, want)
+
+
+def test_search_cap_semantics(monkeypatch):
+    """max_candidates: 1 keeps the heuristic's choice untimed, a positive cap times that many, -1 all;
+    0 takes TTC_MAX_CANDIDATES from the environment (paper Table 1, --maxImplementations)."""
+    monkeypatch.delenv("TTC_PLAN_CACHE", raising=False)
+    dev = torch.device("cuda:0")
+    sizes, perm = (48, 36, 20), (2, 0, 1)
+    n = prod(sizes)
+    dA = torch.rand(n, dtype=torch.float32, device=dev)
+    dB = torch.empty(n, dtype=torch.float32, device=dev)
+    s = torch.cuda.current_stream().cuda_stream
+
+    def timed(cap):
+        p = ttc.ttc_plan_create(wl.F32, 3, sizes, perm, None, None)
+        ttc.ttc_plan_tune(p, dA.data_ptr(), dB.data_ptr(), s, cap)
+        count, sel = 0, ttc.ttc_plan_get_info(p)["candidate_index"]
+        total = ttc.ttc_plan_candidate_count(p)
+        for k in range(total):
+            ttc.ttc_plan_select_candidate(p, k)
+            count += ttc.ttc_plan_get_info(p)["tuned_ms"] > 0
+        ttc.ttc_plan_destroy(p)
+        return count, sel, total
+
+    count, sel, total = timed(1)
+    assert count == 0 and sel == 0
+    count, sel, _ = timed(7)
+    assert count == 7 and sel < 7
+    count, _, _ = timed(-1)
+    assert count == total
+    monkeypatch.setenv("TTC_MAX_CANDIDATES", "5")
+    count, sel, _ = timed(0)
+    assert count == 5 and sel < 5
