@@ -83,6 +83,8 @@ typedef struct {
     int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
     int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + tile buffer(s) */
     int     lds_buffers;                   /* 2: tile buffers alternate (one barrier per tile), 1: one buffer (two barriers) */
+    int     nt_a, nt_b;                    /* 1: loads of A / stores to B (and loads of B if beta != 0) carry the
+                                              non-temporal hint (the paper's streaming stores, and their load counterpart) */
     int     lds_conflict_a, lds_conflict_b;/* modelled worst bank multiplicity of the LDS write / read instructions */
     int     run_bytes_a, run_bytes_b;      /* contiguous bytes the tile spans in A / in B */
     int     seg_bytes_a, seg_bytes_b;      /* contiguous bytes one wavefront instruction covers in A / in B */
@@ -158,10 +160,19 @@ int ttc_plan_candidate_count(ttc_plan_t plan);
 int ttc_plan_select_candidate(ttc_plan_t plan, int index);
 
 /*
+ * Non-temporal ("streaming") accesses of the selected candidate (paper Table 1, --no-streaming-stores, here
+ * for loads as well): stream_a for the loads of A, stream_b for the stores to B and the loads of B when
+ * beta != 0.  1 = on, 0 = off, -1 = the planner's rule (a side streams if all its runs are whole 128-byte
+ * lines).  The direct kernel streams both sides or neither.  Host only.
+ */
+int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b);
+
+/*
  * Search (paper Section 3: candidates are timed and the fastest becomes the solution;
  * Table 1 --maxImplementations).  Times at most max_candidates candidates, in heuristic
  * rank order, on the caller's buffers and stream (HIP events, a few launches each) and
- * selects the fastest.  max_candidates: 0 = environment TTC_MAX_CANDIDATES or 200,
+ * selects the fastest; the best few are timed again, also with the non-temporal hints
+ * switched the other way.  max_candidates: 0 = environment TTC_MAX_CANDIDATES or 200,
  * 1 = keep the heuristic choice without timing, -1 = all candidates.
  * A_scratch / B_scratch are DEVICE buffers of prod(sizes) elements; B_scratch is
  * overwritten.  SYNCHRONISES the stream.
@@ -206,7 +217,7 @@ int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, voi
  * Bandwidth ceilings measured the same way (the role of the STREAM/SAXPY lines in the
  * paper's Section 4).  kind 0: dst <- src with a 128-bit-per-lane copy kernel (1 read, 1
  * write); kind 1: hipMemcpyAsync device-to-device; kind 2: dst <- 0.75*src + 1.25*dst as
- * fp32 (2 reads, 1 write).  `bytes` must be a multiple of 16 and the pointers 16-byte
+ * fp32 (2 reads, 1 write); kind 3: the copy kernel of kind 0 with non-temporal loads and stores.  `bytes` must be a multiple of 16 and the pointers 16-byte
  * aligned.  Buffer pairs rotate as in ttc_time_execute.  SYNCHRONISES.
  */
 int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src_list,

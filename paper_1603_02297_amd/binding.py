@@ -24,7 +24,7 @@ EXPORTS = (
     "ttc_plan_create", "ttc_plan_create_ex", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
     "ttc_plan_get_info", "ttc_plan_candidate_count", "ttc_plan_select_candidate", "ttc_plan_tune",
     "ttc_plan_tune_pairs", "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
-    "ttc_plan_cache_store", "ttc_plan_cache_lookup",
+    "ttc_plan_cache_store", "ttc_plan_cache_lookup", "ttc_plan_set_streaming",
 )
 
 
@@ -41,6 +41,7 @@ class ttc_plan_info_t(ctypes.Structure):
         ("vec_a", ctypes.c_int), ("vec_b", ctypes.c_int), ("partial_a", ctypes.c_int), ("partial_b", ctypes.c_int),
         ("threads", ctypes.c_int), ("wg_per_cu", ctypes.c_int),
         ("xcd_remap", ctypes.c_int), ("lds_bytes", ctypes.c_int), ("lds_buffers", ctypes.c_int),
+        ("nt_a", ctypes.c_int), ("nt_b", ctypes.c_int),
         ("lds_conflict_a", ctypes.c_int), ("lds_conflict_b", ctypes.c_int),
         ("run_bytes_a", ctypes.c_int), ("run_bytes_b", ctypes.c_int), ("seg_bytes_a", ctypes.c_int),
         ("seg_bytes_b", ctypes.c_int), ("align_a", ctypes.c_int), ("align_b", ctypes.c_int),
@@ -106,6 +107,8 @@ def lib() -> ctypes.CDLL:
         L.ttc_time_execute.argtypes = [vp, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
         L.ttc_time_ceiling.restype = i
         L.ttc_time_ceiling.argtypes = [i, ctypes.c_int64, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
+        L.ttc_plan_set_streaming.restype = i
+        L.ttc_plan_set_streaming.argtypes = [vp, i, i]
         L.ttc_plan_cache_store.restype = i
         L.ttc_plan_cache_store.argtypes = [vp, ctypes.c_char_p]
         L.ttc_plan_cache_lookup.restype = i
@@ -238,6 +241,13 @@ def ttc_time_ceiling(kind: int, nbytes: int, src_list: Sequence[int], dst_list: 
     if st != TTC_OK:
         raise TtcError(st, "ttc_time_ceiling")
     return ms.value
+
+
+def ttc_plan_set_streaming(plan: int, stream_a: int = -1, stream_b: int = -1) -> None:
+    """Non-temporal accesses of the selected candidate: 1 on, 0 off, -1 the planner's rule."""
+    st = lib().ttc_plan_set_streaming(plan, int(stream_a), int(stream_b))
+    if st != TTC_OK:
+        raise TtcError(st, "ttc_plan_set_streaming")
 
 
 def ttc_plan_cache_store(plan: int, path: str) -> None:

@@ -15,7 +15,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libttc.so")
-SOURCES = ["ttc_plan.cpp", "ttc_cache.cpp", "ttc_device.hip"]
+SOURCES = ["ttc_launch_f32.hip", "ttc_launch_mixed_real.hip", "ttc_launch_f64.hip", "ttc_launch_c64.hip",
+           "ttc_launch_mixed_complex.hip", "ttc_launch_c128.hip", "ttc_plan.cpp", "ttc_cache.cpp", "ttc_device.hip"]
 
 
 def _flags(verbose: bool):

@@ -4,9 +4,9 @@
 // text per problem in a file the caller names.
 //
 // Line format (all integers, blank separated):
-//   ttc1 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
+//   ttc2 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
 //   <kernel_class> <threads> <wg_per_cu> <lds_buffers> <vec_a> <vec_b> <tile x6> <tile_order x6>
-//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> | <microseconds>
+//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> | <nt_a> <nt_b> <microseconds>
 // The left part is the key: the fused problem as the planner sees it.  The middle part names a
 // candidate by its configuration, not by its rank, so an entry survives changes of the ranking;
 // if no candidate of the current library matches, the entry is ignored.  Later lines win.
@@ -20,7 +20,7 @@
 
 namespace ttc {
 
-static const char* kMagic = "ttc1";
+static const char* kMagic = "ttc2";
 static const char* kArch = "gfx950";
 
 static std::string problem_key(const Problem& P)
@@ -56,7 +56,7 @@ int cache_store(const ttc_plan_s* plan, const char* path)
     std::ostringstream o;
     o << problem_key(plan->prob) << " |";
     for (long long x : config_signature(c)) o << ' ' << x;
-    o << " | " << (long long)(c.tuned_ms * 1000.0f + 0.5f) << '\n';
+    o << " | " << c.kp.nt_a << ' ' << c.kp.nt_b << ' ' << (long long)(c.tuned_ms * 1000.0f + 0.5f) << '\n';
     const std::string line = o.str();
     std::FILE* f = std::fopen(path, "a");
     if (!f) return TTC_ERR_IO;
@@ -77,8 +77,8 @@ int cache_lookup(ttc_plan_s* plan, const char* path)
     }
     std::fclose(f);
     if (hit.empty()) return TTC_ERR_NOT_FOUND;
-    // "<signature> | <microseconds>"
-    std::vector<long long> sig;
+    // "<signature> | <nt_a> <nt_b> <microseconds>"
+    std::vector<long long> sig, tailv;
     long long us = 0;
     {
         std::istringstream in(hit);
@@ -89,12 +89,16 @@ int cache_lookup(ttc_plan_s* plan, const char* path)
             char* end = nullptr;
             const long long v = std::strtoll(tok.c_str(), &end, 10);
             if (!end || *end != '\0') return TTC_ERR_NOT_FOUND;          // damaged line: treat as absent
-            if (tail) us = v; else sig.push_back(v);
+            if (tail) tailv.push_back(v); else sig.push_back(v);
         }
     }
+    if (tailv.size() != 3 || (tailv[0] | 1) != 1 || (tailv[1] | 1) != 1) return TTC_ERR_NOT_FOUND;
+    us = tailv[2];
     for (size_t i = 0; i < plan->cands.size(); ++i) {
         if (config_signature(plan->cands[i]) == sig) {
             plan->selected = (int)i;
+            plan->cands[i].kp.nt_a = (int)tailv[0];
+            plan->cands[i].kp.nt_b = (int)tailv[1];
             plan->cands[i].tuned_ms = (float)us / 1000.0f;
             return TTC_OK;
         }

@@ -85,9 +85,9 @@ struct KernelParams {
     int32_t  lds_data_off;           // byte offset of the first data buffer in dynamic LDS
     int32_t  lds_tile_elems;         // elements per LDS data buffer (padded tile)
     int32_t  lds_buffers;            // 2: tile buffers alternate, one barrier per tile; 1: one buffer, two barriers
-    int32_t  pad3;
+    int32_t  nt_a;                   // 1: loads of A carry the non-temporal hint (streamed, not kept in cache)
     int32_t  nslots;                 // indices the box spans
-    int32_t  pad2;
+    int32_t  nt_b;                   // 1: stores to B, and loads of B when beta != 0, carry the non-temporal hint
     Slot     slot[kBoxDims];
     int32_t  tile[kMaxDim];          // box extent per fused index of A (1 = index not blocked)
     FastDiv  tile_below[kMaxDim];    // prod of tile counts of the indices that vary faster in the tile order
@@ -156,5 +156,6 @@ int cache_lookup(ttc_plan_s* plan, const char* path);
 // Workgroups to launch for a candidate on a device with `cus` compute units.
 uint32_t launch_grid(const Candidate& c, int cus);
 void set_grid(KernelParams* kp, uint32_t grid);
+void default_streaming(const Problem& P, Candidate* c);
 
 }  // namespace ttc

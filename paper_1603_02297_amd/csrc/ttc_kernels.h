@@ -1,0 +1,373 @@
+// The tile ("box") kernels for gfx950 (MI355X) and their launch templates.  Included by one
+// translation unit per group of element types (ttc_launch_*.hip), so that the groups compile in parallel.
+//
+// One kernel template serves both cases of the paper's Section 3.1.
+//   * staged (stride-1 index changes):  a workgroup owns one box of the tensor that spans the
+//     leading indices of A *and* of B.  Wavefronts walk the box in A order with vector loads
+//     (lanes along A's stride-1 index), park it in LDS, and after one barrier walk it again in B
+//     order (lanes along B's stride-1 index), apply the alpha/beta epilogue and store vectors.
+//   * direct (stride-1 index fixed, or 1-D):  the same walk, but every lane stores what it
+//     loaded; no LDS, no barrier.
+// A walk is factorised CDNA-style: the 64 lanes of a wavefront cover a fixed sub-box (lane
+// offsets are computed once and live in VGPRs), and the position of that sub-box inside the
+// tile is wave-uniform, so the per-instruction index arithmetic runs on the scalar unit.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "ttc_internal.h"
+#include "ttc_walk.h"
+
+namespace ttc {
+
+// ---------------------------------------------------------------------------------
+// Element types and the alpha/beta epilogue (fixed evaluation order; built with
+// -ffp-contract=off so the only fused operations are the ones written here).
+//   real:    copy: r = a | scale: r = alpha*a | axpby: t = beta*b, r = fma(alpha, a, t)
+//   complex: product z = s*x as z.re = fma(s.re, x.re, -(s.im*x.im)), z.im = fma(s.re, x.im, s.im*x.re);
+//            scale: r = alpha*a | axpby: r = alpha*a + beta*b componentwise
+// Mixed precision (A and B of different precision): elements are widened to double, the same
+// formulas run in double, the result is rounded once (to nearest even) to B's type.
+// ---------------------------------------------------------------------------------
+struct alignas(8) cfloat { float re, im; };
+struct alignas(8) cdouble { double re, im; };
+
+// Global vectors are only guaranteed element alignment (gfx950 global dwordx2/x4 accesses need
+// no more); the hardware runs them at full rate at any 4-byte boundary.
+template <typename T, int V> struct alignas(alignof(T)) Pack { T v[V]; };
+
+template <typename To, typename From> struct Convert;
+template <typename T> struct Convert<T, T> { __device__ static __forceinline__ T go(T x) { return x; } };
+template <> struct Convert<double, float> { __device__ static __forceinline__ double go(float x) { return (double)x; } };
+template <> struct Convert<float, double> { __device__ static __forceinline__ float go(double x) { return (float)x; } };
+template <> struct Convert<cdouble, cfloat> {
+    __device__ static __forceinline__ cdouble go(cfloat x) { cdouble r; r.re = (double)x.re; r.im = (double)x.im; return r; }
+};
+template <> struct Convert<cfloat, cdouble> {
+    __device__ static __forceinline__ cfloat go(cdouble x) { cfloat r; r.re = (float)x.re; r.im = (float)x.im; return r; }
+};
+
+__device__ __forceinline__ float fused(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fused(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// the arithmetic, in the type it runs in
+template <typename C, int MODE> struct Core {                    // C = float or double
+    C al, be;
+    __device__ explicit Core(const KernelParams& p) : al((C)p.alpha[0]), be((C)p.beta[0]) {}
+    __device__ __forceinline__ C operator()(C a, C b) const
+    {
+        if (MODE == TTC_EPI_COPY) return a;
+        if (MODE == TTC_EPI_SCALE) return al * a;
+        const C t = be * b;
+        return fused(al, a, t);
+    }
+};
+
+template <typename Z, typename R, int MODE> struct ComplexCore {  // Z = cfloat / cdouble over R = float / double
+    R ar, ai, br, bi;
+    __device__ explicit ComplexCore(const KernelParams& p)
+        : ar((R)p.alpha[0]), ai((R)p.alpha[1]), br((R)p.beta[0]), bi((R)p.beta[1]) {}
+    __device__ __forceinline__ Z operator()(Z a, Z b) const
+    {
+        if (MODE == TTC_EPI_COPY) return a;
+        Z p;
+        p.re = fused(ar, a.re, -(ai * a.im));
+        p.im = fused(ar, a.im, ai * a.re);
+        if (MODE == TTC_EPI_SCALE) return p;
+        Z q;
+        q.re = fused(br, b.re, -(bi * b.im));
+        q.im = fused(br, b.im, bi * b.re);
+        Z r;
+        r.re = p.re + q.re;
+        r.im = p.im + q.im;
+        return r;
+    }
+};
+template <int MODE> struct Core<cfloat, MODE> : ComplexCore<cfloat, float, MODE> { using ComplexCore<cfloat, float, MODE>::ComplexCore; };
+template <int MODE> struct Core<cdouble, MODE> : ComplexCore<cdouble, double, MODE> { using ComplexCore<cdouble, double, MODE>::ComplexCore; };
+
+// type the arithmetic runs in: the common type, or the double-precision one when they differ
+template <typename TA, typename TB> struct Wider;
+template <typename T> struct Wider<T, T> { using type = T; };
+template <> struct Wider<float, double> { using type = double; };
+template <> struct Wider<double, float> { using type = double; };
+template <> struct Wider<cfloat, cdouble> { using type = cdouble; };
+template <> struct Wider<cdouble, cfloat> { using type = cdouble; };
+
+template <typename TA, typename TB, int MODE> struct Epilogue {
+    using C = typename Wider<TA, TB>::type;
+    Core<C, MODE> core;
+    __device__ explicit Epilogue(const KernelParams& p) : core(p) {}
+    __device__ __forceinline__ TB operator()(TA a, TB b) const
+    {
+        return Convert<TB, C>::go(core(Convert<C, TA>::go(a), Convert<C, TB>::go(b)));
+    }
+};
+
+// ---------------------------------------------------------------------------------
+// The kernel.  Dynamic LDS: [two shared tile records][spare slots][position tables of both walks][tile buffer 0][tile buffer 1].
+// Cut vectors: where a run is not a multiple of the vector width, the lane that would overhang moves its
+// vector back so that it ends with the run (`back` elements, handed to the stages).  It then repeats what
+// its neighbour does for those elements, with the same values, so nothing diverges and every access stays a
+// full vector.
+// A workgroup walks several tiles; with two tile buffers one barrier per tile is enough: a
+// wavefront can only start filling buffer (t+1)%2 after it passed the barrier of tile t, and
+// every wavefront reached that barrier after it had finished reading that buffer for tile t-1.
+// ---------------------------------------------------------------------------------
+// memory instructions a wavefront keeps in flight per walk step: four 16-byte accesses per lane, more of the
+// narrow ones (the bytes in flight per wavefront are what hides the memory latency)
+template <typename T, int V> struct Unroll { static constexpr int value = (V * sizeof(T) >= 16) ? 4 : 8; };
+
+__device__ __forceinline__ int64_t uniform64(int64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Non-temporal accesses (the paper's streaming stores, Table 1 / Section 3.4, and their load counterpart):
+// data that is touched once need not displace what neighbouring tiles will share.  The hint is a compile-time
+// property of an access; a walk exists in both forms and the (wave-uniform) flag picks one per tile.
+template <int N> struct Words;
+template <> struct Words<1> { typedef uint32_t type; };
+template <> struct Words<2> { typedef uint32_t type __attribute__((ext_vector_type(2), aligned(4))); };
+template <> struct Words<4> { typedef uint32_t type __attribute__((ext_vector_type(4), aligned(4))); };
+template <> struct Words<8> { typedef uint32_t type __attribute__((ext_vector_type(8), aligned(4))); };
+
+template <typename T, int V, bool NT>
+__device__ __forceinline__ Pack<T, V> load_pack(const unsigned char* base, int64_t off)
+{
+    typedef typename Words<V * sizeof(T) / 4>::type W;
+    if (NT) {
+        union { W w; Pack<T, V> p; } u;
+        u.w = __builtin_nontemporal_load(reinterpret_cast<const W*>(base + off));
+        return u.p;
+    }
+    return *reinterpret_cast<const Pack<T, V>*>(base + off);
+}
+
+template <typename T, int V, bool NT>
+__device__ __forceinline__ void store_pack(unsigned char* base, int64_t off, const Pack<T, V>& v)
+{
+    typedef typename Words<V * sizeof(T) / 4>::type W;
+    if (NT) {
+        union { W w; Pack<T, V> p; } u;
+        u.p = v;
+        __builtin_nontemporal_store(u.w, reinterpret_cast<W*>(base + off));
+    } else {
+        *reinterpret_cast<Pack<T, V>*>(base + off) = v;
+    }
+}
+
+template <typename TA, typename TB, int MODE, int VA, int VB, bool DIRECT>
+__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const TA* __restrict__ A,
+                                                          TB* __restrict__ B)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
+    const Scales sc_a = {kScaleA, kScaleB, kScaleA};     // walk over A; the LDS tile holds elements of A
+    const Scales sc_b = {kScaleB, kScaleB, kScaleA};     // walk over B
+    const uint32_t nwave = blockDim.x >> 6;
+    const uint32_t n_a = nwave * (uint32_t)p.a.chunk, n_b = DIRECT ? 0u : nwave * (uint32_t)p.b.chunk;
+    TileShare* share = reinterpret_cast<TileShare*>(smem);            // two slots, kTileShareBytes in all
+    PosEntry* tab_a = reinterpret_cast<PosEntry*>(smem + kTablesOff);
+    PosEntry* tab_b = tab_a + n_a;
+    PosCoord* tabc_a = reinterpret_cast<PosCoord*>(tab_b + n_b);
+    PosCoord* tabc_b = tabc_a + n_a;
+
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    build_tables<DIRECT>(p.a, nwave, threadIdx.x, blockDim.x, sc_a, tab_a, tabc_a);
+    if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, sc_b, tab_b, tabc_b);
+    const LaneState LA = lane_setup<DIRECT>(p.a, lane, sc_a);
+    const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, sc_b);
+    const Epilogue<TA, TB, MODE> epi(p);
+    const bool nt_a = p.nt_a != 0, nt_b = p.nt_b != 0;
+    unsigned char* spare = smem + kTileShareBytes + lane * 16;      // where this lane parks what it must not keep
+    const TileSeq seq = tile_sequence(p, blockIdx.x);
+
+    // Staged kernel: the last wavefront works out where a tile lies (scalar divisions and
+    // multiplications) one tile ahead and leaves the result in LDS; the barrier that already
+    // separates the two walks of the current tile publishes it to the other wavefronts.
+    auto publish = [&](uint32_t tile, uint32_t slot) {
+        const TileBase tb = tile_base(p, tile);
+        const TileLim tl = tile_lim(p, tile);
+        TileShare v;
+        v.a = tb.a; v.b = tb.b;
+        v.lim[0] = tl.lim[0]; v.lim[1] = tl.lim[1]; v.lim[2] = tl.lim[2]; v.lim[3] = tl.lim[3];
+        share[slot] = v;
+    };
+    if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(seq.first, 0);
+    __syncthreads();
+
+    uint32_t parity = 0;
+    for (uint32_t tile = seq.first; tile < seq.end; tile += seq.step) {
+        TileBase tb;
+        TileLim tl;
+        if (DIRECT) {
+            tb = tile_base(p, tile);
+            tl = tile_lim(p, tile);
+        } else {
+            const TileShare v = share[parity];
+            tb.a = uniform64(v.a); tb.b = uniform64(v.b);
+            tl.lim[0] = __builtin_amdgcn_readfirstlane(v.lim[0]); tl.lim[1] = __builtin_amdgcn_readfirstlane(v.lim[1]);
+            tl.lim[2] = __builtin_amdgcn_readfirstlane(v.lim[2]); tl.lim[3] = __builtin_amdgcn_readfirstlane(v.lim[3]);
+            tl.whole = false;
+        }
+        const unsigned char* At = reinterpret_cast<const unsigned char*>(A + tb.a);
+        unsigned char* Bt = reinterpret_cast<unsigned char*>(B + tb.b);
+        const SideLim sla = side_lim(p.a, tl);
+        const WalkMask wma = walk_mask(p.a, LA, sla);
+        if (DIRECT) {
+            auto run = [&](auto stream) {            // the direct kernel streams both tensors or neither
+                constexpr bool NT = decltype(stream)::value;
+                constexpr int kUnroll = Unroll<TA, VA>::value;
+                Pack<TA, VA> ra[kUnroll];
+                Pack<TB, VA> rb[kUnroll];
+                auto load = [&](int u, const PosEntry& e, int back, bool ok) {
+                    ra[u] = load_pack<TA, VA, NT>(At, ok ? e.g + LA.g - back * kScaleA : 0);
+                    if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VA, NT>(Bt, ok ? e.l_or_g2 + LA.g2 - back * kScaleB : 0);
+                };
+                auto store = [&](int u, const PosEntry& e, int back, bool ok) {
+                    if (!ok) return;
+                    Pack<TB, VA> out;
+#pragma unroll
+                    for (int j = 0; j < VA; ++j) {
+                        TB old = TB();
+                        if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
+                        out.v[j] = epi(ra[u].v[j], old);
+                    }
+                    store_pack<TB, VA, NT>(Bt, e.l_or_g2 + LA.g2 - back * kScaleB, out);
+                };
+                walk<kUnroll, VA>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, store);
+            };
+            if (nt_a && nt_b) run(std::true_type()); else run(std::false_type());
+            continue;
+        }
+
+        unsigned char* lds = smem + p.lds_data_off +
+                             (parity & (uint32_t)(p.lds_buffers - 1)) * (uint32_t)(p.lds_tile_elems * kScaleA);
+        parity ^= 1u;
+        // ---- walk 1: A order, global -> LDS
+        {
+            auto run = [&](auto stream) {
+                constexpr bool NT = decltype(stream)::value;
+                const int32_t vs = p.a.vec_lds_stride;
+                constexpr int kUnroll = Unroll<TA, VA>::value;
+                Pack<TA, VA> ra[kUnroll];
+                auto load = [&](int u, const PosEntry& e, int back, bool ok) {
+                    ra[u] = load_pack<TA, VA, NT>(At, ok ? e.g + LA.g - back * kScaleA : 0);
+                };
+                auto park = [&](int u, const PosEntry& e, int back, bool ok) {
+                    unsigned char* dst = lds + ((int32_t)e.l_or_g2 + LA.l - back * vs * kScaleA);
+#pragma unroll
+                    for (int j = 0; j < VA; ++j)
+                        *reinterpret_cast<TA*>(ok ? dst + j * vs * kScaleA : spare) = ra[u].v[j];
+                };
+                walk<kUnroll, VA>(p.a, LA, sla, wma, tab_a, tabc_a, wave, load, park);
+            };
+            if (nt_a) run(std::true_type()); else run(std::false_type());
+        }
+        if (wave == nwave - 1 && tile + seq.step < seq.end) publish(tile + seq.step, parity);   // parity already flipped
+        __syncthreads();
+        // ---- walk 2: B order, LDS -> epilogue -> global
+        {
+            const SideLim slb = side_lim(p.b, tl);
+            const WalkMask wmb = walk_mask(p.b, LB, slb);
+            auto run = [&](auto stream) {
+                constexpr bool NT = decltype(stream)::value;
+                const int32_t vs = p.b.vec_lds_stride;
+                constexpr int kUnroll = Unroll<TB, VB>::value;
+                Pack<TB, VB> rb[kUnroll];
+                Pack<TA, VB> rl[kUnroll];
+                auto load = [&](int u, const PosEntry& e, int back, bool ok) {
+                    if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, VB, NT>(Bt, ok ? e.g + LB.g - back * kScaleB : 0);
+                    const TA* src = reinterpret_cast<const TA*>(lds + (ok ? (int32_t)e.l_or_g2 + LB.l - back * vs * kScaleA : 0));
+#pragma unroll
+                    for (int j = 0; j < VB; ++j) rl[u].v[j] = src[j * vs];
+                };
+                auto store = [&](int u, const PosEntry& e, int back, bool ok) {
+                    if (!ok) return;
+                    Pack<TB, VB> out;
+#pragma unroll
+                    for (int j = 0; j < VB; ++j) {
+                        TB old = TB();
+                        if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
+                        out.v[j] = epi(rl[u].v[j], old);
+                    }
+                    store_pack<TB, VB, NT>(Bt, e.g + LB.g - back * kScaleB, out);
+                };
+                walk<kUnroll, VB>(p.b, LB, slb, wmb, tab_b, tabc_b, wave, load, store);
+            };
+            if (nt_b) run(std::true_type()); else run(std::false_type());
+        }
+        if (p.lds_buffers == 1) __syncthreads();      // the one buffer is refilled by the next tile
+    }
+}
+
+// Compute units of the current device (256 on MI355X), asked once per process and device.
+inline int device_cus()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// ---------------------------------------------------------------------------------
+// Dispatch
+// ---------------------------------------------------------------------------------
+template <typename TA, typename TB, int MODE, int VA, int VB, bool DIRECT>
+inline hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uint32_t grid, int threads,
+                             int lds_bytes, hipStream_t stream)
+{
+    if (grid != kp.grid || grid < 1 || grid > kp.num_tiles) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((box_kernel<TA, TB, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
+                       kp, static_cast<const TA*>(A), static_cast<TB*>(B));
+    return hipGetLastError();
+}
+
+// VMAXA / VMAXB: elements of each type in 16 bytes
+template <typename TA, typename TB, int MODE, int VMAXA, int VMAXB>
+inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
+{
+    KernelParams kp = c.kp;
+    const uint32_t grid = launch_grid(c, device_cus());
+    set_grid(&kp, grid);
+    const int va = kp.a.vec, vb = kp.b.vec;
+    constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct kernel: one width for both sides
+    if (c.kernel_class == TTC_KERNEL_DIRECT) {
+        if (va == 1) return launch_one<TA, TB, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 2 && VD >= 2) return launch_one<TA, TB, MODE, (VD >= 2 ? 2 : 1), (VD >= 2 ? 2 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        if (va == 4 && VD >= 4) return launch_one<TA, TB, MODE, (VD >= 4 ? 4 : 1), (VD >= 4 ? 4 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
+        return hipErrorInvalidValue;
+    }
+#define TTC_CASE(VA_, VB_)                                                                                   \
+    if (va == VA_ && vb == VB_ && VA_ <= VMAXA && VB_ <= VMAXB)                                              \
+        return launch_one<TA, TB, MODE, (VA_ <= VMAXA ? VA_ : 1), (VB_ <= VMAXB ? VB_ : 1), false>(          \
+            kp, A, B, grid, c.threads, c.lds_bytes, s);
+    TTC_CASE(1, 1) TTC_CASE(1, 2) TTC_CASE(2, 1) TTC_CASE(2, 2)
+    TTC_CASE(1, 4) TTC_CASE(2, 4) TTC_CASE(4, 1) TTC_CASE(4, 2) TTC_CASE(4, 4)
+#undef TTC_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename TA, typename TB, int VMAXA, int VMAXB>
+inline hipError_t launch_mode(const Problem& P, const Candidate& c, const void* A, void* B, hipStream_t s)
+{
+    switch (P.epilogue) {
+    case TTC_EPI_COPY:  return launch_vec<TA, TB, TTC_EPI_COPY, VMAXA, VMAXB>(c, A, B, s);
+    case TTC_EPI_SCALE: return launch_vec<TA, TB, TTC_EPI_SCALE, VMAXA, VMAXB>(c, A, B, s);
+    default:            return launch_vec<TA, TB, TTC_EPI_AXPBY, VMAXA, VMAXB>(c, A, B, s);
+    }
+}
+
+}  // namespace ttc

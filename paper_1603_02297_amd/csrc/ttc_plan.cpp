@@ -636,7 +636,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     set_chunks(&kp.a);
     set_chunks(&kp.b);
     const int64_t tab_entries = (int64_t)nwave * (kp.a.chunk + (direct ? 0 : kp.b.chunk));
-    const int tab_bytes = (int)round_up(kTileShareBytes + 24 * tab_entries, 16);
+    const int tab_bytes = (int)round_up(kTablesOff + 24 * tab_entries, 16);
     C.lds_bytes += tab_bytes - kp.lds_data_off;
     kp.lds_data_off = tab_bytes;
     if (C.lds_bytes > kMaxLdsBytes) return false;
@@ -796,11 +796,23 @@ static bool same_config(const Candidate& x, const Candidate& y)
     return true;
 }
 
+// Non-temporal hints by rule: a side streams if all its runs are whole 128-byte lines.  Then no line is
+// shared with a neighbouring tile, and keeping it in cache would only displace lines that are.  (The timed
+// search tries the other settings on its finalists.)
+void default_streaming(const Problem& P, Candidate* c)
+{
+    const AccessShape sh = access_shape(P, *c);
+    c->kp.nt_a = (sh.align[0] >= 128) ? 1 : 0;
+    c->kp.nt_b = (sh.align[1] >= 128) ? 1 : 0;
+    if (c->kernel_class == TTC_KERNEL_DIRECT) c->kp.nt_a = c->kp.nt_b = (c->kp.nt_a && c->kp.nt_b) ? 1 : 0;   // both or neither
+}
+
 static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Candidate& c)
 {
     for (const Candidate& o : v) if (same_config(o, c)) return;
     v.push_back(c);
-    v.back().score = heuristic_cost(P, c);
+    default_streaming(P, &v.back());
+    v.back().score = heuristic_cost(P, v.back());
 }
 
 static int max_vec(int eb, int64_t extent)
@@ -943,6 +955,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
         if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c,
                             true, true, nullptr, b.kp.lds_buffers))
             return TTC_ERR_OVERFLOW;
+        default_streaming(P, &c);
         c.score = heuristic_cost(P, c);
         plan->cands.push_back(c);
         plan->fallback = (int)plan->cands.size() - 1;
@@ -1054,6 +1067,8 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->xcd_remap = C.kp.xcd_remap;
     out->lds_bytes = C.lds_bytes;
     out->lds_buffers = C.kp.lds_buffers;
+    out->nt_a = C.kp.nt_a;
+    out->nt_b = C.kp.nt_b;
     out->lds_conflict_a = C.lds_conflict_a;
     out->lds_conflict_b = C.lds_conflict_b;
     {
@@ -1072,6 +1087,19 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
+    return TTC_OK;
+}
+
+int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b)
+{
+    if (!plan) return TTC_ERR_NULL_POINTER;
+    if (stream_a < -1 || stream_a > 1 || stream_b < -1 || stream_b > 1) return TTC_ERR_INVALID_VALUE;
+    ttc::Candidate& C = plan->cands[plan->selected];
+    ttc::Candidate rule = C;
+    ttc::default_streaming(plan->prob, &rule);
+    C.kp.nt_a = stream_a < 0 ? rule.kp.nt_a : stream_a;
+    C.kp.nt_b = stream_b < 0 ? rule.kp.nt_b : stream_b;
+    if (C.kernel_class == TTC_KERNEL_DIRECT) C.kp.nt_a = C.kp.nt_b = (C.kp.nt_a && C.kp.nt_b) ? 1 : 0;
     return TTC_OK;
 }
 
@@ -1123,7 +1151,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     };
     // position tables, as a workgroup builds them
     const uint32_t ta = nwave * (uint32_t)p.a.chunk, tbn = direct ? 0u : nwave * (uint32_t)p.b.chunk;
-    if (kTileShareBytes + (int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
+    if (kTablesOff + (int64_t)24 * (ta + tbn) > p.lds_data_off) return TTC_ERR_INTERNAL;
     if (p.a.chunk_rem < 1 || p.a.chunk_rem > (int)nwave || (p.a.chunk - 1) * (int)nwave + p.a.chunk_rem != p.a.n_iter)
         return TTC_ERR_INTERNAL;
     if (!direct && (p.b.chunk_rem < 1 || p.b.chunk_rem > (int)nwave ||
@@ -1147,7 +1175,7 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     int fail_line = 0;
     auto fail_at = [&](int line) { if (!bad) fail_line = line; bad = true; };
 #define fail() fail_at(__LINE__)
-    auto nop = [](int, const PosEntry&, int) {};
+    auto nop = [](int, const PosEntry&, int, bool) {};
     const bool axpby = (P.epilogue == TTC_EPI_AXPBY);
     std::vector<int64_t> writer((size_t)P.span_b, -1);      // which instruction wrote an element of B
     int64_t written = 0;
@@ -1160,12 +1188,18 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
             const int64_t base_a = tb.a * eba, base_b = tb.b * ebb;
             const TileLim tl = tile_lim(p, tile);
             const SideLim la = side_lim(p.a, tl);
+            // lanes outside the tile load the tile's first vector instead (and read the LDS tile's first slots)
+            for (int j = 0; j < p.a.vec; ++j) if (!inside(tb.a + j, P.stride_a, false)) return TTC_ERR_INTERNAL;
+            for (int j = 0; j < (direct ? p.a.vec : p.b.vec); ++j)
+                if (!inside(tb.b + j, P.stride_b, true)) return TTC_ERR_INTERNAL;
+            if (!direct && (int64_t)(p.b.vec - 1) * p.b.vec_lds_stride >= p.lds_tile_elems) return TTC_ERR_INTERNAL;
             if (direct) {
                 for (uint32_t wave = 0; wave < nwave; ++wave)
                     for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                         const LaneState L = lane_setup<true>(p.a, lane, sc_a);
                         const WalkMask wm = walk_mask(p.a, L, la);
-                        auto st = [&](int, const PosEntry& e, int back) {
+                        auto st = [&](int, const PosEntry& e, int back, bool ok) {
+                            if (!ok) return;
                             const int64_t oa = base_a + e.g + L.g, ob = base_b + e.l_or_g2 + L.g2;
                             if (oa % eba || ob % ebb || back < 0 || back >= p.a.vec) return fail();
                             const int64_t who = ((int64_t)tile << 32) | (wave << 16) | (uint32_t)(&e - tab_a.data());
@@ -1189,7 +1223,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.a, lane, sc_a);
                     const WalkMask wm = walk_mask(p.a, L, la);
-                    auto st = [&](int, const PosEntry& e, int back) {
+                    auto st = [&](int, const PosEntry& e, int back, bool ok) {
+                        if (!ok) return;
                         const int64_t oa = base_a + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
                         if (oa % eba || lo % eba || back < 0 || back >= p.a.vec) return fail();
@@ -1210,7 +1245,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
                 for (uint32_t lane = 0; lane < (uint32_t)kWave; ++lane) {
                     const LaneState L = lane_setup<false>(p.b, lane, sc_b);
                     const WalkMask wm = walk_mask(p.b, L, lb);
-                    auto st = [&](int, const PosEntry& e, int back) {
+                    auto st = [&](int, const PosEntry& e, int back, bool ok) {
+                        if (!ok) return;
                         const int64_t ob = base_b + e.g + L.g;
                         const int64_t lo = (int64_t)(int32_t)e.l_or_g2 + L.l;
                         if (ob % ebb || lo % eba || back < 0 || back >= p.b.vec) return fail();

@@ -57,6 +57,9 @@ struct TileBase { int64_t a, b; };
 // what one wavefront works out for the others about a tile (two of these sit at the start of LDS)
 struct alignas(16) TileShare { int64_t a, b; int32_t lim[kBoxDims]; };
 constexpr int kTileShareBytes = 2 * (int)sizeof(TileShare);
+// after them: one spare slot of 16 bytes per lane of a wavefront, where lanes outside a tile park what they loaded
+constexpr int kSpareBytes = 64 * 16;
+constexpr int kTablesOff = kTileShareBytes + kSpareBytes;
 
 TTC_HD TileBase tile_base(const KernelParams& p, uint32_t tile)
 {
@@ -227,8 +230,11 @@ TTC_HD uint32_t wave_positions(const Side& s, uint32_t wave)
 enum { kWalkFull = 0, kWalkMasked = 1, kWalkPartial = 2 };
 
 // U positions at a time: stage1 for all U (issue the loads), then stage2 for all U (consume
-// them), so that U memory instructions are in flight per wavefront.  stage(u, entry, back):
-// u = slot 0..U-1, back = elements the lane's vector is moved back by (0 unless the walk is partial).
+// them), so that U memory instructions are in flight per wavefront.  stage(u, entry, back, ok):
+// u = slot 0..U-1, back = elements the lane's vector is moved back by (0 unless the walk is partial),
+// ok = the lane's element lies inside the tile.  Stages run for every lane: a lane that is not ok must
+// do something harmless (load the tile's first vector, write to a spare LDS slot, skip a global store),
+// so that no load sits inside divergent control flow, where it would be waited for on the spot.
 template <int U, int V, int MODE, class Stage1, class Stage2>
 TTC_HD void walk_group(const LaneLim& x, int vec_slot, const PosEntry* e_ptr, const PosCoord* c_ptr,
                        Stage1&& stage1, Stage2&& stage2)
@@ -244,10 +250,10 @@ TTC_HD void walk_group(const LaneLim& x, int vec_slot, const PosEntry* e_ptr, co
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (back[u] >= 0) stage1(u, e[u], MODE == kWalkPartial ? back[u] : 0);
+        stage1(u, e[u], (MODE == kWalkPartial && back[u] > 0) ? back[u] : 0, MODE == kWalkFull ? true : back[u] >= 0);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (back[u] >= 0) stage2(u, e[u], MODE == kWalkPartial ? back[u] : 0);
+        stage2(u, e[u], (MODE == kWalkPartial && back[u] > 0) ? back[u] : 0, MODE == kWalkFull ? true : back[u] >= 0);
 }
 
 // What a walk has to test per lane in one tile.  Digits with a single sub-box position are

@@ -300,3 +300,25 @@ def test_search_cap_semantics(monkeypatch):
     monkeypatch.setenv("TTC_MAX_CANDIDATES", "5")
     count, sel, _ = timed(0)
     assert count == 5 and sel < 5
+
+
+@pytest.mark.parametrize("dtype,sizes,perm,alpha,beta", [
+    (wl.F32, (128, 96, 40), (2, 1, 0), 1.5, 0.0), (wl.F32, (85, 33, 47), (1, 2, 0), 1.0, 0.0),
+    (wl.F64, (64, 20, 48), (0, 2, 1), 0.75, 1.25), (wl.C64, (32, 24, 40), (2, 0, 1), 0.5 + 0.5j, 1.0),
+], ids=["f32-aligned", "f32-odd", "f64-direct", "c64"])
+def test_streaming_accesses_change_nothing_in_the_result(dtype, sizes, perm, alpha, beta):
+    n = prod(sizes)
+    A = wl.uniform_tensor(dtype, n, 11, "a")
+    B0 = wl.uniform_tensor(dtype, n, 12, "b")
+    want = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy(), 4)
+    dev = torch.device("cuda:0")
+    dA = torch.from_numpy(A).to(dev)
+    s = torch.cuda.current_stream().cuda_stream
+    plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+    for sa, sb in ((0, 0), (1, 1), (1, 0), (0, 1), (-1, -1)):
+        ttc.ttc_plan_set_streaming(plan, sa, sb)
+        dB = torch.from_numpy(B0).to(dev)
+        ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), s)
+        torch.cuda.synchronize()
+        assert ulp_distance(dB.cpu().numpy(), want) <= 1, (sa, sb, ttc.ttc_plan_get_info(plan))
+    ttc.ttc_plan_destroy(plan)

@@ -378,3 +378,32 @@ def test_cut_vectors_never_overlap_where_b_is_read():
                 assert list(ttc.ttc_debug_emulate_map(p)) == want, (sizes, perm, k, i)
             cut_a += i["partial_a"]
         ttc.ttc_plan_destroy(p)
+
+
+# ---- non-temporal accesses (paper Table 1: streaming stores) -----------------------------------
+def test_streaming_rule_and_override():
+    p = plan(ttc.TTC_F32, (384, 384, 384), (2, 1, 0), 1.5, 0.0)         # every run is whole 128-byte lines
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 1 and i["nt_b"] == 1
+    ttc.ttc_plan_set_streaming(p, 0, -1)
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 0 and i["nt_b"] == 1
+    ttc.ttc_plan_set_streaming(p, -1, 0)
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 1 and i["nt_b"] == 0
+    with pytest.raises(ttc.TtcError):
+        ttc.ttc_plan_set_streaming(p, 2, 0)
+    ttc.ttc_plan_destroy(p)
+    p = plan(ttc.TTC_F32, (85, 85, 85), (2, 1, 0))                      # 340-byte rows: lines are shared
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 0 and i["nt_b"] == 0
+    ttc.ttc_plan_destroy(p)
+    p = plan(ttc.TTC_F32, (384, 24, 24), (0, 2, 1))                     # direct kernel: both sides or neither
+    assert ttc.ttc_plan_get_info(p)["kernel_class"] == ttc.TTC_KERNEL_DIRECT
+    ttc.ttc_plan_set_streaming(p, 1, 0)
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 0 and i["nt_b"] == 0
+    ttc.ttc_plan_set_streaming(p, 1, 1)
+    i = ttc.ttc_plan_get_info(p)
+    assert i["nt_a"] == 1 and i["nt_b"] == 1
+    ttc.ttc_plan_destroy(p)
