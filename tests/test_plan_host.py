@@ -399,6 +399,10 @@ def test_streaming_rule_and_override():
     assert i["nt_a"] == 0 and i["nt_b"] == 0
     ttc.ttc_plan_destroy(p)
     p = plan(ttc.TTC_F32, (384, 24, 24), (0, 2, 1))                     # direct kernel: both sides or neither
+    for k in range(ttc.ttc_plan_candidate_count(p)):
+        ttc.ttc_plan_select_candidate(p, k)
+        if ttc.ttc_plan_get_info(p)["kernel_class"] == ttc.TTC_KERNEL_DIRECT:
+            break
     assert ttc.ttc_plan_get_info(p)["kernel_class"] == ttc.TTC_KERNEL_DIRECT
     ttc.ttc_plan_set_streaming(p, 1, 0)
     i = ttc.ttc_plan_get_info(p)
