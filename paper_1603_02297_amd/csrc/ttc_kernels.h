@@ -161,11 +161,36 @@ __device__ __forceinline__ void store_pack(unsigned char* base, int64_t off, con
     }
 }
 
+// what one wavefront left in LDS about a tile and a walk, as the (wave-uniform) limits and the lane's own verdict
+__device__ __forceinline__ void take_side(const SideShare& v, uint32_t single, const LaneState& L, SideLim* sl, WalkMask* wm)
+{
+    sl->lim[0] = __builtin_amdgcn_readfirstlane(v.lim[0]); sl->lim[1] = __builtin_amdgcn_readfirstlane(v.lim[1]);
+    sl->lim[2] = __builtin_amdgcn_readfirstlane(v.lim[2]); sl->lim[3] = __builtin_amdgcn_readfirstlane(v.lim[3]);
+    sl->t01 = __builtin_amdgcn_readfirstlane(v.t01); sl->t23 = __builtin_amdgcn_readfirstlane(v.t23);
+    wm->dynamic = __builtin_amdgcn_readfirstlane(v.dynamic) != 0;
+    wm->lane_ok = lane_inside(single, L, *sl);
+}
+
 template <typename TA, typename TB, int MODE, int VA, int VB, bool DIRECT>
-__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, const TA* __restrict__ A,
+__global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams params_by_value, const TA* __restrict__ A,
                                                           TB* __restrict__ B)
 {
+    // The parameter block is read where the launch put it, at the start of the kernel-argument segment (constant
+    // memory, scalar loads).  Reading the by-value argument instead leaves it to the optimiser to see through the
+    // copy the language asks for, and past a certain number of uses it keeps the copy: 1.4 KB of scratch per lane.
+    const KernelParams& p = *reinterpret_cast<const KernelParams*>((const void*)__builtin_amdgcn_kernarg_segment_ptr());
     extern __shared__ __align__(16) unsigned char smem[];
+#if 1
+    {   // Bring the whole parameter block into the scalar cache at once (read-only scalar loads of one word per
+        // 64-byte line): the set-up code below reads it piece by piece, and each piece would otherwise be a miss.
+        typedef const uint32_t __attribute__((address_space(4))) ConstWord;
+        const ConstWord* args = (const ConstWord*)__builtin_amdgcn_kernarg_segment_ptr();
+        uint32_t touched = 0;
+#pragma unroll
+        for (int i = 0; i < (int)(sizeof(KernelParams) / 64); ++i) touched ^= args[i * 16];
+        asm volatile("" :: "s"(touched));
+    }
+#endif
     constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
     const Scales sc_a = {kScaleA, kScaleB, kScaleA};     // walk over A; the LDS tile holds elements of A
     const Scales sc_b = {kScaleB, kScaleB, kScaleA};     // walk over B
@@ -192,35 +217,38 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
     // Staged kernel: the last wavefront works out where a tile lies (scalar divisions and
     // multiplications) one tile ahead and leaves the result in LDS; the barrier that already
     // separates the two walks of the current tile publishes it to the other wavefronts.
-    auto publish = [&](uint32_t tile, uint32_t slot) {
+    auto publish = [&](uint32_t tile, uint32_t slot) __attribute__((always_inline)) {     // (not inlined, it would need the parameter block in memory)
         const TileBase tb = tile_base(p, tile);
         const TileLim tl = tile_lim(p, tile);
         TileShare v;
         v.a = tb.a; v.b = tb.b;
-        v.lim[0] = tl.lim[0]; v.lim[1] = tl.lim[1]; v.lim[2] = tl.lim[2]; v.lim[3] = tl.lim[3];
+        v.sa = make_side_share(p.a, tl);
+        v.sb = make_side_share(p.b, tl);
         share[slot] = v;
     };
+    const uint32_t single_a = single_digits(p.a), single_b = DIRECT ? 0u : single_digits(p.b);
     if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(seq.first, 0);
     __syncthreads();
 
     uint32_t parity = 0;
     for (uint32_t tile = seq.first; tile < seq.end; tile += seq.step) {
         TileBase tb;
-        TileLim tl;
+        SideLim sla, slb;
+        WalkMask wma, wmb;
         if (DIRECT) {
             tb = tile_base(p, tile);
-            tl = tile_lim(p, tile);
+            const TileLim tl = tile_lim(p, tile);
+            sla = side_lim(p.a, tl);
+            wma = walk_mask(p.a, LA, sla);
+            slb = sla; wmb = wma;
         } else {
             const TileShare v = share[parity];
             tb.a = uniform64(v.a); tb.b = uniform64(v.b);
-            tl.lim[0] = __builtin_amdgcn_readfirstlane(v.lim[0]); tl.lim[1] = __builtin_amdgcn_readfirstlane(v.lim[1]);
-            tl.lim[2] = __builtin_amdgcn_readfirstlane(v.lim[2]); tl.lim[3] = __builtin_amdgcn_readfirstlane(v.lim[3]);
-            tl.whole = false;
+            take_side(v.sa, single_a, LA, &sla, &wma);
+            take_side(v.sb, single_b, LB, &slb, &wmb);
         }
         const unsigned char* At = reinterpret_cast<const unsigned char*>(A + tb.a);
         unsigned char* Bt = reinterpret_cast<unsigned char*>(B + tb.b);
-        const SideLim sla = side_lim(p.a, tl);
-        const WalkMask wma = walk_mask(p.a, LA, sla);
         if (DIRECT) {
             auto run = [&](auto stream) {            // the direct kernel streams both tensors or neither
                 constexpr bool NT = decltype(stream)::value;
@@ -275,8 +303,6 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams p, 
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
         {
-            const SideLim slb = side_lim(p.b, tl);
-            const WalkMask wmb = walk_mask(p.b, LB, slb);
             auto run = [&](auto stream) {
                 constexpr bool NT = decltype(stream)::value;
                 const int32_t vs = p.b.vec_lds_stride;

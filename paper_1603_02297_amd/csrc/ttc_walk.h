@@ -55,7 +55,10 @@ TTC_HD TileSeq tile_sequence(const KernelParams& p, uint32_t wg)
 // tile id -> element offsets of the box origin in A and in B
 struct TileBase { int64_t a, b; };
 // what one wavefront works out for the others about a tile (two of these sit at the start of LDS)
-struct alignas(16) TileShare { int64_t a, b; int32_t lim[kBoxDims]; };
+// (per walk: the tile's limits in the walk's digits, packed for the bounds test, and whether the walk has to
+// test its positions in this tile, so that the other wavefronts read all of it instead of deriving it again)
+struct alignas(16) SideShare { int32_t lim[kBoxDims]; uint32_t t01, t23, dynamic, pad; };
+struct alignas(16) TileShare { int64_t a, b; SideShare sa, sb; };
 constexpr int kTileShareBytes = 2 * (int)sizeof(TileShare);
 // after them: one spare slot of 16 bytes per lane of a wavefront, where lanes outside a tile park what they loaded
 constexpr int kSpareBytes = 64 * 16;
@@ -82,15 +85,12 @@ TTC_HD TileLim tile_lim(const KernelParams& p, uint32_t tile)
     TileLim t;
     t.whole = true;
 #pragma unroll
-    for (int j = 0; j < kBoxDims; ++j) {
-        t.lim[j] = 1;
-        if (j < p.nslots) {
-            const Slot& sl = p.slot[j];
-            const int64_t origin = (int64_t)fdigit(tile, sl.tile_below, sl.tile_cnt) * sl.tile;
-            const int64_t left = sl.size - origin;
-            t.lim[j] = (int32_t)(left < (int64_t)sl.tile ? left : (int64_t)sl.tile);
-            t.whole = t.whole && (t.lim[j] == sl.tile);
-        }
+    for (int j = 0; j < kBoxDims; ++j) {            // unused slots: extent 1, size 1, one tile
+        const Slot& sl = p.slot[j];
+        const int64_t origin = (int64_t)fdigit(tile, sl.tile_below, sl.tile_cnt) * sl.tile;
+        const int64_t left = sl.size - origin;
+        t.lim[j] = (int32_t)(left < (int64_t)sl.tile ? left : (int64_t)sl.tile);
+        t.whole = t.whole && (t.lim[j] == sl.tile);
     }
     return t;
 }
@@ -136,16 +136,13 @@ TTC_HD LaneState lane_setup(const Side& s, uint32_t lane, const Scales& scale)
     L.active = lane < (uint32_t)s.lanes;
     uint32_t cs[kBoxDims];
 #pragma unroll
-    for (int j = 0; j < kBoxDims; ++j) {
-        cs[j] = 0;
-        if (s.d[j].lane > 1) {
-            const Digit& d = s.d[j];
-            const int32_t c = (int32_t)fdigit(lane, d.lane_below, d.lane_cnt) * d.lane_mul;
-            cs[j] = (uint32_t)c;
-            L.g += (int64_t)c * d.gstride;
-            if (DIRECT) L.g2 += (int64_t)c * d.g2stride;
-            else L.l += c * d.lstride;
-        }
+    for (int j = 0; j < kBoxDims; ++j) {            // empty digits: one lane step, stride 0
+        const Digit& d = s.d[j];
+        const int32_t c = (int32_t)fdigit(lane, d.lane_below, d.lane_cnt) * d.lane_mul;
+        cs[j] = (uint32_t)c;
+        L.g += (int64_t)c * d.gstride;
+        if (DIRECT) L.g2 += (int64_t)c * d.g2stride;
+        else L.l += c * d.lstride;
     }
     L.g *= scale.g; L.g2 *= scale.g2; L.l *= scale.l;
     L.c01 = cs[0] | (cs[1] << 16);
@@ -168,15 +165,12 @@ TTC_HD void make_position(const Side& s, uint32_t it, const Scales& scale, PosEn
     int64_t g = 0, x = 0;
     uint32_t pc[kBoxDims];
 #pragma unroll
-    for (int i = 0; i < kBoxDims; ++i) {
-        pc[i] = 0;
-        if (s.d[i].iters > 1) {
-            const Digit& d = s.d[i];
-            const uint32_t q = fdigit(it, d.iter_below, d.iter_cnt) * (uint32_t)d.lane;
-            pc[i] = q;
-            g += (int64_t)q * d.gstride;
-            x += (int64_t)q * (DIRECT ? d.g2stride : (int64_t)d.lstride);
-        }
+    for (int i = 0; i < kBoxDims; ++i) {            // digits with one position contribute 0
+        const Digit& d = s.d[i];
+        const uint32_t q = fdigit(it, d.iter_below, d.iter_cnt) * (uint32_t)d.lane;
+        pc[i] = q;
+        g += (int64_t)q * d.gstride;
+        x += (int64_t)q * (DIRECT ? d.g2stride : (int64_t)d.lstride);
     }
     e->g = g * scale.g;
     e->l_or_g2 = x * (DIRECT ? scale.g2 : scale.l);
@@ -261,18 +255,56 @@ TTC_HD void walk_group(const LaneLim& x, int vec_slot, const PosEntry* e_ptr, co
 // overhang the tile need the test at every position (dynamic, wave-uniform).
 struct WalkMask { bool lane_ok; bool dynamic; };
 
-TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
+// bit j: digit j has a single sub-box position (the same for every tile)
+TTC_HD uint32_t single_digits(const Side& s)
 {
-    WalkMask m;
-    m.lane_ok = L.active;
-    m.dynamic = (s.partial != 0);
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < kBoxDims; ++j) m |= (s.d[j].iters == 1 ? 1u : 0u) << j;
+    return m;
+}
+
+// the wave-uniform half: does the walk have to test its positions in this tile?
+TTC_HD bool walk_dynamic(const Side& s, const SideLim& lim)
+{
+    bool dynamic = (s.partial != 0);
 #pragma unroll
     for (int j = 0; j < kBoxDims; ++j) {
         const Digit& d = s.d[j];
-        const int32_t c = (int32_t)(((j & 2) ? L.c23 : L.c01) >> ((j & 1) ? 16 : 0)) & 0xffff;
-        if (d.iters == 1) m.lane_ok = m.lane_ok & (c < lim.lim[j]);
-        else m.dynamic = m.dynamic | (lim.lim[j] != d.tile) | (d.ragged != 0);
+        if (d.iters != 1) dynamic = dynamic | (lim.lim[j] != d.tile) | (d.ragged != 0);
     }
+    return dynamic;
+}
+
+// the per-lane half: is the lane inside the tile along the digits that do not step?
+TTC_HD bool lane_inside(uint32_t single, const LaneState& L, const SideLim& lim)
+{
+    bool ok = L.active;
+#pragma unroll
+    for (int j = 0; j < kBoxDims; ++j) {
+        const int32_t c = (int32_t)(((j & 2) ? L.c23 : L.c01) >> ((j & 1) ? 16 : 0)) & 0xffff;
+        if ((single >> j) & 1u) ok = ok & (c < lim.lim[j]);
+    }
+    return ok;
+}
+
+// one walk's part of the shared tile record
+TTC_HD SideShare make_side_share(const Side& s, const TileLim& tl)
+{
+    const SideLim sl = side_lim(s, tl);
+    SideShare v;
+    v.lim[0] = sl.lim[0]; v.lim[1] = sl.lim[1]; v.lim[2] = sl.lim[2]; v.lim[3] = sl.lim[3];
+    v.t01 = sl.t01; v.t23 = sl.t23;
+    v.dynamic = walk_dynamic(s, sl) ? 1u : 0u;
+    v.pad = 0;
+    return v;
+}
+
+TTC_HD WalkMask walk_mask(const Side& s, const LaneState& L, const SideLim& lim)
+{
+    WalkMask m;
+    m.lane_ok = lane_inside(single_digits(s), L, lim);
+    m.dynamic = walk_dynamic(s, lim);
     return m;
 }
 
