@@ -68,8 +68,10 @@ TTC_HD TileBase tile_base(const KernelParams& p, uint32_t tile)
 {
     TileBase t;
     t.a = 0; t.b = 0;
-    for (int k = 0; k < p.n; ++k) {
-        if (p.tile_cnt[k].div == 1) continue;
+    // straight-line over all kMaxDim entries: unused ones hold neutral values (one tile, stride 0), and code
+    // without branches lets the compiler fetch every parameter in one batch instead of index by index
+#pragma unroll
+    for (int k = 0; k < kMaxDim; ++k) {
         const int64_t origin = (int64_t)fdigit(tile, p.tile_below[k], p.tile_cnt[k]) * p.tile[k];
         t.a += origin * p.stride_a[k];
         t.b += origin * p.stride_b[k];
