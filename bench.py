@@ -102,8 +102,8 @@ def measured_traffic(case_name: str):
 def main() -> int:
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); "
-              "multi-GPU sharding is described in DESIGN.md, not built", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1); sharding over several GPUs is not built",
+              file=sys.stderr)
         return 2
     import numpy as np
     import torch

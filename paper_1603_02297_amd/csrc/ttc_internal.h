@@ -105,7 +105,7 @@ struct Candidate {
     int      kernel_class;           // TTC_KERNEL_*
     int      threads;
     int      wg_per_cu;              // workgroups launched per compute unit (each walks several tiles)
-    int      lds_bytes;              // dynamic LDS per workgroup: position tables + two tile buffers
+    int      lds_bytes;              // dynamic LDS per workgroup: shared tile records, spare slots, position tables, one or two tile buffers
     int      tile_order[kMaxDim];
     int      tile[kMaxDim], lds_stride[kMaxDim];   // by fused index of A
     int      digits_a, digits_b;                   // digits of each walk, in the walk's own order:
