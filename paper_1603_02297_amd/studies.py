@@ -23,6 +23,7 @@ from __future__ import annotations
 
 import argparse
 import itertools
+import json
 import statistics
 import sys
 import time
@@ -135,7 +136,6 @@ def d2d_copy_gbps(nbytes, a_ptrs, b_ptrs, stream):
 # ---- study 1: reduction of the search space -------------------------------------------------------
 def study_search(out, dump=None):
     import torch
-    import json
     stream = torch.cuda.current_stream().cuda_stream
     bufs = Buffers()
     caps = (1, 10, 100, 200)
@@ -192,7 +192,7 @@ def ablations(rows):
     }
 
 
-def study_sweep(out, limit=None):
+def study_sweep(out, limit=None, dump=None):
     import torch
     stream = torch.cuda.current_stream().cuda_stream
     bufs = Buffers()
@@ -213,6 +213,9 @@ def study_sweep(out, limit=None):
         ms = np.array([r[1] for r in rows])
         k = int(ms.argmin())
         nbytes = rows[0][0]["bytes_moved"]
+        if dump is not None:
+            name = f"sweep-{len(perm)}d-{cls}-cfg{cfg}-p{''.join(map(str, perm))}"
+            dump.write(json.dumps({"problem": name, "rows": [dict(r[0], ms=r[1]) for r in rows]}) + "\n")
         res = {"perm": perm, "class": cls, "cfg": cfg, "sizes": sizes, "copy": copy,
                "best": nbytes / ms[k] / 1e6, "heur": nbytes / heur_ms / 1e6, "info": rows[k][0],
                "abl": ablations(rows), "cands": len(rows)}
@@ -253,7 +256,7 @@ def main(argv=None):
     ap.add_argument("study", choices=("search", "sweep"))
     ap.add_argument("--out", default="", help="write the table to this file (default: stdout)")
     ap.add_argument("--limit", type=int, default=0, help="sweep: only the first LIMIT cases")
-    ap.add_argument("--dump", default="", help="search: also write every candidate's configuration and time (JSON lines)")
+    ap.add_argument("--dump", default="", help="also write every candidate's configuration and time (JSON lines; .gz compresses)")
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
@@ -263,16 +266,16 @@ def main(argv=None):
     out = open(args.out, "w") if args.out else sys.stdout
     t0 = time.time()
     print(f"# python -m paper_1603_02297_amd.studies {args.study}" + (f" --limit {args.limit}" if args.limit else ""), file=out)
+    dump = None
+    if args.dump:
+        import gzip
+        dump = gzip.open(args.dump, "wt") if args.dump.endswith(".gz") else open(args.dump, "w")
     if args.study == "search":
-        dump = None
-        if args.dump:
-            import gzip
-            dump = gzip.open(args.dump, "wt") if args.dump.endswith(".gz") else open(args.dump, "w")
         study_search(out, dump)
-        if dump:
-            dump.close()
     else:
-        study_sweep(out, args.limit or None)
+        study_sweep(out, args.limit or None, dump)
+    if dump:
+        dump.close()
     print(f"# {time.time() - t0:.0f} s", file=out)
     if args.out:
         out.close()
