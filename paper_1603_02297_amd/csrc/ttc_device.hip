@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -170,11 +171,18 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         *ms_out = ms / reps;
         return TTC_OK;
     };
-    // pass 1: every candidate briefly; pass 2: the fastest few again, longer, to beat the noise
+    // pass 1: every candidate briefly; pass 2: the fastest few again, longer, to beat the noise.  Launches of a
+    // few microseconds are repeated more often: both passes time at least 0.2 ms and 1 ms of work.
+    float first_ms = 0.f;
+    const int st0 = time_one(plan->cands[0], 2, 3, &first_ms);
+    if (st0 != TTC_OK) return st0;
+    const float unit = first_ms > 1e-4f ? first_ms : 1e-4f;
+    const int reps1 = std::min(40, std::max(3, (int)std::ceil(0.2f / unit)));
+    const int reps2 = std::min(200, std::max(12, (int)std::ceil(1.0f / unit)));
     std::vector<std::pair<float, int>> timed;
     for (int i = 0; i < cap; ++i) {
         float ms = 0.f;
-        const int st1 = time_one(plan->cands[i], 1, 3, &ms);
+        const int st1 = time_one(plan->cands[i], 1, reps1, &ms);
         if (st1 != TTC_OK) return st1;
         plan->cands[i].tuned_ms = ms;
         timed.emplace_back(ms, i);
@@ -196,7 +204,7 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
             c.kp.nt_a = variants[v][0];
             c.kp.nt_b = variants[v][1];
             float ms = 0.f;
-            const int st2 = time_one(c, 2, 12, &ms);
+            const int st2 = time_one(c, 2, reps2, &ms);
             if (st2 != TTC_OK) { c.kp.nt_a = rule_a; c.kp.nt_b = rule_b; return st2; }
             if (v == 0 || ms < cand_ms) { cand_ms = ms; keep_a = variants[v][0]; keep_b = variants[v][1]; }
         }

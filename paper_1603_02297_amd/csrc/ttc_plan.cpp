@@ -797,7 +797,7 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
     if (kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - kp.num_tiles) / 2048.0;
     // small problems (outside the fitted range): a tile per compute unit comes before large tiles
     const double cus_wanted = std::min(256.0, std::max(1.0, (double)P.elements * eb_a / 4096.0));
-    if (kp.num_tiles < cus_wanted) e += 0.5 * (cus_wanted - kp.num_tiles) / 256.0;
+    if (kp.num_tiles < cus_wanted) e += 1.5 * (cus_wanted - kp.num_tiles) / 256.0;
     return std::exp(e);
 }
 

@@ -411,3 +411,12 @@ def test_streaming_rule_and_override():
     i = ttc.ttc_plan_get_info(p)
     assert i["nt_a"] == 1 and i["nt_b"] == 1
     ttc.ttc_plan_destroy(p)
+
+
+@pytest.mark.parametrize("sizes,perm", [((256, 256), (1, 0)), ((512, 512), (1, 0)), ((1024, 1024), (1, 0)), ((384, 24, 24), (0, 2, 1)),
+                                        ((64, 64, 64), (2, 1, 0)), ((24, 24, 24, 24), (3, 2, 1, 0)), ((17, 19, 23, 29), (2, 0, 3, 1))])
+def test_first_candidate_of_a_small_problem_spreads_over_the_chip(sizes, perm):
+    # outside the range the cost model was fitted on, guard rails keep the first candidate from a few giant tiles
+    i = info_of(ttc.TTC_F32, sizes, perm)
+    nbytes = 4 * int(np.prod(sizes))
+    assert i["num_tiles"] >= min(128, nbytes // 8192), i
