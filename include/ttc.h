@@ -80,7 +80,7 @@ typedef struct {
                                               back to end with the run and overlaps its neighbour */
     int     threads;                       /* workgroup size */
     int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles */
-    int     xcd_remap;                     /* 1: each XCD walks a contiguous range of tiles */
+    int     xcd_remap;                     /* tiles -> XCDs: 0 round robin, 1 a contiguous range each, k >= 2: chunks of 2^k tiles in turn */
     int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + tile buffer(s) */
     int     lds_buffers;                   /* 2: tile buffers alternate (one barrier per tile), 1: one buffer (two barriers) */
     int     nt_a, nt_b;                    /* 1: loads of A / stores to B (and loads of B if beta != 0) carry the
@@ -166,6 +166,15 @@ int ttc_plan_select_candidate(ttc_plan_t plan, int index);
  * lines).  The direct kernel streams both sides or neither.  Host only.
  */
 int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b);
+
+/*
+ * How the selected candidate deals its tiles to the 8 XCDs (each has its own L2): the MI355X form of the
+ * paper's loop-order question (Section 3.3) one level up.  mode 0: tile ids round robin over all workgroups;
+ * 1: one contiguous range of tile ids per XCD; 2..10: chunks of 2^mode consecutive tile ids dealt to the
+ * XCDs in turn; -1: the default (chunks of 32).  Reported as xcd_remap by ttc_plan_get_info.  The search
+ * times its finalists with modes 1 and 3 as well.  Host only.
+ */
+int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode);
 
 /*
  * Search (paper Section 3: candidates are timed and the fastest becomes the solution;

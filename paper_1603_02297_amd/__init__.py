@@ -7,4 +7,5 @@ from .binding import *  # noqa: F401,F403
 from .binding import (TtcError, lib, ttc_execute, ttc_last_status, ttc_plan_candidate_count, ttc_plan_create, ttc_plan_create_ex,
                       ttc_plan_destroy, ttc_plan_get_info, ttc_plan_select_candidate, ttc_plan_tune, ttc_plan_tune_pairs,
                       ttc_status_string, ttc_time_ceiling, ttc_time_execute, ttc_debug_emulate_map,
-                      ttc_plan_cache_store, ttc_plan_cache_lookup, ttc_plan_set_streaming)
+                      ttc_plan_cache_store, ttc_plan_cache_lookup, ttc_plan_set_streaming,
+                      ttc_plan_set_tile_mapping)

@@ -24,7 +24,7 @@ EXPORTS = (
     "ttc_plan_create", "ttc_plan_create_ex", "ttc_execute", "ttc_plan_destroy", "ttc_last_status", "ttc_status_string",
     "ttc_plan_get_info", "ttc_plan_candidate_count", "ttc_plan_select_candidate", "ttc_plan_tune",
     "ttc_plan_tune_pairs", "ttc_time_execute", "ttc_time_ceiling", "ttc_debug_emulate_map",
-    "ttc_plan_cache_store", "ttc_plan_cache_lookup", "ttc_plan_set_streaming",
+    "ttc_plan_cache_store", "ttc_plan_cache_lookup", "ttc_plan_set_streaming", "ttc_plan_set_tile_mapping",
 )
 
 
@@ -109,6 +109,8 @@ def lib() -> ctypes.CDLL:
         L.ttc_time_ceiling.argtypes = [i, ctypes.c_int64, i, pvp, pvp, vp, i, i, ctypes.POINTER(ctypes.c_float)]
         L.ttc_plan_set_streaming.restype = i
         L.ttc_plan_set_streaming.argtypes = [vp, i, i]
+        L.ttc_plan_set_tile_mapping.restype = i
+        L.ttc_plan_set_tile_mapping.argtypes = [vp, i]
         L.ttc_plan_cache_store.restype = i
         L.ttc_plan_cache_store.argtypes = [vp, ctypes.c_char_p]
         L.ttc_plan_cache_lookup.restype = i
@@ -241,6 +243,13 @@ def ttc_time_ceiling(kind: int, nbytes: int, src_list: Sequence[int], dst_list: 
     if st != TTC_OK:
         raise TtcError(st, "ttc_time_ceiling")
     return ms.value
+
+
+def ttc_plan_set_tile_mapping(plan: int, mode: int = -1) -> None:
+    """How the selected candidate deals its tiles to the XCDs: 0 round robin, 1 one range each, 2..10 chunks of 2**mode, -1 default."""
+    st = lib().ttc_plan_set_tile_mapping(plan, int(mode))
+    if st != TTC_OK:
+        raise TtcError(st, "ttc_plan_set_tile_mapping")
 
 
 def ttc_plan_set_streaming(plan: int, stream_a: int = -1, stream_b: int = -1) -> None:

@@ -4,9 +4,9 @@
 // text per problem in a file the caller names.
 //
 // Line format (all integers, blank separated):
-//   ttc2 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
+//   ttc3 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
 //   <kernel_class> <threads> <wg_per_cu> <lds_buffers> <vec_a> <vec_b> <tile x6> <tile_order x6>
-//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> | <nt_a> <nt_b> <microseconds>
+//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> | <nt_a> <nt_b> <tile mapping> <microseconds>
 // The left part is the key: the fused problem as the planner sees it.  The middle part names a
 // candidate by its configuration, not by its rank, so an entry survives changes of the ranking;
 // if no candidate of the current library matches, the entry is ignored.  Later lines win.
@@ -20,7 +20,7 @@
 
 namespace ttc {
 
-static const char* kMagic = "ttc2";
+static const char* kMagic = "ttc3";
 static const char* kArch = "gfx950";
 
 static std::string problem_key(const Problem& P)
@@ -56,7 +56,7 @@ int cache_store(const ttc_plan_s* plan, const char* path)
     std::ostringstream o;
     o << problem_key(plan->prob) << " |";
     for (long long x : config_signature(c)) o << ' ' << x;
-    o << " | " << c.kp.nt_a << ' ' << c.kp.nt_b << ' ' << (long long)(c.tuned_ms * 1000.0f + 0.5f) << '\n';
+    o << " | " << c.kp.nt_a << ' ' << c.kp.nt_b << ' ' << c.kp.xcd_remap << ' ' << (long long)(c.tuned_ms * 1000.0f + 0.5f) << '\n';
     const std::string line = o.str();
     std::FILE* f = std::fopen(path, "a");
     if (!f) return TTC_ERR_IO;
@@ -77,7 +77,7 @@ int cache_lookup(ttc_plan_s* plan, const char* path)
     }
     std::fclose(f);
     if (hit.empty()) return TTC_ERR_NOT_FOUND;
-    // "<signature> | <nt_a> <nt_b> <microseconds>"
+    // "<signature> | <nt_a> <nt_b> <tile mapping> <microseconds>"
     std::vector<long long> sig, tailv;
     long long us = 0;
     {
@@ -92,13 +92,14 @@ int cache_lookup(ttc_plan_s* plan, const char* path)
             if (tail) tailv.push_back(v); else sig.push_back(v);
         }
     }
-    if (tailv.size() != 3 || (tailv[0] | 1) != 1 || (tailv[1] | 1) != 1) return TTC_ERR_NOT_FOUND;
-    us = tailv[2];
+    if (tailv.size() != 4 || (tailv[0] | 1) != 1 || (tailv[1] | 1) != 1 || tailv[2] < 0 || tailv[2] > 10) return TTC_ERR_NOT_FOUND;
+    us = tailv[3];
     for (size_t i = 0; i < plan->cands.size(); ++i) {
         if (config_signature(plan->cands[i]) == sig) {
             plan->selected = (int)i;
             plan->cands[i].kp.nt_a = (int)tailv[0];
             plan->cands[i].kp.nt_b = (int)tailv[1];
+            if (!set_tile_mapping(&plan->cands[i].kp, (int)tailv[2])) return TTC_ERR_NOT_FOUND;
             plan->cands[i].tuned_ms = (float)us / 1000.0f;
             return TTC_OK;
         }

@@ -233,6 +233,17 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         }
         c.kp.nt_a = keep_a;
         c.kp.nt_b = keep_b;
+        // the same for the mapping of tiles to XCDs: chunks of 32 (the default), one range per XCD, chunks of 8
+        const int mapping0 = c.kp.xcd_remap;
+        int keep_map = mapping0;
+        for (int mode : {1, 3}) {
+            if (mode == mapping0 || !ttc::set_tile_mapping(&c.kp, mode)) continue;
+            float ms = 0.f;
+            const int st3 = time_one(c, 2, reps2, &ms);
+            if (st3 != TTC_OK) { (void)ttc::set_tile_mapping(&c.kp, mapping0); return st3; }
+            if (ms < cand_ms) { cand_ms = ms; keep_map = mode; }
+        }
+        (void)ttc::set_tile_mapping(&c.kp, keep_map);
         c.tuned_ms = cand_ms;
         if (best < 0 || cand_ms < best_ms) { best = i; best_ms = cand_ms; }
     }

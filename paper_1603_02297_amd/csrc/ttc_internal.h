@@ -75,13 +75,15 @@ struct Slot {
 // Everything a kernel launch needs; passed by value as the kernel argument.
 struct KernelParams {
     int32_t  n;                      // fused number of indices
-    int32_t  xcd_remap;
+    int32_t  xcd_remap;              // how tile ids map to the 8 XCDs: 0 round robin, 1 one contiguous range each,
+                                     // k >= 2: chunks of 2^k consecutive tiles dealt round robin
     uint32_t num_tiles;
     uint32_t tiles_per_xcd;          // num_tiles / 8
     uint32_t tiles_rem_xcd;          // num_tiles % 8
     uint32_t grid;                   // workgroups launched (filled at launch; <= num_tiles)
     uint32_t grid_per_xcd;           // grid / 8
     uint32_t grid_rem_xcd;           // grid % 8
+    uint32_t xcd_tiles[8];           // chunked mapping: tiles of each XCD
     int32_t  lds_data_off;           // byte offset of the first data buffer in dynamic LDS
     int32_t  lds_tile_elems;         // elements per LDS data buffer (padded tile)
     int32_t  lds_buffers;            // 2: tile buffers alternate, one barrier per tile; 1: one buffer, two barriers
@@ -156,6 +158,9 @@ int cache_lookup(ttc_plan_s* plan, const char* path);
 // Workgroups to launch for a candidate on a device with `cus` compute units.
 uint32_t launch_grid(const Candidate& c, int cus);
 void set_grid(KernelParams* kp, uint32_t grid);
+// tile ids -> XCDs: 0 round robin, 1 one contiguous range per XCD, 2..10: chunks of 2^mode tiles dealt in turn
+constexpr int kDefaultTileMapping = 5;
+bool set_tile_mapping(KernelParams* kp, int mode);
 void default_streaming(const Problem& P, Candidate* c);
 
 }  // namespace ttc

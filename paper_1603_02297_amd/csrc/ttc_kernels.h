@@ -227,11 +227,12 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
         share[slot] = v;
     };
     const uint32_t single_a = single_digits(p.a), single_b = DIRECT ? 0u : single_digits(p.b);
-    if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(seq.first, 0);
+    if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(tile_of(seq, seq.first), 0);
     __syncthreads();
 
     uint32_t parity = 0;
-    for (uint32_t tile = seq.first; tile < seq.end; tile += seq.step) {
+    for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
+        const uint32_t tile = tile_of(seq, q);
         TileBase tb;
         SideLim sla, slb;
         WalkMask wma, wmb;
@@ -299,7 +300,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
             };
             if (nt_a) run(std::true_type()); else run(std::false_type());
         }
-        if (wave == nwave - 1 && tile + seq.step < seq.end) publish(tile + seq.step, parity);   // parity already flipped
+        if (wave == nwave - 1 && q + seq.step < seq.end) publish(tile_of(seq, q + seq.step), parity);   // parity already flipped
         __syncthreads();
         // ---- walk 2: B order, LDS -> epilogue -> global
         {

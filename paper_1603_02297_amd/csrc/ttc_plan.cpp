@@ -482,7 +482,6 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
 
     KernelParams& kp = C.kp;
     kp.n = P.ndim;
-    kp.xcd_remap = xcd_remap;
     int64_t ntiles = 1;
     for (int k = 0; k < kMaxDim; ++k) {
         kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
@@ -504,6 +503,7 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     kp.num_tiles = (uint32_t)ntiles;
     kp.tiles_per_xcd = kp.num_tiles / 8;
     kp.tiles_rem_xcd = kp.num_tiles % 8;
+    if (!set_tile_mapping(&kp, xcd_remap)) return false;
     kp.alpha[0] = P.alpha[0]; kp.alpha[1] = P.alpha[1];
     kp.beta[0] = P.beta[0];   kp.beta[1] = P.beta[1];
 
@@ -643,6 +643,23 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     set_grid(&kp, launch_grid(C, 256));
     C.tuned_ms = 0.f;
     *out = C;
+    return true;
+}
+
+bool set_tile_mapping(KernelParams* kp, int mode)
+{
+    if (mode < 0 || mode > 10) return false;
+    kp->xcd_remap = mode;
+    for (int x = 0; x < 8; ++x) kp->xcd_tiles[x] = 0;
+    if (mode >= 2) {
+        const uint32_t C = 1u << mode;
+        const uint32_t chunks = (kp->num_tiles + C - 1) / C;             // the last one may be partial
+        for (uint32_t x = 0; x < 8; ++x) {
+            const uint32_t mine = chunks > x ? (chunks - x + 7) / 8 : 0;
+            kp->xcd_tiles[x] = mine * C;
+            if (mine > 0 && (chunks - 1) % 8 == x) kp->xcd_tiles[x] -= chunks * C - kp->num_tiles;
+        }
+    }
     return true;
 }
 
@@ -894,7 +911,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                     for (int o = 0; o < norders; ++o)
                         for (const LaunchShape& ls : kLaunchShapes) {
                             Candidate c;
-                            if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], 1, &c))
+                            if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], kDefaultTileMapping, &c))
                                 add_candidate(P, out, c);
                         }
                 }
@@ -934,7 +951,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                                 for (int o = 0; o < norders; ++o)
                                     for (const LaunchShape& ls : kLaunchShapes) {
                                         Candidate c;
-                                        if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], 1,
+                                        if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], kDefaultTileMapping,
                                                            &c, (mg & 1) == 0, (mg & 2) == 0, &cache, nbuf))
                                             add_candidate(P, out, c);
                                     }
@@ -948,7 +965,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
         int t[kMaxDim];
         build_group(P, order_a, P.eb_a, 16384 / eb, 1, kBoxDims, t);
         Candidate c;
-        if (make_candidate(P, t, 1, true, 256, 8, order_a, 1, &c)) add_candidate(P, out, c);
+        if (make_candidate(P, t, 1, true, 256, 8, order_a, kDefaultTileMapping, &c)) add_candidate(P, out, c);
     }
 }
 
@@ -971,7 +988,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
         // every candidate is vectorised: add the scalar variant of the best one
         const Candidate& b = plan->cands[0];
         Candidate c;
-        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, 1, &c,
+        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, kDefaultTileMapping, &c,
                             true, true, nullptr, b.kp.lds_buffers))
             return TTC_ERR_OVERFLOW;
         default_streaming(P, &c);
@@ -1122,6 +1139,14 @@ int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b)
     return TTC_OK;
 }
 
+int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode)
+{
+    if (!plan) return TTC_ERR_NULL_POINTER;
+    if (mode < -1 || mode > 10) return TTC_ERR_INVALID_VALUE;
+    ttc::Candidate& C = plan->cands[plan->selected];
+    return ttc::set_tile_mapping(&C.kp, mode < 0 ? ttc::kDefaultTileMapping : mode) ? TTC_OK : TTC_ERR_INVALID_VALUE;
+}
+
 int ttc_plan_candidate_count(ttc_plan_t plan)
 {
     if (!plan) return -TTC_ERR_NULL_POINTER;
@@ -1200,7 +1225,8 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     int64_t written = 0;
     for (uint32_t wg = 0; wg < p.grid && !bad; ++wg) {
         const TileSeq seq = tile_sequence(p, wg);
-        for (uint32_t tile = seq.first; tile < seq.end && !bad; tile += seq.step) {
+        for (uint32_t q = seq.first; q < seq.end && !bad; q += seq.step) {
+            const uint32_t tile = tile_of(seq, q);
             if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
             seen[tile] = 1;
             const TileBase tb = tile_base(p, tile);

@@ -35,21 +35,39 @@ TTC_HD uint32_t fdigit(uint32_t x, const FastDiv& below, const FastDiv& cnt)
 // Consecutive workgroup ids land on consecutive XCDs (8 of them, each with its own L2).  Every
 // XCD owns one contiguous range of tile ids; its workgroups take the tiles of that range round
 // robin, so tiles that are neighbours in memory are in flight on the same XCD at the same time.
-struct TileSeq { uint32_t first, end, step; };
+// A workgroup walks positions first, first + step, ... < end of its XCD's sequence of tiles; tile_of() turns a
+// position into a tile id.  Three mappings: plain round robin over all workgroups (one window that advances
+// through the tensor: the lowest memory latency when tiles share no cache lines); one contiguous range of
+// tile ids per XCD (neighbouring tiles always meet in one L2); and chunks of 2^k consecutive tiles dealt to the
+// XCDs in turn (neighbours inside a chunk share an L2 and the window still advances as one).
+struct TileSeq { uint32_t first, end, step, base, xcd, chunk_log; };
 
 TTC_HD TileSeq tile_sequence(const KernelParams& p, uint32_t wg)
 {
     TileSeq s;
+    s.base = 0; s.xcd = 0; s.chunk_log = 0;
     if (!p.xcd_remap || p.grid < 8u) {
         s.first = wg; s.end = p.num_tiles; s.step = p.grid;
         return s;
     }
     const uint32_t x = wg & 7u, slot = wg >> 3;
-    const uint32_t lo = x * p.tiles_per_xcd + (x < p.tiles_rem_xcd ? x : p.tiles_rem_xcd);
-    s.first = lo + slot;
-    s.end = lo + p.tiles_per_xcd + (x < p.tiles_rem_xcd ? 1u : 0u);
+    s.first = slot;
     s.step = p.grid_per_xcd + (x < p.grid_rem_xcd ? 1u : 0u);
+    if (p.xcd_remap == 1) {
+        s.base = x * p.tiles_per_xcd + (x < p.tiles_rem_xcd ? x : p.tiles_rem_xcd);
+        s.end = p.tiles_per_xcd + (x < p.tiles_rem_xcd ? 1u : 0u);
+    } else {
+        s.xcd = x;
+        s.chunk_log = (uint32_t)p.xcd_remap;
+        s.end = p.xcd_tiles[x];
+    }
     return s;
+}
+
+TTC_HD uint32_t tile_of(const TileSeq& s, uint32_t q)
+{
+    if (s.chunk_log == 0) return s.base + q;
+    return ((s.xcd + 8u * (q >> s.chunk_log)) << s.chunk_log) + (q & ((1u << s.chunk_log) - 1u));
 }
 
 // tile id -> element offsets of the box origin in A and in B

@@ -322,3 +322,29 @@ def test_streaming_accesses_change_nothing_in_the_result(dtype, sizes, perm, alp
         torch.cuda.synchronize()
         assert ulp_distance(dB.cpu().numpy(), want) <= 1, (sa, sb, ttc.ttc_plan_get_info(plan))
     ttc.ttc_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("dtype,sizes,perm,alpha,beta", [
+    (wl.F32, (85, 33, 47), (2, 1, 0), 1.0, 0.0), (wl.F32, (200, 150, 9), (1, 0, 2), 1.5, 0.0),
+    (wl.F64, (64, 20, 48), (0, 2, 1), 0.75, 1.25), (wl.C64, (8, 33, 12, 30), (3, 1, 0, 2), 0.5 + 0.5j, 1.0),
+], ids=["f32-odd", "f32-ragged", "f64-direct", "c64"])
+def test_tile_mappings_change_nothing_in_the_result(dtype, sizes, perm, alpha, beta):
+    n = prod(sizes)
+    A = wl.uniform_tensor(dtype, n, 31, "a")
+    B0 = wl.uniform_tensor(dtype, n, 32, "b")
+    want = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy(), 4)
+    dev = torch.device("cuda:0")
+    dA = torch.from_numpy(A).to(dev)
+    s = torch.cuda.current_stream().cuda_stream
+    plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+    count = ttc.ttc_plan_candidate_count(plan)
+    for k in sorted({0, count // 5, count // 2, count - 1}):
+        ttc.ttc_plan_select_candidate(plan, k)
+        for mode in (0, 1, 2, 3, 5, 9, -1):
+            ttc.ttc_plan_set_tile_mapping(plan, mode)
+            dB = torch.from_numpy(B0).to(dev)
+            ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), s)
+            torch.cuda.synchronize()
+            exact = (complex(alpha) == 1 and complex(beta) == 0)
+            assert ulp_distance(dB.cpu().numpy(), want) <= (0 if exact else 1), (k, mode, ttc.ttc_plan_get_info(plan))
+    ttc.ttc_plan_destroy(plan)

@@ -282,6 +282,7 @@ def test_plan_store_round_trip(tmp_path):
     assert ttc.ttc_plan_cache_lookup(p, path) is False                 # no file yet
     n = ttc.ttc_plan_candidate_count(p)
     ttc.ttc_plan_select_candidate(p, n // 3)
+    ttc.ttc_plan_set_tile_mapping(p, 3)                                # the stored solution carries its tile mapping
     chosen = config_of(p)
     ttc.ttc_plan_cache_store(p, path)
     ttc.ttc_plan_destroy(p)
@@ -290,6 +291,7 @@ def test_plan_store_round_trip(tmp_path):
     assert ttc.ttc_plan_get_info(q)["candidate_index"] == 0
     assert ttc.ttc_plan_cache_lookup(q, path) is True
     assert config_of(q) == chosen and ttc.ttc_plan_get_info(q)["candidate_index"] == n // 3
+    assert ttc.ttc_plan_get_info(q)["xcd_remap"] == 3
     ttc.ttc_plan_destroy(q)
 
     # alpha does not enter the key, beta == 0 does; neither do unrelated problems match
@@ -420,3 +422,27 @@ def test_first_candidate_of_a_small_problem_spreads_over_the_chip(sizes, perm):
     i = info_of(ttc.TTC_F32, sizes, perm)
     nbytes = 4 * int(np.prod(sizes))
     assert i["num_tiles"] >= min(128, nbytes // 8192), i
+
+
+@pytest.mark.parametrize("sizes,perm", [((70, 33, 45), (2, 0, 1)), ((19, 7, 23, 5), (3, 1, 0, 2)), ((300, 11), (1, 0)),
+                                        ((96, 20, 31), (0, 2, 1)), ((5, 4, 3, 6, 2, 7), (5, 3, 1, 0, 4, 2))])
+def test_every_tile_mapping_covers_the_tensor(sizes, perm):
+    """How tiles are dealt to the XCDs (round robin, one range each, chunks of 2**k in turn) changes which
+    workgroup takes which tile, never what is computed: the replay of every workgroup's walk still writes
+    every element of B once, from the element of A the oracle names."""
+    want = [-1] * int(np.prod(sizes))
+    for off_a, off_b in oracle.element_pairs(sizes, perm, None, None):
+        want[off_b] = off_a
+    p = plan(ttc.TTC_F32, sizes, perm)
+    assert ttc.ttc_plan_get_info(p)["xcd_remap"] == 5                  # the default: chunks of 32
+    n = ttc.ttc_plan_candidate_count(p)
+    for k in sorted({0, n // 7, n // 2, n - 1}):
+        ttc.ttc_plan_select_candidate(p, k)
+        for mode in (0, 1, 2, 3, 5, 8, 10, -1):
+            ttc.ttc_plan_set_tile_mapping(p, mode)
+            assert ttc.ttc_plan_get_info(p)["xcd_remap"] == (5 if mode < 0 else mode)
+            assert list(ttc.ttc_debug_emulate_map(p)) == want, (k, mode)
+    for bad in (-2, 11):
+        with pytest.raises(ttc.TtcError):
+            ttc.ttc_plan_set_tile_mapping(p, bad)
+    ttc.ttc_plan_destroy(p)
