@@ -108,8 +108,8 @@ def time_candidates(plan, a_ptrs, b_ptrs, stream, warm=1, reps=4):
 
 
 def retime_best(plan, rows, a_ptrs, b_ptrs, stream, keep=8):
-    """Time the fastest few again, longer, with the streaming hints by rule, off and on (as the library's
-    own search does), and return rows with those entries replaced by their best."""
+    """Time the fastest few again, longer, with the streaming hints by rule, off and on, then with the other
+    tile mappings (as the library's own search does), and return rows with those entries replaced by their best."""
     order = sorted(range(len(rows)), key=lambda i: rows[i][1])[:keep]
     rows = list(rows)
     for i in order:
@@ -120,6 +120,14 @@ def retime_best(plan, rows, a_ptrs, b_ptrs, stream, keep=8):
             ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
             if best is None or ms < best[1]:
                 best = (ttc.ttc_plan_get_info(plan), ms)
+        info = best[0]
+        ttc.ttc_plan_set_streaming(plan, info["nt_a"], info["nt_b"])
+        for mode in (1, 3):                      # tiles dealt to the XCDs: one range each, chunks of 8 (default: chunks of 32)
+            ttc.ttc_plan_set_tile_mapping(plan, mode)
+            ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
+            if ms < best[1]:
+                best = (ttc.ttc_plan_get_info(plan), ms)
+        ttc.ttc_plan_set_tile_mapping(plan, -1)
         ttc.ttc_plan_set_streaming(plan, -1, -1)
         rows[i] = best
     return rows
