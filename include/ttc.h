@@ -171,7 +171,7 @@ int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b);
  * How the selected candidate deals its tiles to the 8 XCDs (each has its own L2): the MI355X form of the
  * paper's loop-order question (Section 3.3) one level up.  mode 0: tile ids round robin over all workgroups;
  * 1: one contiguous range of tile ids per XCD; 2..10: chunks of 2^mode consecutive tile ids dealt to the
- * XCDs in turn; -1: the default (chunks of 32).  Reported as xcd_remap by ttc_plan_get_info.  The search
+ * XCDs in turn; -1: the default (chunks of 32; round robin below 2048 tiles).  Reported as xcd_remap by ttc_plan_get_info.  The search
  * times its finalists with modes 1 and 3 as well.  Host only.
  */
 int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode);

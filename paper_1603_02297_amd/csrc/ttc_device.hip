@@ -200,6 +200,12 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
     const int st0 = time_one(plan->cands[0], 2, 3, &first_ms);
     if (st0 != TTC_OK) return st0;
     const float unit = first_ms > 1e-4f ? first_ms : 1e-4f;
+    {   // a GPU that has been idle runs its first milliseconds at low clocks (short launches measured 3-4x
+        // slower there): keep it busy for about 3 ms before anything is compared
+        float ignored = 0.f;
+        const int st_warm = time_one(plan->cands[0], std::min(2000, std::max(1, (int)std::ceil(3.0f / unit))), 1, &ignored);
+        if (st_warm != TTC_OK) return st_warm;
+    }
     const int reps1 = std::min(40, std::max(3, (int)std::ceil(0.2f / unit)));
     const int reps2 = std::min(200, std::max(12, (int)std::ceil(1.0f / unit)));
     std::vector<std::pair<float, int>> timed;
@@ -233,7 +239,8 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         }
         c.kp.nt_a = keep_a;
         c.kp.nt_b = keep_b;
-        // the same for the mapping of tiles to XCDs: chunks of 32 (the default), one range per XCD, chunks of 8
+        // the same for the mapping of tiles to XCDs: the default (chunks of 32 if there are enough tiles), one
+        // range per XCD, chunks of 8
         const int mapping0 = c.kp.xcd_remap;
         int keep_map = mapping0;
         for (int mode : {1, 3}) {

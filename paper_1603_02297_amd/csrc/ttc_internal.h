@@ -159,7 +159,8 @@ int cache_lookup(ttc_plan_s* plan, const char* path);
 uint32_t launch_grid(const Candidate& c, int cus);
 void set_grid(KernelParams* kp, uint32_t grid);
 // tile ids -> XCDs: 0 round robin, 1 one contiguous range per XCD, 2..10: chunks of 2^mode tiles dealt in turn
-constexpr int kDefaultTileMapping = 5;
+// mode -1: the default, chunks of 32 tiles; round robin below 2048 tiles
+constexpr int kDefaultTileMapping = -1;
 bool set_tile_mapping(KernelParams* kp, int mode);
 void default_streaming(const Problem& P, Candidate* c);
 

@@ -648,6 +648,9 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
 
 bool set_tile_mapping(KernelParams* kp, int mode)
 {
+    if (mode == kDefaultTileMapping) {
+        mode = kp->num_tiles >= 2048u ? 5 : 0;      // few tiles (a workgroup gets one or two): round robin spreads them best
+    }
     if (mode < 0 || mode > 10) return false;
     kp->xcd_remap = mode;
     for (int x = 0; x < 8; ++x) kp->xcd_tiles[x] = 0;
@@ -739,8 +742,8 @@ static AccessShape access_shape(const Problem& P, const Candidate& C)
 
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
-    // Weights fitted to timings of every candidate of 87 problems on MI355X (the benchmark workloads, 3-D and
-    // 5-D problems with odd extents, and a 57-case benchmark drawn by the paper's rules): log-linear least
+    // Weights fitted to timings of every candidate of 105 problems on MI355X (the benchmark workloads, 3-D and
+    // 5-D problems with odd extents, a 57-case benchmark drawn by the paper's rules, power-of-two shapes): log-linear least
     // squares weighted towards the fast candidates, penalties constrained to be penalties, a small ridge term,
     // checked by holding problems out; rounded, with guard rails outside the measured range (runs under 64
     // bytes, small problems).
@@ -765,50 +768,55 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
     }
     const bool order_a = !b_order && a_order, order_mixed = !b_order && !a_order;
     double e = 0.0;
-    // coalescing: the contiguous run per tile and the contiguous piece per wavefront instruction
-    e += 0.008 * oct_below(run_a, 1024.0) + 0.009 * oct_below(run_b, 1024.0);
+    // coalescing: the contiguous run per tile and the contiguous piece per wavefront instruction; where runs
+    // are whole lines their length counts for more (nothing is shared with a neighbour that could hide it)
+    e += 0.002 * oct_below(run_a, 1024.0) + 0.016 * oct_below(run_b, 1024.0);
     e += 0.15 * oct_below(run_a, 64.0) + 0.20 * oct_below(run_b, 64.0);
-    e += 0.024 * oct_below(seg_a, 256.0) + 0.021 * oct_below(seg_b, 256.0);
+    e += 0.015 * oct_below(seg_a, 256.0) + 0.025 * oct_below(seg_b, 256.0);
     e += 0.066 * oct_below(seg_a, 64.0) + 0.10 * oct_below(seg_b, 64.0);
-    // runs of B that start or end inside a line: lines_shared = what a run shares with its neighbours per
-    // 128 bytes it writes; requests = 64-byte write requests per 64 bytes written, minus one.  Both cost
-    // more when B is read as well, and more still when the tiles that share the line run far apart in
-    // time (tile ids in A's order).
+    if (sh.align[0] >= 128) e += 0.026 * oct_below(run_a, 1024.0) - 0.004 * oct_below(run_a, 256.0);
+    if (sh.align[1] >= 128) e += 0.007 * oct_below(run_b, 2048.0);
+    // runs that start or end inside a line: lines_shared = what a run shares with its neighbours per 128
+    // bytes it moves; requests = line (A) or 64-byte write (B) requests per line or 64 bytes moved, minus one.
+    // On the B side both cost more when the tiles that share the line run far apart in time (tile ids in
+    // A's order).
+    const double lines_shared_a = (1.0 - sh.align[0] / 128.0) * 128.0 / run_a;
+    const double requests_a = ((run_a + 128.0 - std::min(sh.align[0], 128)) / 128.0) * 128.0 / run_a - 1.0;
     const double lines_shared = (1.0 - sh.align[1] / 128.0) * 128.0 / run_b;
     const double requests = ((run_b + 64.0 - std::min(sh.align[1], 64)) / 64.0) * 64.0 / run_b - 1.0;
-    e += 0.093 * requests;
-    if (reads_b) e += 0.024 * requests;
-    if (order_a) e += 0.003 + 0.075 * lines_shared + 0.094 * requests;
-    if (order_mixed) e += -0.008 + 0.018 * lines_shared;
-    e -= 0.0485 * (kp.nt_a + kp.nt_b);                                  // sides that stream (whole lines only)
-    e += (kp.a.vec * eb_a >= 16 ? 0.0 : (kp.a.vec * eb_a >= 8 ? 0.046 : 0.060));
-    e += (vec_b * eb_b >= 8 ? 0.0 : 0.017);
-    e += 0.218 * (padded - 1.0);                                        // lanes idle in remainder tiles
+    e += 0.014 * lines_shared_a + 0.014 * requests_a + 0.0705 * requests;
+    if (order_a) e += 0.002 + 0.065 * lines_shared + 0.124 * requests;
+    if (order_mixed) e += -0.010 + 0.021 * lines_shared;
+    e -= 0.0568 * (kp.nt_a + kp.nt_b);                                  // sides that stream (whole lines only)
+    e += (kp.a.vec * eb_a >= 16 ? 0.0 : (kp.a.vec * eb_a >= 8 ? 0.037 : 0.057));
+    e += (vec_b * eb_b >= 8 ? 0.0 : 0.005);
+    if (!direct && kp.b.partial) e -= 0.016;
+    e += 0.214 * (padded - 1.0);                                        // lanes idle in remainder tiles
     // tile size and occupancy
-    e += 0.204 * oct_below(tile_bytes, 8192.0);
-    if (tile_bytes > 16384.0) e -= 0.0745 * std::log2(tile_bytes / 16384.0);
-    if (tile_bytes > 32768.0) e += 0.072 * std::log2(tile_bytes / 32768.0);
+    e += 0.2035 * oct_below(tile_bytes, 8192.0);
+    if (tile_bytes > 16384.0) e -= 0.0626 * std::log2(tile_bytes / 16384.0);
+    if (tile_bytes > 32768.0) e += 0.0629 * std::log2(tile_bytes / 32768.0);
     const double lane_a = (double)kp.a.n_iter * kWave * kp.a.vec / volume;
-    e += 0.048 * (lane_a - 1.0);
+    e += 0.052 * (lane_a - 1.0);
     double groups = 16.0, resident_waves = 32.0;
     if (direct) {
         // no regrouping through LDS: every instruction's piece meets memory as it is
-        e += 0.042 + 0.050 * ((1.0 - sh.align[0] / 128.0) * 128.0 / seg_a + (1.0 - sh.align[1] / 128.0) * 128.0 / seg_b);
+        e += 0.0436 + 0.0555 * ((1.0 - sh.align[0] / 128.0) * 128.0 / seg_a + (1.0 - sh.align[1] / 128.0) * 128.0 / seg_b);
     } else {
         groups = std::min(16.0, std::floor(160.0 * 1024 / C.lds_bytes));
         resident_waves = std::min(32.0, groups * (C.threads / kWave));
-        if (kp.lds_buffers == 1) e += reads_b ? 0.009 : 0.003;
+        if (kp.lds_buffers == 1) e += reads_b ? 0.005 : 0.002;
         const double lane_b = (double)kp.b.n_iter * kWave * kp.b.vec / volume;
-        e += 0.004 * (lane_b - 1.0);
+        e += 0.006 * (lane_b - 1.0);
     }
-    if (resident_waves < 16.0) e += 0.260 * (16.0 - resident_waves) / 16.0;
-    if (resident_waves < 8.0) e += 0.2535 * (8.0 - resident_waves) / 8.0;
-    if (groups < 4.0) e += 0.0475 * (4.0 - groups) / 4.0;
+    if (resident_waves < 16.0) e += 0.233 * (16.0 - resident_waves) / 16.0;
+    if (resident_waves < 8.0) e += 0.277 * (8.0 - resident_waves) / 8.0;
+    if (groups < 4.0) e += 0.061 * (4.0 - groups) / 4.0;
     // launch shape: measured preference
-    if (C.threads == 128) e -= reads_b ? 0.081 : 0.029;
-    else if (C.threads == 512) e += 0.032;
+    if (C.threads == 128) e -= reads_b ? 0.0744 : 0.0259;
+    else if (C.threads == 512) e += 0.0285;
     if (C.wg_per_cu == 4) e += 0.022;
-    else if (C.wg_per_cu == 8) e += 0.024;
+    else if (C.wg_per_cu == 8) e += 0.0225;
     // too few tiles to fill the chip (a problem too small for 2048 tiles of 8 KB is not pushed below 8 KB)
     const double tiles_wanted = std::min(2048.0, std::max(1.0, (double)P.elements * eb_a / 8192.0));
     if (kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - kp.num_tiles) / 2048.0;
@@ -1144,7 +1152,7 @@ int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode)
     if (!plan) return TTC_ERR_NULL_POINTER;
     if (mode < -1 || mode > 10) return TTC_ERR_INVALID_VALUE;
     ttc::Candidate& C = plan->cands[plan->selected];
-    return ttc::set_tile_mapping(&C.kp, mode < 0 ? ttc::kDefaultTileMapping : mode) ? TTC_OK : TTC_ERR_INVALID_VALUE;
+    return ttc::set_tile_mapping(&C.kp, mode) ? TTC_OK : TTC_ERR_INVALID_VALUE;
 }
 
 int ttc_plan_candidate_count(ttc_plan_t plan)

@@ -433,16 +433,28 @@ def test_every_tile_mapping_covers_the_tensor(sizes, perm):
     want = [-1] * int(np.prod(sizes))
     for off_a, off_b in oracle.element_pairs(sizes, perm, None, None):
         want[off_b] = off_a
+    def default_mode(tiles):         # chunks of 32; round robin where a workgroup gets one or two tiles at most
+        return 5 if tiles >= 2048 else 0
     p = plan(ttc.TTC_F32, sizes, perm)
-    assert ttc.ttc_plan_get_info(p)["xcd_remap"] == 5                  # the default: chunks of 32
     n = ttc.ttc_plan_candidate_count(p)
     for k in sorted({0, n // 7, n // 2, n - 1}):
         ttc.ttc_plan_select_candidate(p, k)
+        tiles = ttc.ttc_plan_get_info(p)["num_tiles"]
+        assert ttc.ttc_plan_get_info(p)["xcd_remap"] == default_mode(tiles)
         for mode in (0, 1, 2, 3, 5, 8, 10, -1):
             ttc.ttc_plan_set_tile_mapping(p, mode)
-            assert ttc.ttc_plan_get_info(p)["xcd_remap"] == (5 if mode < 0 else mode)
+            assert ttc.ttc_plan_get_info(p)["xcd_remap"] == (default_mode(tiles) if mode < 0 else mode)
             assert list(ttc.ttc_debug_emulate_map(p)) == want, (k, mode)
     for bad in (-2, 11):
         with pytest.raises(ttc.TtcError):
             ttc.ttc_plan_set_tile_mapping(p, bad)
     ttc.ttc_plan_destroy(p)
+
+
+def test_default_tile_mapping_follows_the_tile_count():
+    # 200 MB problems get chunks of 32 tiles; a problem with a few hundred tiles is dealt round robin, so that
+    # no XCD is left without work
+    big = info_of(ttc.TTC_F32, (384, 384, 384), (2, 1, 0))
+    assert big["num_tiles"] >= 2048 and big["xcd_remap"] == 5
+    small = info_of(ttc.TTC_F32, (256, 256), (1, 0))
+    assert small["num_tiles"] < 256 and small["xcd_remap"] == 0
