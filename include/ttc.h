@@ -96,21 +96,23 @@ typedef struct {
     int64_t stride_a[TTC_MAX_DIM];         /* element stride of each fused index in A ... */
     int64_t stride_b[TTC_MAX_DIM];         /* ... and in B */
     int     candidate_index;               /* which candidate is selected */
-    int     candidate_count;               /* how many the plan holds (ranked by the heuristic, best first) */
+    int     candidate_count;               /* how many the plan holds: 1 until the ranked list has been built (ttc_plan_create),
+                                              then all of them: candidate 0 as created, the others by heuristic cost */
     float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
     double  heuristic_cost;                /* the ranking key: modelled relative cost, smaller is better */
 } ttc_plan_info_t;
 
 /*
  * Create a plan for one transposition (paper Eq. 1; defaults of Table 1).
- *   dtype       TTC_F32 / TTC_F64 / TTC_C64.
+ *   dtype       any TTC_* element type; for the mixed-precision pairs see ttc_plan_create_ex.
  *   ndim        1..TTC_MAX_DIM.
  *   sizes, perm HOST arrays of length ndim, copied; every extent >= 1.
- *   alpha, beta HOST pointers to one scalar of dtype (float, double, float[2]);
- *               NULL means alpha = 1, beta = 0.  Copied.
+ *   alpha, beta HOST pointers to one scalar of dtype (float, double, float[2], double[2]; double or
+ *               double[2] for the mixed-precision pairs); NULL means alpha = 1, beta = 0.  Copied.
  * Touches no device.  Returns NULL on error; ttc_last_status() says why.
- * The plan holds a ranked list of candidate launch configurations (tile shape, vector
- * widths, lane mapping, tile order); candidate 0, the heuristic's choice, is selected.
+ * Only the heuristic's choice (candidate 0: tile shape, vector widths, lane mapping, tile order) is
+ * laid out here; the ranked list of all candidate launch configurations is built when something
+ * first asks for it (ttc_plan_candidate_count, ttc_plan_select_candidate, the search, the plan store).
  */
 ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int* perm,
                            const void* alpha, const void* beta);
@@ -118,7 +120,7 @@ ttc_plan_t ttc_plan_create(int dtype, int ndim, const int64_t* sizes, const int*
 /*
  * The same for tensors that are parts of larger ones, and for every data type of Table 1.
  *   lda   HOST array of length ndim or NULL: lda[k] >= sizes[k] is the extent of the enclosing tensor
- *         along index k of A ("leading dimension of each index of A", Table 1 --lda), so A's element
+ *         along index k of A (Table 1, --lda), so A's element
  *         strides are 1, lda[0], lda[0]*lda[1], ...  NULL = dense.  The sub-tensor starts at the pointer
  *         later given to ttc_execute (the caller adds the offset of its corner).
  *   ldb   likewise for B: ldb[j] >= sizes[perm[j]] belongs to index j of B.
@@ -213,40 +215,6 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
  */
 int ttc_plan_cache_store(ttc_plan_t plan, const char* path);
 int ttc_plan_cache_lookup(ttc_plan_t plan, const char* path);
-
-/*
- * Measurement helper: enqueue `warmup` untimed and `iters` timed ttc_execute calls on
- * `stream`, launch i using the buffer pair (A_list[i % npairs], B_list[i % npairs])
- * (HOST arrays of DEVICE pointers; rotating pairs keeps the last-level cache from holding
- * the working set), bracket the timed launches with HIP events recorded on `stream`, wait
- * for them, and return the mean milliseconds per launch in *ms_per_launch.  SYNCHRONISES.
- */
-int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
-                     void* stream, int warmup, int iters, float* ms_per_launch);
-
-/*
- * Bandwidth ceilings measured the same way (the role of the STREAM/SAXPY lines in the
- * paper's Section 4).  kind 0: dst <- src with a 128-bit-per-lane copy kernel (1 read, 1
- * write); kind 1: hipMemcpyAsync device-to-device; kind 2: dst <- 0.75*src + 1.25*dst as
- * fp32 (2 reads, 1 write); kind 3: the copy kernel of kind 0 with non-temporal loads and stores.  `bytes` must be a multiple of 16 and the pointers 16-byte
- * aligned.  Buffer pairs rotate as in ttc_time_execute.  SYNCHRONISES.
- */
-int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src_list,
-                     void* const* dst_list, void* stream, int warmup, int iters,
-                     float* ms_per_launch);
-
-/*
- * Host-side bounds checker for the planner and the kernels' index arithmetic; it is a test
- * aid, never part of ttc_execute.  Replays the walk of the selected candidate lane by lane on
- * the host, with the index code the kernels are compiled from, and writes to b_from_a[o]
- * (HOST array of span_b entries, see ttc_plan_info_t; prod(sizes) for dense tensors) the element
- * offset of A that the candidate moves to element offset o of B (the element map of paper Eq. 1),
- * -1 where B is not written.  Returns TTC_ERR_INTERNAL if any access would leave the (sub-)tensors
- * or the LDS tile, or an element of B would not be written at all or be written twice from different
- * sources (overlapping vectors write an element twice with the same value; if beta != 0 they must
- * belong to one instruction).  Cost grows with prod(sizes).
- */
-int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a);
 
 #ifdef __cplusplus
 }

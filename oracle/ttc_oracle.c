@@ -16,9 +16,9 @@
  *     The parallel-code listing of Section 3.5 (permutation (i3,i2,i1)) fixes this
  *     reading: its B address has i3 at stride 1.
  *
- * Walk: B is visited linearly (the loop order of the paper's reference routine,
- * Section 4.2: "output tensor accessed in a perfectly linear fashion"), an odometer
- * over B's multi-index keeps the matching offset into A.  No index fusion, no
+ * Walk: B is visited in the order of its linear offsets (the loop order of the paper's
+ * reference routine, Section 4.2), an odometer over B's multi-index keeps the matching
+ * offset into A.  No index fusion, no
  * tiling, no reordering.
  *
  * Arithmetic, per element, in the precision of the data type, round to nearest

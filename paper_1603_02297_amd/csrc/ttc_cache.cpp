@@ -12,6 +12,7 @@
 // if no candidate of the current library matches, the entry is ignored.  Later lines win.
 #include <cstdio>
 #include <cstring>
+#include <new>
 #include <sstream>
 #include <string>
 #include <vector>
@@ -94,13 +95,19 @@ int cache_lookup(ttc_plan_s* plan, const char* path)
     }
     if (tailv.size() != 4 || (tailv[0] | 1) != 1 || (tailv[1] | 1) != 1 || tailv[2] < 0 || tailv[2] > 10) return TTC_ERR_NOT_FOUND;
     us = tailv[3];
+    const int st = complete_plan(plan);           // an entry may name any candidate of the full list
+    if (st != TTC_OK) return st;
     for (size_t i = 0; i < plan->cands.size(); ++i) {
         if (config_signature(plan->cands[i]) == sig) {
+            // everything is applied to a copy first: a refused entry leaves the plan as it was
+            Candidate c = plan->cands[i];
+            c.kp.nt_a = (int)tailv[0];
+            c.kp.nt_b = (int)tailv[1];
+            if (c.kernel_class == TTC_KERNEL_DIRECT && c.kp.nt_a != c.kp.nt_b) return TTC_ERR_NOT_FOUND;   // streams both sides or neither
+            if (!set_tile_mapping(&c.kp, (int)tailv[2])) return TTC_ERR_NOT_FOUND;
+            c.tuned_ms = (float)us / 1000.0f;
+            plan->cands[i] = c;
             plan->selected = (int)i;
-            plan->cands[i].kp.nt_a = (int)tailv[0];
-            plan->cands[i].kp.nt_b = (int)tailv[1];
-            if (!set_tile_mapping(&plan->cands[i].kp, (int)tailv[2])) return TTC_ERR_NOT_FOUND;
-            plan->cands[i].tuned_ms = (float)us / 1000.0f;
             return TTC_OK;
         }
     }
@@ -114,13 +121,13 @@ extern "C" {
 int ttc_plan_cache_store(ttc_plan_t plan, const char* path)
 {
     if (!plan || !path) return TTC_ERR_NULL_POINTER;
-    try { return ttc::cache_store(plan, path); } catch (...) { return TTC_ERR_ALLOC; }
+    try { return ttc::cache_store(plan, path); } catch (const std::bad_alloc&) { return TTC_ERR_ALLOC; } catch (...) { return TTC_ERR_INTERNAL; }
 }
 
 int ttc_plan_cache_lookup(ttc_plan_t plan, const char* path)
 {
     if (!plan || !path) return TTC_ERR_NULL_POINTER;
-    try { return ttc::cache_lookup(plan, path); } catch (...) { return TTC_ERR_ALLOC; }
+    try { return ttc::cache_lookup(plan, path); } catch (const std::bad_alloc&) { return TTC_ERR_ALLOC; } catch (...) { return TTC_ERR_INTERNAL; }
 }
 
 }  // extern "C"

@@ -15,7 +15,9 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
+#include <new>
 #include <cstring>
 #include <vector>
 
@@ -59,12 +61,6 @@ static int check_buffers(const ttc_plan_s* plan, const void* A, const void* B)
     const uintptr_t bytes_a = (uintptr_t)P.span_a * P.eb_a, bytes_b = (uintptr_t)P.span_b * P.eb_b;
     if (a < b + bytes_b && b < a + bytes_a) return TTC_ERR_ALIAS;
     return TTC_OK;
-}
-
-static const Candidate& pick_candidate(const ttc_plan_s* plan, const void* A, const void* B)
-{
-    (void)A; (void)B;
-    return plan->cands[plan->selected];
 }
 
 // ---------------------------------------------------------------------------------
@@ -152,12 +148,23 @@ int ttc_execute(ttc_plan_t plan, const void* A, void* B, void* stream)
 {
     const int st = ttc::check_buffers(plan, A, B);
     if (st != TTC_OK) return st;
-    const ttc::Candidate& c = ttc::pick_candidate(plan, A, B);
+    const ttc::Candidate& c = plan->cands[plan->selected];
     return ttc::launch(plan->prob, c, A, B, (hipStream_t)stream) == hipSuccess ? TTC_OK : TTC_ERR_HIP;
 }
 
+static int tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                      void* stream, int max_candidates);
+
 int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
                         void* stream, int max_candidates)
+{
+    try { return tune_pairs(plan, npairs, A_list, B_list, stream, max_candidates); }
+    catch (const std::bad_alloc&) { return TTC_ERR_ALLOC; }
+    catch (...) { return TTC_ERR_INTERNAL; }
+}
+
+static int tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, void* const* B_list,
+                      void* stream, int max_candidates)
 {
     if (!plan || !A_list || !B_list) return TTC_ERR_NULL_POINTER;
     if (npairs < 1) return TTC_ERR_INVALID_VALUE;
@@ -172,9 +179,11 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         cap = e ? std::atoi(e) : 200;
         if (cap == 0) cap = 200;
     }
+    if (cap == 1) return ttc_plan_select_candidate(plan, 0);         // the heuristic's choice, nothing timed
+    const int st_list = ttc::complete_plan(plan);
+    if (st_list != TTC_OK) return st_list;
     const int total = (int)plan->cands.size();
     if (cap < 0 || cap > total) cap = total;
-    if (cap == 1) { plan->selected = 0; return TTC_OK; }
     const char* store = std::getenv("TTC_PLAN_CACHE");
     if (store && *store && ttc::cache_lookup(plan, store) == TTC_OK) return TTC_OK;     // solved before
     ttc::EventPair ev;
@@ -255,6 +264,8 @@ int ttc_plan_tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, 
         if (best < 0 || cand_ms < best_ms) { best = i; best_ms = cand_ms; }
     }
     if (best >= 0) plan->selected = best;
+    if (ttc::verbose())
+        std::fprintf(stderr, "ttc: search timed %d of %d candidates, selected %d (%.4f ms)\n", cap, total, plan->selected, best_ms);
     if (store && *store) (void)ttc::cache_store(plan, store);       // a store that cannot be written costs a later search, no more
     return TTC_OK;
 }

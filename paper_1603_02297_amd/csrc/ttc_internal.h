@@ -7,13 +7,14 @@
 #include <vector>
 
 #include "ttc.h"
+#include "ttc_aux.h"
 
 namespace ttc {
 
 constexpr int kMaxDim = TTC_MAX_DIM;
 constexpr int kWave = 64;                 // CDNA wavefront
 constexpr int kMaxThreads = 512;          // launch bound of every kernel
-constexpr int kMaxLdsBytes = 64 * 1024;   // per workgroup; several workgroups share a CU's 160 KB
+constexpr int kMaxLdsBytes = 160 * 1024;  // per workgroup: all of a CU's LDS (gfx950); smaller tiles let several workgroups share it
 
 // Exact unsigned division by a run-time constant d >= 1 for any 32-bit x whose
 // quotient sum does not overflow (x < 2^31 is enough):
@@ -141,9 +142,10 @@ struct Problem {
 
 struct ttc_plan_s {
     ttc::Problem prob;
-    std::vector<ttc::Candidate> cands;     // ranked, best first
+    std::vector<ttc::Candidate> cands;     // complete: candidate 0 is ttc_plan_create's choice, the others follow ranked
+                                           // by the heuristic cost; not complete: only that choice
     int selected;
-    int fallback;                          // index of a candidate with vec_a = vec_b = 1
+    bool complete;
 };
 
 namespace ttc {
@@ -151,7 +153,9 @@ namespace ttc {
 // Host planner.  Returns TTC_OK and fills *out, or a status.
 int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const int64_t* lda, const int64_t* ldb,
                const void* alpha, const void* beta, ttc_plan_s* out);
+int complete_plan(ttc_plan_s* plan);
 void set_last_status(int status);
+bool verbose();
 // Plan store (ttc_cache.cpp).
 int cache_store(const ttc_plan_s* plan, const char* path);
 int cache_lookup(ttc_plan_s* plan, const char* path);

@@ -15,6 +15,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "ttc_internal.h"
@@ -180,7 +181,6 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
     // copy the language asks for, and past a certain number of uses it keeps the copy: 1.4 KB of scratch per lane.
     const KernelParams& p = *reinterpret_cast<const KernelParams*>((const void*)__builtin_amdgcn_kernarg_segment_ptr());
     extern __shared__ __align__(16) unsigned char smem[];
-#if 1
     {   // Bring the whole parameter block into the scalar cache at once (read-only scalar loads of one word per
         // 64-byte line): the set-up code below reads it piece by piece, and each piece would otherwise be a miss.
         typedef const uint32_t __attribute__((address_space(4))) ConstWord;
@@ -190,7 +190,6 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
         for (int i = 0; i < (int)(sizeof(KernelParams) / 64); ++i) touched ^= args[i * 16];
         asm volatile("" :: "s"(touched));
     }
-#endif
     constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
     const Scales sc_a = {kScaleA, kScaleB, kScaleA};     // walk over A; the LDS tile holds elements of A
     const Scales sc_b = {kScaleB, kScaleB, kScaleA};     // walk over B
@@ -357,9 +356,23 @@ inline hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uin
                              int lds_bytes, hipStream_t stream)
 {
     if (grid != kp.grid || grid < 1 || grid > kp.num_tiles) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((box_kernel<TA, TB, MODE, VA, VB, DIRECT>), dim3(grid), dim3(threads), (size_t)lds_bytes, stream,
-                       kp, static_cast<const TA*>(A), static_cast<TB*>(B));
-    return hipGetLastError();
+    const void* fn = reinterpret_cast<const void*>(&box_kernel<TA, TB, MODE, VA, VB, DIRECT>);
+    // more than 64 KB of dynamic LDS has to be asked for, once per kernel and device (a CU of gfx950 has 160 KB)
+    if (lds_bytes > 64 * 1024) {
+        static std::atomic<uint64_t> raised{0};                 // bit d: done on device d
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!((raised.load(std::memory_order_acquire) >> dev) & 1u)) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+            if (e != hipSuccess) return e;
+            raised.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+        }
+    }
+    const TA* a = static_cast<const TA*>(A);
+    TB* b = static_cast<TB*>(B);
+    void* args[] = {const_cast<KernelParams*>(&kp), &a, &b};
+    // the launch's own status: an error left behind by an earlier, unrelated call on this thread is not ours
+    return hipLaunchKernel(fn, dim3(grid), dim3(threads), args, (size_t)lds_bytes, stream);
 }
 
 // VMAXA / VMAXB: elements of each type in 16 bytes

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <unordered_map>
 
 #include "ttc_internal.h"
 #include "ttc_walk.h"
@@ -16,10 +17,17 @@ namespace ttc {
 static thread_local int g_last_status = TTC_OK;
 void set_last_status(int status) { g_last_status = status; }
 
+// TTC_VERBOSE=1 in the environment: one line on stderr per plan, per completed candidate list and per search
+bool verbose()
+{
+    static const bool on = [] { const char* e = std::getenv("TTC_VERBOSE"); return e && *e && *e != '0'; }();
+    return on;
+}
+
 FastDiv make_fastdiv(uint32_t d)
 {
     FastDiv f;
-    if (d < 1) d = 1;
+    if (d <= 1) { f.div = 1; f.shift = 0; f.mul = 1; return f; }      // (x * 1 >> 32) + x >> 0 = x for x < 2^32
     uint32_t s = 0;
     while ((1ull << s) < d) ++s;
     f.div = d;
@@ -384,34 +392,54 @@ static bool fill_side(const Problem& P, const WalkSpec& w, int vec, const int* s
 // stride-1 index comes first, the others follow, each chain head on a small pad chosen by
 // simulating which banks the 64 lanes of one LDS instruction touch.
 // ---------------------------------------------------------------------------------
-static int bank_multiplicity(const Problem& P, const Side& s, int banks)
+// Lane coordinates of one walk, per digit slot, in flat elements: what the bank simulation needs besides the
+// LDS strides (computed once per layout search; the strides change from one trial layout to the next).
+struct LaneCoords { int lanes, vec; int c[kWave][kBoxDims]; };
+
+static void lane_coords(const Side& s, LaneCoords* out)
 {
-    const int words = P.eb_a / 4;               // the LDS tile holds elements of A
-    int worst = 1;
-    std::vector<int64_t> addr(kWave);
-    for (int j = 0; j < s.vec; ++j) {
-        int n = 0;
-        for (int lane = 0; lane < s.lanes; ++lane) {
-            int64_t a = (int64_t)j * s.vec_lds_stride;
-            for (int i = 0; i < kBoxDims; ++i) {
-                const Digit& d = s.d[i];
-                const uint32_t c = (lane / d.lane_below.div) % d.lane_cnt.div;
-                a += (int64_t)c * d.lane_mul * d.lstride;
-            }
-            addr[n++] = a * words;
+    out->lanes = s.lanes;
+    out->vec = s.vec;
+    for (int lane = 0; lane < s.lanes; ++lane)
+        for (int i = 0; i < kBoxDims; ++i) {
+            const Digit& d = s.d[i];
+            out->c[lane][i] = (int)((lane / d.lane_below.div) % d.lane_cnt.div) * d.lane_mul;
         }
-        // distinct word addresses per bank (same address = broadcast, no conflict)
-        std::sort(addr.begin(), addr.begin() + n);
-        n = (int)(std::unique(addr.begin(), addr.begin() + n) - addr.begin());
-        std::vector<int> cnt(banks, 0);
-        for (int i = 0; i < n; ++i)
-            for (int w = 0; w < words; ++w) cnt[(addr[i] + w) % banks]++;
-        const int ideal = (int)ceil_div((int64_t)n * words, banks);
-        int mx = 0;
-        for (int b = 0; b < banks; ++b) mx = std::max(mx, cnt[b]);
-        worst = std::max(worst, (int)ceil_div(mx, std::max(ideal, 1)));
+}
+
+// Worst number of distinct addresses that the lanes of one LDS instruction send to one bank, relative to the
+// unavoidable number (ceil(addresses / banks)), for 32 and for 64 banks; the two are added (2 = conflict-free).
+static int bank_multiplicity(const LaneCoords& lc, const int* lstride /* per slot */, int vec_stride, int words)
+{
+    int worst32 = 1, worst64 = 1;
+    int64_t base[kWave], addr[kWave];
+    for (int lane = 0; lane < lc.lanes; ++lane) {
+        int64_t a = 0;
+        for (int i = 0; i < kBoxDims; ++i) a += (int64_t)lc.c[lane][i] * lstride[i];
+        base[lane] = a;
     }
-    return worst;
+    for (int j = 0; j < lc.vec; ++j) {
+        int n = lc.lanes;
+        for (int lane = 0; lane < n; ++lane) addr[lane] = (base[lane] + (int64_t)j * vec_stride) * words;
+        // distinct word addresses per bank (same address = broadcast, no conflict)
+        std::sort(addr, addr + n);
+        n = (int)(std::unique(addr, addr + n) - addr);
+        int cnt32[32] = {0}, cnt64[64] = {0};
+        for (int i = 0; i < n; ++i)
+            for (int w = 0; w < words; ++w) {
+                const uint64_t x = (uint64_t)(addr[i] + w);
+                cnt32[x & 31u]++;
+                cnt64[x & 63u]++;
+            }
+        int mx32 = 0, mx64 = 0;
+        for (int b = 0; b < 32; ++b) mx32 = std::max(mx32, cnt32[b]);
+        for (int b = 0; b < 64; ++b) mx64 = std::max(mx64, cnt64[b]);
+        const int ideal32 = std::max(1, (int)ceil_div((int64_t)n * words, 32));
+        const int ideal64 = std::max(1, (int)ceil_div((int64_t)n * words, 64));
+        worst32 = std::max(worst32, (int)ceil_div(mx32, ideal32));
+        worst64 = std::max(worst64, (int)ceil_div(mx64, ideal64));
+    }
+    return worst32 + worst64;
 }
 
 struct LdsLayout { int stride[kMaxDim]; int elems; int conflict_a, conflict_b; };
@@ -421,12 +449,24 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
                                    const int* next_in_chain /* by dim, -1 = chain end */,
                                    const bool* is_head /* by dim */)
 {
+    LdsLayout best;
+    best.elems = 0; best.conflict_a = best.conflict_b = 1 << 20;
     // chain heads in layout order: the chain of index 0 first, then by index
     int heads[kMaxDim], nh = 0;
     for (int k = 0; k < P.ndim; ++k) if (t[k] > 1 && is_head[k]) heads[nh++] = k;
     const int npad = std::max(0, std::min(nh - 1, 3));
-    LdsLayout best;
-    best.elems = 0; best.conflict_a = best.conflict_b = 1 << 20;
+    // the walks' lane mappings do not depend on the LDS strides: lay the sides out once
+    Side sa, sb;
+    const int zero[kMaxDim] = {0, 0, 0, 0, 0, 0};
+    if (!fill_side(P, wa, va, slot_of_dim, zero, false, &sa)) return best;
+    if (!fill_side(P, wb, vb, slot_of_dim, zero, true, &sb)) return best;
+    LaneCoords la, lb;
+    lane_coords(sa, &la);
+    lane_coords(sb, &lb);
+    int dim_of_slot_a[kBoxDims] = {-1, -1, -1, -1}, dim_of_slot_b[kBoxDims] = {-1, -1, -1, -1};
+    for (int i = 0; i < wa.nd; ++i) dim_of_slot_a[slot_of_dim[wa.d[i].outer_dim]] = wa.d[i].first_dim;
+    for (int i = 0; i < wb.nd; ++i) dim_of_slot_b[slot_of_dim[wb.d[i].outer_dim]] = wb.d[i].first_dim;
+    const int words = P.eb_a / 4;               // the LDS tile holds elements of A
     int64_t best_cost = INT64_MAX;
     const int combos = 1 << (2 * npad);
     for (int c = 0; c < combos; ++c) {
@@ -442,11 +482,13 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
         }
         L.elems = (int)run;
         if ((int64_t)L.elems * P.eb_a > kMaxLdsBytes) continue;
-        Side sa, sb;
-        if (!fill_side(P, wa, va, slot_of_dim, L.stride, false, &sa)) continue;
-        if (!fill_side(P, wb, vb, slot_of_dim, L.stride, true, &sb)) continue;
-        L.conflict_a = bank_multiplicity(P, sa, 32) + bank_multiplicity(P, sa, 64);
-        L.conflict_b = bank_multiplicity(P, sb, 32) + bank_multiplicity(P, sb, 64);
+        int ls_a[kBoxDims], ls_b[kBoxDims];
+        for (int j = 0; j < kBoxDims; ++j) {
+            ls_a[j] = dim_of_slot_a[j] >= 0 ? L.stride[dim_of_slot_a[j]] : 0;
+            ls_b[j] = dim_of_slot_b[j] >= 0 ? L.stride[dim_of_slot_b[j]] : 0;
+        }
+        L.conflict_a = bank_multiplicity(la, ls_a, L.stride[wa.d[0].first_dim], words);
+        L.conflict_b = bank_multiplicity(lb, ls_b, L.stride[wb.d[0].first_dim], words);
         const int64_t cost = ((int64_t)(L.conflict_a + L.conflict_b) << 24) + L.elems;
         if (cost < best_cost) { best_cost = cost; best = L; }
         if (L.conflict_a + L.conflict_b == 4) break;             // conflict-free under both bank counts
@@ -851,12 +893,35 @@ void default_streaming(const Problem& P, Candidate* c)
     if (c->kernel_class == TTC_KERNEL_DIRECT) c->kp.nt_a = c->kp.nt_b = (c->kp.nt_a && c->kp.nt_b) ? 1 : 0;   // both or neither
 }
 
-static void add_candidate(const Problem& P, std::vector<Candidate>& v, const Candidate& c)
+// what same_config() compares, folded into one number: candidates are looked up by it instead of being
+// compared with every earlier one
+static uint64_t config_hash(const Candidate& c)
 {
-    for (const Candidate& o : v) if (same_config(o, c)) return;
-    v.push_back(c);
-    default_streaming(P, &v.back());
-    v.back().score = heuristic_cost(P, v.back());
+    uint64_t h = 1469598103934665603ull;
+    auto mix = [&](int64_t x) { h = (h ^ (uint64_t)x) * 1099511628211ull; };
+    mix(c.kernel_class); mix(c.threads); mix(c.wg_per_cu);
+    mix(c.kp.a.vec); mix(c.kp.b.vec); mix(c.kp.lds_buffers);
+    for (int k = 0; k < kMaxDim; ++k) { mix(c.tile[k]); mix(c.kp.tile_below[k].div); }
+    for (int i = 0; i < kBoxDims; ++i) { mix(c.dlane_a[i]); mix(c.dlane_b[i]); mix(c.dtile_a[i]); mix(c.dtile_b[i]); }
+    return h;
+}
+
+struct CandidateList {
+    std::vector<Candidate>& v;
+    std::unordered_multimap<uint64_t, size_t> seen;
+    explicit CandidateList(std::vector<Candidate>& out) : v(out) {}
+};
+
+static void add_candidate(const Problem& P, CandidateList& L, const Candidate& c)
+{
+    const uint64_t h = config_hash(c);
+    const auto range = L.seen.equal_range(h);
+    for (auto it = range.first; it != range.second; ++it)
+        if (same_config(L.v[it->second], c)) return;
+    L.seen.emplace(h, L.v.size());
+    L.v.push_back(c);
+    default_streaming(P, &L.v.back());
+    L.v.back().score = heuristic_cost(P, L.v.back());
 }
 
 static int max_vec(int eb, int64_t extent)
@@ -868,10 +933,33 @@ static int max_vec(int eb, int64_t extent)
 
 // Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
 struct LaunchShape { int threads, wg_per_cu; };
-static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}, {512, 8}};
+static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}, {512, 8}, {64, 32}, {64, 16}};
 
-static void enumerate(const Problem& P, std::vector<Candidate>& out)
+// Different run-length targets often ask for the same box: each (box, vector rule, kernel family) is expanded once.
+struct ShapesSeen {
+    struct Key { int t[kMaxDim]; int vec, family; };
+    std::vector<Key> keys;
+    bool first_time(const int* t, int vec, int family)
+    {
+        for (const Key& k : keys) {
+            bool same = (k.vec == vec && k.family == family);
+            for (int i = 0; same && i < kMaxDim; ++i) same = (k.t[i] == t[i]);
+            if (same) return false;
+        }
+        Key k;
+        for (int i = 0; i < kMaxDim; ++i) k.t[i] = t[i];
+        k.vec = vec; k.family = family;
+        keys.push_back(k);
+        return true;
+    }
+};
+
+// quick: only the variants the ranking prefers (both walks merged, the two favoured launch shapes) -- what
+// ttc_plan_create pays for; the full list is built when something first asks for it.
+static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool quick)
 {
+    CandidateList out(out_list);
+    ShapesSeen shapes;
     LayoutCache cache;
     const int n = P.ndim;
     const int eb = std::max(P.eb_a, P.eb_b);
@@ -891,6 +979,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     }
     const int* orders[4] = {order_b, order_a, order_ab, order_ba};
     const int norders = stride1_fixed ? 2 : 4;
+    const int nshapes = quick ? 2 : (int)(sizeof(kLaunchShapes) / sizeof(kLaunchShapes[0]));
 
     // -- direct candidates: only when the stride-1 index keeps its place.  The box takes leading
     //    indices of A and of B so that both sides move a few long contiguous chunks per tile.
@@ -916,8 +1005,10 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                     for (int k = 0; k < n; ++k) { vol *= t[k]; spanned += (t[k] > 1); }
                     if (spanned > kBoxDims || vol * eb > 128 * 1024) continue;
                     if (vol * eb < 4096 && vol < P.elements) continue;
+                    if (!shapes.first_time(t, v, 0)) continue;
                     for (int o = 0; o < norders; ++o)
-                        for (const LaunchShape& ls : kLaunchShapes) {
+                        for (int li = 0; li < nshapes; ++li) {
+                            const LaunchShape& ls = kLaunchShapes[li];
                             Candidate c;
                             if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], kDefaultTileMapping, &c))
                                 add_candidate(P, out, c);
@@ -953,11 +1044,13 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
                         if (spanned > kBoxDims) continue;
                         if (vol * P.eb_a > kMaxLdsBytes - 2048) continue;
                         if (vol * eb < 2048 && md > 1 && vol < P.elements) continue;
+                        if (!shapes.first_time(t, vec_limit, 1)) continue;
                         for (int nbuf = 2; nbuf >= 1; --nbuf) {
                             if (nbuf == 1 && vol * eb < 8192) continue;     // small tiles can afford two buffers
-                            for (int mg = 0; mg < 4; ++mg)
+                            for (int mg = 0; mg < (quick ? 1 : 4); ++mg)
                                 for (int o = 0; o < norders; ++o)
-                                    for (const LaunchShape& ls : kLaunchShapes) {
+                                    for (int li = 0; li < nshapes; ++li) {
+                                        const LaunchShape& ls = kLaunchShapes[li];
                                         Candidate c;
                                         if (make_candidate(P, t, vec_limit, false, ls.threads, ls.wg_per_cu, orders[o], kDefaultTileMapping,
                                                            &c, (mg & 1) == 0, (mg & 2) == 0, &cache, nbuf))
@@ -969,7 +1062,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out)
     }
 
     // -- last resort so that every problem has a candidate: scalar direct walk in A order
-    if (out.empty() || n == 1) {
+    if (out_list.empty() || n == 1) {
         int t[kMaxDim];
         build_group(P, order_a, P.eb_a, 16384 / eb, 1, kBoxDims, t);
         Candidate c;
@@ -983,31 +1076,55 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
     Problem& P = plan->prob;
     int st = normalise(dtype, ndim, sizes, perm, lda, ldb, alpha, beta, &P);
     if (st != TTC_OK) return st;
-    plan->cands.clear();
-    enumerate(P, plan->cands);
-    if (plan->cands.empty()) return TTC_ERR_OVERFLOW;
-    std::stable_sort(plan->cands.begin(), plan->cands.end(),
-                     [](const Candidate& x, const Candidate& y) { return x.score < y.score; });
+    std::vector<Candidate> quick;
+    enumerate(P, quick, true);
+    if (quick.empty()) enumerate(P, quick, false);
+    if (quick.empty()) return TTC_ERR_OVERFLOW;
+    size_t best = 0;
+    for (size_t i = 1; i < quick.size(); ++i) if (quick[i].score < quick[best].score) best = i;
+    plan->cands.assign(1, quick[best]);
     plan->selected = 0;
-    plan->fallback = -1;
-    for (size_t i = 0; i < plan->cands.size(); ++i)
-        if (plan->cands[i].kp.a.vec == 1 && plan->cands[i].kp.b.vec == 1) { plan->fallback = (int)i; break; }
-    if (plan->fallback < 0) {
-        // every candidate is vectorised: add the scalar variant of the best one
-        const Candidate& b = plan->cands[0];
-        Candidate c;
-        if (!make_candidate(P, b.tile, 1, b.kernel_class == TTC_KERNEL_DIRECT, b.threads, b.wg_per_cu, b.tile_order, kDefaultTileMapping, &c,
-                            true, true, nullptr, b.kp.lds_buffers))
-            return TTC_ERR_OVERFLOW;
-        default_streaming(P, &c);
-        c.score = heuristic_cost(P, c);
-        plan->cands.push_back(c);
-        plan->fallback = (int)plan->cands.size() - 1;
+    plan->complete = false;
+    if (verbose()) {
+        const Candidate& c = plan->cands[0];
+        std::fprintf(stderr, "ttc: plan dtype %d, %d fused indices, %s kernel, tile", P.dtype, P.ndim,
+                     c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : "staged");
+        for (int k = 0; k < P.ndim; ++k) std::fprintf(stderr, " %d", c.tile[k]);
+        std::fprintf(stderr, ", vectors %d/%d, %d threads, %d B LDS, cost %.4f (best of %zu quick candidates)\n",
+                     c.kp.a.vec, c.kp.b.vec, c.threads, c.lds_bytes, c.score, quick.size());
     }
     return TTC_OK;
 }
 
+// The ranked list of all candidates, built on first use.  Candidate 0 stays what ttc_plan_create chose (with
+// whatever the caller has set on it since); the others follow in the order of the heuristic cost.
+int complete_plan(ttc_plan_s* plan)
+{
+    if (plan->complete) return TTC_OK;
+    const Candidate first = plan->cands[plan->selected];
+    std::vector<Candidate> all;
+    enumerate(plan->prob, all, false);
+    std::stable_sort(all.begin(), all.end(), [](const Candidate& x, const Candidate& y) { return x.score < y.score; });
+    std::vector<Candidate> ranked;
+    ranked.reserve(all.size() + 1);
+    ranked.push_back(first);
+    for (const Candidate& c : all) if (!same_config(c, first)) ranked.push_back(c);
+    plan->cands.swap(ranked);
+    plan->selected = 0;
+    plan->complete = true;
+    if (verbose()) std::fprintf(stderr, "ttc: %zu candidates ranked\n", plan->cands.size());
+    return TTC_OK;
+}
+
 }  // namespace ttc
+
+// Nothing may throw across the C boundary: allocation failures and anything unexpected become status codes.
+template <class F> static int guarded(F&& body)
+{
+    try { return body(); }
+    catch (const std::bad_alloc&) { return TTC_ERR_ALLOC; }
+    catch (...) { return TTC_ERR_INTERNAL; }
+}
 
 // The kernels instantiate a walk for a compile-time vector width; the replay picks the same one.
 template <class S1, class S2>
@@ -1081,6 +1198,7 @@ const char* ttc_status_string(int status)
 int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
 {
     if (!plan || !out) return TTC_ERR_NULL_POINTER;
+    return guarded([&]() -> int {
     const ttc::Problem& P = plan->prob;
     const ttc::Candidate& C = plan->cands[plan->selected];
     std::memset(out, 0, sizeof(*out));
@@ -1132,19 +1250,22 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
     return TTC_OK;
+    });
 }
 
 int ttc_plan_set_streaming(ttc_plan_t plan, int stream_a, int stream_b)
 {
     if (!plan) return TTC_ERR_NULL_POINTER;
     if (stream_a < -1 || stream_a > 1 || stream_b < -1 || stream_b > 1) return TTC_ERR_INVALID_VALUE;
-    ttc::Candidate& C = plan->cands[plan->selected];
-    ttc::Candidate rule = C;
-    ttc::default_streaming(plan->prob, &rule);
-    C.kp.nt_a = stream_a < 0 ? rule.kp.nt_a : stream_a;
-    C.kp.nt_b = stream_b < 0 ? rule.kp.nt_b : stream_b;
-    if (C.kernel_class == TTC_KERNEL_DIRECT) C.kp.nt_a = C.kp.nt_b = (C.kp.nt_a && C.kp.nt_b) ? 1 : 0;
-    return TTC_OK;
+    return guarded([&]() -> int {
+        ttc::Candidate& C = plan->cands[plan->selected];
+        ttc::Candidate rule = C;
+        ttc::default_streaming(plan->prob, &rule);
+        C.kp.nt_a = stream_a < 0 ? rule.kp.nt_a : stream_a;
+        C.kp.nt_b = stream_b < 0 ? rule.kp.nt_b : stream_b;
+        if (C.kernel_class == TTC_KERNEL_DIRECT) C.kp.nt_a = C.kp.nt_b = (C.kp.nt_a && C.kp.nt_b) ? 1 : 0;
+        return TTC_OK;
+    });
 }
 
 int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode)
@@ -1158,13 +1279,18 @@ int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode)
 int ttc_plan_candidate_count(ttc_plan_t plan)
 {
     if (!plan) return -TTC_ERR_NULL_POINTER;
-    return (int)plan->cands.size();
+    const int st = guarded([&] { return ttc::complete_plan(plan); });
+    return st == TTC_OK ? (int)plan->cands.size() : -st;
 }
 
 int ttc_plan_select_candidate(ttc_plan_t plan, int index)
 {
     if (!plan) return TTC_ERR_NULL_POINTER;
-    if (index < 0 || index >= (int)plan->cands.size()) return TTC_ERR_INVALID_VALUE;
+    if (index < 0) return TTC_ERR_INVALID_VALUE;
+    if (index == 0 && plan->selected == 0) return TTC_OK;          // the choice of ttc_plan_create: no list needed
+    const int st = guarded([&] { return ttc::complete_plan(plan); });
+    if (st != TTC_OK) return st;
+    if (index >= (int)plan->cands.size()) return TTC_ERR_INVALID_VALUE;
     plan->selected = index;
     return TTC_OK;
 }
@@ -1174,10 +1300,19 @@ int ttc_plan_select_candidate(ttc_plan_t plan, int index)
 // there.  Fails on any access outside the (sub-)tensors or the LDS tile, any access that is
 // not element-aligned, any element of B written twice or never, and any LDS slot read before
 // it was written.
+static int emulate_map(ttc_plan_t plan, int64_t* b_from_a);
+
 int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
 {
-    using namespace ttc;
     if (!plan || !b_from_a) return TTC_ERR_NULL_POINTER;
+    return guarded([&] { return emulate_map(plan, b_from_a); });
+}
+
+}  // extern "C"
+
+static int emulate_map(ttc_plan_t plan, int64_t* b_from_a)
+{
+    using namespace ttc;
     const Problem& P = plan->prob;
     const Candidate& C = plan->cands[plan->selected];
     KernelParams p = C.kp;
@@ -1327,5 +1462,3 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
     }
     return TTC_OK;
 }
-
-}  // extern "C"

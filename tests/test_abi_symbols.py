@@ -1,4 +1,4 @@
-"""The C-ABI library loads without a GPU and exports every function include/ttc.h declares."""
+"""The C-ABI library loads without a GPU and exports every function include/ttc.h and include/ttc_aux.h declare."""
 import ctypes
 import os
 import re
@@ -10,7 +10,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "ttc.h")).read()
+    text = open(os.path.join(ROOT, "include", "ttc.h")).read() + open(os.path.join(ROOT, "include", "ttc_aux.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ttc_[a-z_0-9]+)\s*\(", text)))
 
@@ -42,6 +42,10 @@ def test_info_struct_layout_matches_header():
     p = ttc.ttc_plan_create(ttc.TTC_F32, 3, (6, 5, 4), (2, 0, 1), 1.0, 0.0)
     info = ttc.ttc_plan_get_info(p)
     assert info["elements"] == 120 and info["bytes_moved"] == 2 * 120 * 4
-    assert info["candidate_count"] == ttc.ttc_plan_candidate_count(p) and info["candidate_index"] == 0
+    assert info["candidate_count"] == 1 and info["candidate_index"] == 0      # only the heuristic's choice is laid out yet
     assert info["heuristic_cost"] > 0
+    n = ttc.ttc_plan_candidate_count(p)                                        # builds the ranked list
+    again = ttc.ttc_plan_get_info(p)
+    assert n > 1 and again["candidate_count"] == n and again["candidate_index"] == 0
+    assert {k: v for k, v in again.items() if k != "candidate_count"} == {k: v for k, v in info.items() if k != "candidate_count"}
     ttc.ttc_plan_destroy(p)
