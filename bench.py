@@ -55,6 +55,11 @@ def parse():
     ap.add_argument("--plan-cache", type=str, default=DEFAULT_STORE,
                     help="file of stored search results: cases found there are not searched again")
     ap.add_argument("--search", action="store_true", help="search every case in the run, whatever the store holds")
+    ap.add_argument("--problem", type=str, default="",
+                    help="time this problem instead of the suite: dtype:sizes:perm[:alpha:beta], e.g. f32:85x85x85x85:3210:1:0 "
+                         "(what profiles/ uses for shapes outside the suite; not a bench line)")
+    ap.add_argument("--force-class", type=str, default="", choices=("", "direct", "lds", "rows"),
+                    help="run the best-ranked candidate of this kernel family instead of the stored or searched plan")
     ap.add_argument("--store-plans", type=str, default="",
                     help="append what the run selected for every case to this file (the format of --plan-cache)")
     return ap.parse_args()
@@ -116,7 +121,7 @@ class CpuLeg:
 
 def plan_text(info, ttc) -> str:
     """The selected configuration in one short string (the fields that name it in the plan store and the profiles)."""
-    cls = "direct" if info["kernel_class"] == ttc.TTC_KERNEL_DIRECT else "lds"
+    cls = {ttc.TTC_KERNEL_DIRECT: "direct", ttc.TTC_KERNEL_LDS: "lds", ttc.TTC_KERNEL_ROWS: "rows"}[info["kernel_class"]]
     tile = "x".join(str(t) for t in info["tile"])
     return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} "
             f"buf{info['lds_buffers']} lds{info['lds_bytes']} nt{info['nt_a']}{info['nt_b']} x{info['xcd_remap']} "
@@ -158,6 +163,14 @@ def main() -> int:
     stream = torch.cuda.current_stream().cuda_stream
     sel = [s for s in args.cases.split(",") if s]
     cases = [c for c in wl.CASES if not sel or any(s in c.name for s in sel)]
+    if args.problem:
+        f = args.problem.split(":")
+        dt = {v: k for k, v in wl.DTYPE_NAME.items()}[f[0]]
+        al = complex(f[3]) if len(f) > 3 else 1.0
+        be = complex(f[4]) if len(f) > 4 else 0.0
+        if dt in (wl.F32, wl.F64, wl.F32_F64, wl.F64_F32):
+            al, be = al.real, be.real
+        cases = [wl.Case(9, dt, tuple(int(x) for x in f[1].split("x")), tuple(int(x) for x in f[2]), al, be)]
     K, W = args.steps, args.warmup
     cpu = None if args.no_cpu else CpuLeg()
 
@@ -195,7 +208,16 @@ def main() -> int:
         ms_heur = None if args.no_heuristic else ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, reps)
         t0 = time.perf_counter()
         source = "search"
-        if not args.search and args.plan_cache and ttc.ttc_plan_cache_lookup(plan, args.plan_cache):
+        if args.force_class:
+            want_cls = {"direct": ttc.TTC_KERNEL_DIRECT, "lds": ttc.TTC_KERNEL_LDS, "rows": ttc.TTC_KERNEL_ROWS}[args.force_class]
+            source = "first " + args.force_class
+            for k in range(ttc.ttc_plan_candidate_count(plan)):
+                ttc.ttc_plan_select_candidate(plan, k)
+                if ttc.ttc_plan_get_info(plan)["kernel_class"] == want_cls:
+                    break
+            else:
+                raise SystemExit(f"bench.py: {c.name} has no candidate of class {args.force_class}")
+        elif not args.search and args.plan_cache and ttc.ttc_plan_cache_lookup(plan, args.plan_cache):
             source = "store"
         else:
             ttc.ttc_plan_tune_pairs(plan, a_ptrs, b_ptrs, stream, args.max_candidates)

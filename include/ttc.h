@@ -49,7 +49,8 @@ enum {
 };
 
 /* Kernel families (paper Section 3.1: the stride-1 index keeps its place, or not). */
-enum { TTC_KERNEL_DIRECT = 0 /* no staging: stride-1 index fixed */, TTC_KERNEL_LDS = 1 /* tile staged through LDS */ };
+enum { TTC_KERNEL_DIRECT = 0 /* tiles, no staging: stride-1 index fixed */, TTC_KERNEL_LDS = 1 /* tile staged through LDS */,
+       TTC_KERNEL_ROWS = 2 /* stride-1 index fixed: B walked front to back, rows gathered from A */ };
 /* Epilogues chosen from alpha, beta. */
 enum { TTC_EPI_COPY = 0 /* alpha=1, beta=0 */, TTC_EPI_SCALE = 1 /* beta=0: B never read */, TTC_EPI_AXPBY = 2 };
 

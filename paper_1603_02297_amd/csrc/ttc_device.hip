@@ -37,7 +37,7 @@ hipError_t launch_mixed_complex(const Problem& P, const Candidate& c, const void
 static hipError_t launch(const Problem& P, const Candidate& c, const void* A, void* B, hipStream_t s)
 {
     if (c.threads < kWave || c.threads > kMaxThreads || (c.threads % kWave) != 0) return hipErrorInvalidValue;
-    if (c.lds_bytes > kMaxLdsBytes) return hipErrorInvalidValue;
+    if (c.lds_bytes < 0 || c.lds_bytes > kMaxLdsBytes) return hipErrorInvalidValue;
     switch (P.dtype) {
     case TTC_F32:      return launch_f32(P, c, A, B, s);
     case TTC_F64:      return launch_f64(P, c, A, B, s);
@@ -232,12 +232,14 @@ static int tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, vo
     for (int k = 0; k < finalists; ++k) {
         const int i = timed[k].second;
         ttc::Candidate& c = plan->cands[i];
-        // the rule's streaming hints, then none, then all: keep what is fastest for this candidate
+        // the rule's streaming hints, then none, all, and one side only (the direct kernel streams both sides or
+        // neither): keep what is fastest for this candidate
         const int rule_a = c.kp.nt_a, rule_b = c.kp.nt_b;
-        const int variants[3][2] = {{rule_a, rule_b}, {0, 0}, {1, 1}};
+        const int variants[5][2] = {{rule_a, rule_b}, {0, 0}, {1, 1}, {1, 0}, {0, 1}};
+        const int nvariants = c.kernel_class == TTC_KERNEL_DIRECT ? 3 : 5;
         float cand_ms = 0.f;
         int keep_a = rule_a, keep_b = rule_b;
-        for (int v = 0; v < 3; ++v) {
+        for (int v = 0; v < nvariants; ++v) {
             if (v > 0 && variants[v][0] == rule_a && variants[v][1] == rule_b) continue;
             c.kp.nt_a = variants[v][0];
             c.kp.nt_b = variants[v][1];
@@ -253,6 +255,7 @@ static int tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, vo
         const int mapping0 = c.kp.xcd_remap;
         int keep_map = mapping0;
         for (int mode : {1, 3}) {
+            if (c.kernel_class == TTC_KERNEL_ROWS) break;           // no tiles to deal
             if (mode == mapping0 || !ttc::set_tile_mapping(&c.kp, mode)) continue;
             float ms = 0.f;
             const int st3 = time_one(c, 2, reps2, &ms);

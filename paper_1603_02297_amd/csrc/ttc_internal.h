@@ -101,6 +101,27 @@ struct KernelParams {
     Side     b;                      // store walk (B order); unused by the direct kernel
     double   alpha[2];               // re, im (im = 0 for real types)
     double   beta[2];
+    int32_t  debug_stop;             // measurement aid: 1 = every workgroup returns after its set-up
+    int32_t  pad_end;
+};
+
+// Parameters of the row kernel (stride-1 index fixed: rows are contiguous in both tensors).  B is walked in
+// the order of its multi-index, so the writes of consecutive workgroups are consecutive in memory.
+struct RowsParams {
+    int32_t  n;                      // fused number of indices; index 0 is the row
+    int32_t  vec;                    // elements per lane and access
+    int32_t  unroll;                 // accesses a lane keeps in flight
+    int32_t  straddle;               // 1: a vector may cross the end of a row or of the tensor (handled element by element)
+    uint32_t row;                    // extent of index 0
+    uint32_t chunk;                  // elements a workgroup moves: threads * unroll * vec
+    int32_t  nt_a, nt_b;             // non-temporal accesses per side
+    FastDiv  row_div;                // x / row
+    FastDiv  size_div[kMaxDim];      // extent of B's index d, d = 1 .. n-1 (entry 0 unused)
+    int64_t  stride_a[kMaxDim];      // element stride in A of B's index d
+    int64_t  stride_b[kMaxDim];      // element stride in B of B's index d
+    int64_t  elements;
+    double   alpha[2];
+    double   beta[2];
 };
 
 // One candidate launch configuration ("candidate" in the paper's Section 3).
@@ -117,7 +138,8 @@ struct Candidate {
     int      lds_conflict_a, lds_conflict_b;
     double   score;                  // heuristic cost, smaller is better
     float    tuned_ms;
-    KernelParams kp;
+    KernelParams kp;                 // box kernels (staged and direct); the streaming flags and the tile mapping of every class
+    RowsParams rows;                 // row kernel
 };
 
 // Element kinds of one tensor (the two tensors of a mixed-precision problem differ).

@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <climits>
+#include <cstdlib>
 #include <type_traits>
 
 #include "ttc_internal.h"
@@ -56,7 +58,7 @@ __device__ __forceinline__ double fused(double a, double b, double c) { return _
 // the arithmetic, in the type it runs in
 template <typename C, int MODE> struct Core {                    // C = float or double
     C al, be;
-    __device__ explicit Core(const KernelParams& p) : al((C)p.alpha[0]), be((C)p.beta[0]) {}
+    __device__ Core(const double* alpha, const double* beta) : al((C)alpha[0]), be((C)beta[0]) {}
     __device__ __forceinline__ C operator()(C a, C b) const
     {
         if (MODE == TTC_EPI_COPY) return a;
@@ -68,8 +70,8 @@ template <typename C, int MODE> struct Core {                    // C = float or
 
 template <typename Z, typename R, int MODE> struct ComplexCore {  // Z = cfloat / cdouble over R = float / double
     R ar, ai, br, bi;
-    __device__ explicit ComplexCore(const KernelParams& p)
-        : ar((R)p.alpha[0]), ai((R)p.alpha[1]), br((R)p.beta[0]), bi((R)p.beta[1]) {}
+    __device__ ComplexCore(const double* alpha, const double* beta)
+        : ar((R)alpha[0]), ai((R)alpha[1]), br((R)beta[0]), bi((R)beta[1]) {}
     __device__ __forceinline__ Z operator()(Z a, Z b) const
     {
         if (MODE == TTC_EPI_COPY) return a;
@@ -100,7 +102,7 @@ template <> struct Wider<cdouble, cfloat> { using type = cdouble; };
 template <typename TA, typename TB, int MODE> struct Epilogue {
     using C = typename Wider<TA, TB>::type;
     Core<C, MODE> core;
-    __device__ explicit Epilogue(const KernelParams& p) : core(p) {}
+    __device__ Epilogue(const double* alpha, const double* beta) : core(alpha, beta) {}
     __device__ __forceinline__ TB operator()(TA a, TB b) const
     {
         return Convert<TB, C>::go(core(Convert<C, TA>::go(a), Convert<C, TB>::go(b)));
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
     if (!DIRECT) build_tables<false>(p.b, nwave, threadIdx.x, blockDim.x, sc_b, tab_b, tabc_b);
     const LaneState LA = lane_setup<DIRECT>(p.a, lane, sc_a);
     const LaneState LB = DIRECT ? LA : lane_setup<false>(p.b, lane, sc_b);
-    const Epilogue<TA, TB, MODE> epi(p);
+    const Epilogue<TA, TB, MODE> epi(p.alpha, p.beta);
     const bool nt_a = p.nt_a != 0, nt_b = p.nt_b != 0;
     unsigned char* spare = smem + kTileShareBytes + lane * 16;      // where this lane parks what it must not keep
     const TileSeq seq = tile_sequence(p, blockIdx.x);
@@ -228,6 +230,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
     const uint32_t single_a = single_digits(p.a), single_b = DIRECT ? 0u : single_digits(p.b);
     if (!DIRECT && wave == nwave - 1 && seq.first < seq.end) publish(tile_of(seq, seq.first), 0);
     __syncthreads();
+    if (p.debug_stop) return;
 
     uint32_t parity = 0;
     for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
@@ -334,6 +337,77 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
     }
 }
 
+// ---------------------------------------------------------------------------------
+// The row kernel, for the case where the stride-1 index keeps its place and rows are contiguous in both tensors
+// (paper Section 3.1, case 1: loops around a copy of the first column).  B is walked in the order of its
+// multi-index: workgroup w moves the `chunk` elements that start at logical position w * chunk, so consecutive
+// workgroups write consecutive memory (a dense B is written front to back like a copy), and every lane gathers
+// its vectors from the rows of A.  No tiles, no LDS, no tables: a lane finds its row by one division and the
+// row's place in both tensors by one division per index.  Vectors that would cross the end of a row (rows that
+// are not a multiple of the vector) are left out of the vector pass and moved element by element afterwards.
+// ---------------------------------------------------------------------------------
+constexpr int kRowsThreads = 256;
+constexpr int kRowsUnroll = 4;
+
+template <typename TA, typename TB, int MODE, int V>
+__global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, const TA* __restrict__ A, TB* __restrict__ B)
+{
+    constexpr int U = kRowsUnroll;
+    constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
+    const Epilogue<TA, TB, MODE> epi(p.alpha, p.beta);
+    const int64_t base = (int64_t)blockIdx.x * (int64_t)p.chunk;
+    const int64_t row0_wide = base / (int64_t)p.row;                    // wave-uniform: once per workgroup
+    const uint32_t row0 = (uint32_t)row0_wide;
+    const uint32_t col0 = (uint32_t)(base - row0_wide * (int64_t)p.row);
+    const unsigned char* Ab = reinterpret_cast<const unsigned char*>(A);
+    unsigned char* Bb = reinterpret_cast<unsigned char*>(B);
+    auto run = [&](auto stream_a, auto stream_b) {
+        constexpr bool NTA = decltype(stream_a)::value, NTB = decltype(stream_b)::value;
+        Pack<TA, V> ra[U];
+        Pack<TB, V> rb[U];
+        int64_t to[U];
+        bool whole[U];
+        // a lane whose vector is not whole loads the first vector of the tensor instead (always there: rows hold at
+        // least V elements), so that no load sits in divergent control flow
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t k = ((uint32_t)u * kRowsThreads + threadIdx.x) * V;
+            const RowAccess x = rows_access(p, base, row0, col0, k, V);
+            whole[u] = x.whole;
+            to[u] = x.at.b * kScaleB;
+            ra[u] = load_pack<TA, V, NTA>(Ab, x.whole ? x.at.a * kScaleA : 0);
+            if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, V, NTB>(Bb, x.whole ? to[u] : 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!whole[u]) continue;
+            Pack<TB, V> out;
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                TB old = TB();
+                if (MODE == TTC_EPI_AXPBY) old = rb[u].v[j];
+                out.v[j] = epi(ra[u].v[j], old);
+            }
+            store_pack<TB, V, NTB>(Bb, to[u], out);
+        }
+        if (V > 1 && p.straddle) {
+            for (int u = 0; u < U; ++u) {
+                if (whole[u]) continue;
+                const uint32_t k = ((uint32_t)u * kRowsThreads + threadIdx.x) * V;
+                for (int j = 0; j < V; ++j) {
+                    const RowAccess x = rows_access(p, base, row0, col0, k + (uint32_t)j, 1);
+                    if (!x.whole) continue;                              // past the end of the tensor
+                    TB old = TB();
+                    if (MODE == TTC_EPI_AXPBY) old = B[x.at.b];
+                    B[x.at.b] = epi(A[x.at.a], old);
+                }
+            }
+        }
+    };
+    if (p.nt_a) { if (p.nt_b) run(std::true_type(), std::true_type()); else run(std::true_type(), std::false_type()); }
+    else        { if (p.nt_b) run(std::false_type(), std::true_type()); else run(std::false_type(), std::false_type()); }
+}
+
 // Compute units of the current device (256 on MI355X), asked once per process and device.
 inline int device_cus()
 {
@@ -375,6 +449,22 @@ inline hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uin
     return hipLaunchKernel(fn, dim3(grid), dim3(threads), args, (size_t)lds_bytes, stream);
 }
 
+template <typename TA, typename TB, int MODE, int V>
+inline hipError_t launch_rows_one(const Candidate& c, const void* A, void* B, hipStream_t stream)
+{
+    RowsParams rp = c.rows;
+    rp.nt_a = c.kp.nt_a;
+    rp.nt_b = c.kp.nt_b;
+    if (rp.vec != V || rp.unroll != kRowsUnroll || c.threads != kRowsThreads || rp.chunk != (uint32_t)(kRowsThreads * kRowsUnroll * V) ||
+        rp.row < (uint32_t)V || rp.elements < 1) return hipErrorInvalidValue;
+    const int64_t grid = (rp.elements + rp.chunk - 1) / rp.chunk;
+    if (grid < 1 || grid > INT32_MAX) return hipErrorInvalidValue;
+    const TA* a = static_cast<const TA*>(A);
+    TB* b = static_cast<TB*>(B);
+    void* args[] = {&rp, &a, &b};
+    return hipLaunchKernel(reinterpret_cast<const void*>(&rows_kernel<TA, TB, MODE, V>), dim3((uint32_t)grid), dim3(kRowsThreads), args, 0, stream);
+}
+
 // VMAXA / VMAXB: elements of each type in 16 bytes
 template <typename TA, typename TB, int MODE, int VMAXA, int VMAXB>
 inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
@@ -382,8 +472,16 @@ inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStre
     KernelParams kp = c.kp;
     const uint32_t grid = launch_grid(c, device_cus());
     set_grid(&kp, grid);
+    { static const bool stop = std::getenv("TTC_DEBUG_STOP") != nullptr; kp.debug_stop = stop ? 1 : 0; }
     const int va = kp.a.vec, vb = kp.b.vec;
-    constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct kernel: one width for both sides
+    constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct and row kernel: one width for both sides
+    if (c.kernel_class == TTC_KERNEL_ROWS) {
+        const int v = c.rows.vec;
+        if (v == 1) return launch_rows_one<TA, TB, MODE, 1>(c, A, B, s);
+        if (v == 2 && VD >= 2) return launch_rows_one<TA, TB, MODE, (VD >= 2 ? 2 : 1)>(c, A, B, s);
+        if (v == 4 && VD >= 4) return launch_rows_one<TA, TB, MODE, (VD >= 4 ? 4 : 1)>(c, A, B, s);
+        return hipErrorInvalidValue;
+    }
     if (c.kernel_class == TTC_KERNEL_DIRECT) {
         if (va == 1) return launch_one<TA, TB, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
         if (va == 2 && VD >= 2) return launch_one<TA, TB, MODE, (VD >= 2 ? 2 : 1), (VD >= 2 ? 2 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);

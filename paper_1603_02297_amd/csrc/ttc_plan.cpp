@@ -454,7 +454,10 @@ static LdsLayout choose_lds_layout(const Problem& P, const int* t, const int* sl
     // chain heads in layout order: the chain of index 0 first, then by index
     int heads[kMaxDim], nh = 0;
     for (int k = 0; k < P.ndim; ++k) if (t[k] > 1 && is_head[k]) heads[nh++] = k;
-    const int npad = std::max(0, std::min(nh - 1, 3));
+    // TTC_LDS_PAD=0 in the environment lays every tile out without pads (the ablation of the studies)
+    const char* pad_env = std::getenv("TTC_LDS_PAD");
+    const bool pads = !(pad_env && pad_env[0] == '0');
+    const int npad = pads ? std::max(0, std::min(nh - 1, 3)) : 0;
     // the walks' lane mappings do not depend on the LDS strides: lay the sides out once
     Side sa, sb;
     const int zero[kMaxDim] = {0, 0, 0, 0, 0, 0};
@@ -668,7 +671,6 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
         C.dtile_b[i] = i < wb.nd ? wb.d[i].tile : 0;  C.dlane_b[i] = i < wb.nd ? wb.d[i].lane : 0;
     }
     C.threads = threads;
-    C.wg_per_cu = wg_per_cu;
     const int nwave = threads / kWave;
     auto set_chunks = [&](Side* sd) {
         sd->chunk = (int)ceil_div(sd->n_iter, nwave);
@@ -682,8 +684,76 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     C.lds_bytes += tab_bytes - kp.lds_data_off;
     kp.lds_data_off = tab_bytes;
     if (C.lds_bytes > kMaxLdsBytes) return false;
+    // wg_per_cu <= 0: as many workgroups as a compute unit holds at once (LDS in granules of 1280 bytes, 32
+    // wavefronts, 16 workgroups that need a barrier), so that every workgroup is resident from the start and its
+    // set-up is paid once per slot instead of once per round
+    if (wg_per_cu <= 0) {
+        const int by_lds = (int)(kMaxLdsBytes / round_up(std::max(C.lds_bytes, 1), 1280));
+        const int by_waves = 32 / nwave;
+        wg_per_cu = std::max(1, std::min(std::min(by_lds, by_waves), nwave > 1 ? 16 : 32));
+    }
+    C.wg_per_cu = wg_per_cu;
     set_grid(&kp, launch_grid(C, 256));
     C.tuned_ms = 0.f;
+    *out = C;
+    return true;
+}
+
+// The row kernel's candidate: B walked front to back, `vec` elements per lane and access.  Needs rows that are
+// contiguous in both tensors and hold at least one vector, fewer than 2^31 rows, rows shorter than 2^30.
+static bool make_rows_candidate(const Problem& P, int vec, Candidate* out)
+{
+    if (P.perm[0] != 0 || P.stride_a[0] != 1 || P.stride_b[0] != 1) return false;
+    const int64_t row = P.size[0], rows = P.elements / P.size[0];
+    if (row < vec || row >= (int64_t(1) << 30) || rows >= (int64_t(1) << 31)) return false;
+    Candidate C;
+    std::memset(&C, 0, sizeof(C));
+    C.kernel_class = TTC_KERNEL_ROWS;
+    C.threads = 256;
+    C.wg_per_cu = 0;
+    C.lds_bytes = 0;
+    RowsParams& r = C.rows;
+    r.n = P.ndim;
+    r.vec = vec;
+    r.unroll = 4;
+    r.row = (uint32_t)row;
+    r.chunk = (uint32_t)(C.threads * r.unroll * vec);
+    r.straddle = (row % vec != 0 || P.elements % vec != 0) ? 1 : 0;
+    r.row_div = make_fastdiv((uint32_t)row);
+    r.elements = P.elements;
+    for (int d = 0; d < kMaxDim; ++d) {
+        r.size_div[d] = make_fastdiv(1);
+        r.stride_a[d] = 0;
+        r.stride_b[d] = 0;
+        if (d >= 1 && d < P.ndim) {
+            const int k = P.perm[d];                       // B's index d is A's index k
+            r.size_div[d] = make_fastdiv((uint32_t)P.size[k]);
+            r.stride_a[d] = P.stride_a[k];
+            r.stride_b[d] = P.stride_b[k];
+        }
+    }
+    r.alpha[0] = P.alpha[0]; r.alpha[1] = P.alpha[1];
+    r.beta[0] = P.beta[0];   r.beta[1] = P.beta[1];
+    // what the other kernels' fields say about this one
+    KernelParams& kp = C.kp;
+    kp.n = P.ndim;
+    kp.a.vec = vec; kp.b.vec = vec;
+    kp.lds_buffers = 1;
+    const int64_t grid = ceil_div(P.elements, r.chunk);
+    if (grid > INT32_MAX / 2) return false;
+    kp.num_tiles = (uint32_t)grid;
+    kp.grid = (uint32_t)grid;
+    for (int k = 0; k < kMaxDim; ++k) {
+        C.tile[k] = (k == 0) ? (int)row : 1;
+        C.tile_order[k] = (k < P.ndim) ? P.perm[k] : k;
+        kp.tile[k] = C.tile[k];
+        kp.tile_below[k] = kp.tile_cnt[k] = make_fastdiv(1);
+        kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
+        kp.stride_b[k] = (k < P.ndim) ? P.stride_b[k] : 0;
+    }
+    C.digits_a = C.digits_b = 1;
+    C.dtile_a[0] = C.dtile_b[0] = (int)row;
+    C.dlane_a[0] = C.dlane_b[0] = (int)std::min<int64_t>(row, (int64_t)kWave * vec);
     *out = C;
     return true;
 }
@@ -782,8 +852,32 @@ static AccessShape access_shape(const Problem& P, const Candidate& C)
     return r;
 }
 
+// The row kernel against the tiled kernels: measured on 384^3, 376^3, 374^3 (0,2,1) and 4-D to 6-D problems with
+// the stride-1 index fixed (fp32, fp64, complex64).  Long rows gathered whole are what it is good at (87-94 % of a
+// copy where the tiled kernels reach 75-90 %); short rows leave it with sub-line pieces of A that a tile spanning
+// A's next index reads as one run (53-62 % against 71-81 %).
+static double rows_cost(const Problem& P, const Candidate& C)
+{
+    const double row_bytes = (double)P.size[0] * P.eb_a;
+    auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
+    double e = -0.30;
+    e += 0.60 * oct_below(row_bytes, 512.0);                            // 576-byte rows: 94 % of a copy; 340-byte rows: 62 %
+    if (std::fmod(row_bytes, 128.0) != 0.0) e += 0.04;                  // rows that share lines with their neighbours
+    if (C.rows.straddle) e += 0.35;                                     // vectors cut by the row ends go element by element
+    const int access = C.rows.vec * std::max(P.eb_a, P.eb_b);
+    if (access >= 16) e += 0.015;                                       // 8-byte accesses measured a little ahead of 16-byte ones
+    else if (access < 8) e += 0.05;
+    // small problems: a chunk is 16 KB, and too few of them leave compute units idle (the same guard rails as for tiles)
+    const double tiles_wanted = std::min(2048.0, std::max(1.0, (double)P.elements * P.eb_a / 8192.0));
+    if (C.kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - C.kp.num_tiles) / 2048.0;
+    const double cus_wanted = std::min(256.0, std::max(1.0, (double)P.elements * P.eb_a / 4096.0));
+    if (C.kp.num_tiles < cus_wanted) e += 1.5 * (cus_wanted - C.kp.num_tiles) / 256.0;
+    return std::exp(e);
+}
+
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
+    if (C.kernel_class == TTC_KERNEL_ROWS) return rows_cost(P, C);
     // Weights fitted to timings of every candidate of 105 problems on MI355X (the benchmark workloads, 3-D and
     // 5-D problems with odd extents, a 57-case benchmark drawn by the paper's rules, power-of-two shapes): log-linear least
     // squares weighted towards the fast candidates, penalties constrained to be penalties, a small ridge term,
@@ -887,6 +981,10 @@ static bool same_config(const Candidate& x, const Candidate& y)
 // search tries the other settings on its finalists.)
 void default_streaming(const Problem& P, Candidate* c)
 {
+    if (c->kernel_class == TTC_KERNEL_ROWS) {      // B is written front to back and A's rows are read once: stream both
+        c->kp.nt_a = c->kp.nt_b = 1;
+        return;
+    }
     const AccessShape sh = access_shape(P, *c);
     c->kp.nt_a = (sh.align[0] >= 128) ? 1 : 0;
     c->kp.nt_b = (sh.align[1] >= 128) ? 1 : 0;
@@ -933,7 +1031,8 @@ static int max_vec(int eb, int64_t extent)
 
 // Launch shapes tried for every tile shape: workgroup size and workgroups per compute unit.
 struct LaunchShape { int threads, wg_per_cu; };
-static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}, {512, 8}, {64, 32}, {64, 16}};
+static const LaunchShape kLaunchShapes[] = {{256, 16}, {128, 8}, {256, 8}, {128, 16}, {256, 4}, {512, 8}, {64, 32},
+                                            {256, 0}, {128, 0}, {512, 0}};      // 0: what a compute unit holds at once
 
 // Different run-length targets often ask for the same box: each (box, vector rule, kernel family) is expanded once.
 struct ShapesSeen {
@@ -981,11 +1080,20 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
     const int norders = stride1_fixed ? 2 : 4;
     const int nshapes = quick ? 2 : (int)(sizeof(kLaunchShapes) / sizeof(kLaunchShapes[0]));
 
+    // -- the row kernel: only when the stride-1 index keeps its place (or there is one index only)
+    if (stride1_fixed) {
+        const int vwide = std::max(1, 16 / eb);
+        for (int v = vwide; v >= 1; v /= 2) {
+            Candidate c;
+            if (make_rows_candidate(P, v, &c)) add_candidate(P, out, c);
+        }
+    }
+
     // -- direct candidates: only when the stride-1 index keeps its place.  The box takes leading
     //    indices of A and of B so that both sides move a few long contiguous chunks per tile.
     if (stride1_fixed) {
         const int vfull = max_vec(eb, P.size[0]);
-        const int64_t chunk_bytes[6] = {16384, 4096, 32768, 8192, 2048, 65536};
+        const int64_t chunk_bytes[7] = {16384, 4096, 32768, 8192, 2048, 65536, 1024};
         const int vwide = std::max(1, 16 / eb);
         for (int vsel = 0; vsel < 3; ++vsel) {
             if (vsel == 1 && vfull == 1) continue;
@@ -1088,7 +1196,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
     if (verbose()) {
         const Candidate& c = plan->cands[0];
         std::fprintf(stderr, "ttc: plan dtype %d, %d fused indices, %s kernel, tile", P.dtype, P.ndim,
-                     c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : "staged");
+                     c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : (c.kernel_class == TTC_KERNEL_ROWS ? "row" : "staged"));
         for (int k = 0; k < P.ndim; ++k) std::fprintf(stderr, " %d", c.tile[k]);
         std::fprintf(stderr, ", vectors %d/%d, %d threads, %d B LDS, cost %.4f (best of %zu quick candidates)\n",
                      c.kp.a.vec, c.kp.b.vec, c.threads, c.lds_bytes, c.score, quick.size());
@@ -1310,11 +1418,64 @@ int ttc_debug_emulate_map(ttc_plan_t plan, int64_t* b_from_a)
 
 }  // extern "C"
 
+// Replay of the row kernel: every workgroup, every lane, the index code the kernel runs.
+static int emulate_rows(const ttc::Problem& P, const ttc::Candidate& C, int64_t* b_from_a)
+{
+    using namespace ttc;
+    const RowsParams& p = C.rows;
+    for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
+    if ((p.vec != 1 && p.vec != 2 && p.vec != 4) || p.unroll != 4 || C.threads != 256 ||
+        p.chunk != (uint32_t)(C.threads * p.unroll * p.vec) || p.row < (uint32_t)p.vec || p.row != (uint32_t)P.size[0] ||
+        p.elements != P.elements || P.size[0] >= (int64_t(1) << 30) || P.elements / P.size[0] >= (int64_t(1) << 31))
+        return TTC_ERR_INTERNAL;
+    auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
+        if (off < 0) return false;
+        for (int i = P.ndim - 1; i >= 0; --i) {
+            const int k = b_side ? P.perm[i] : i;
+            const int64_t c = off / stride[k];
+            if (c >= P.size[k]) return false;
+            off -= c * stride[k];
+        }
+        return off == 0;
+    };
+    // lanes without a whole vector load the first vector of each tensor
+    for (int j = 0; j < p.vec; ++j)
+        if (!inside(j, P.stride_a, false) || !inside(j, P.stride_b, true)) return TTC_ERR_INTERNAL;
+    int64_t written = 0;
+    bool bad = false;
+    auto move = [&](int64_t ea, int64_t eo) {
+        if (!inside(ea, P.stride_a, false) || !inside(eo, P.stride_b, true) || b_from_a[eo] != -1) { bad = true; return; }
+        b_from_a[eo] = ea;
+        ++written;
+    };
+    const int64_t grid = (p.elements + p.chunk - 1) / p.chunk;
+    for (int64_t wg = 0; wg < grid && !bad; ++wg) {
+        const int64_t base = wg * (int64_t)p.chunk;
+        const int64_t row0_wide = base / (int64_t)p.row;
+        const uint32_t row0 = (uint32_t)row0_wide, col0 = (uint32_t)(base - row0_wide * (int64_t)p.row);
+        for (int u = 0; u < p.unroll && !bad; ++u)
+            for (uint32_t tid = 0; tid < (uint32_t)C.threads && !bad; ++tid) {
+                const uint32_t k = ((uint32_t)u * (uint32_t)C.threads + tid) * (uint32_t)p.vec;
+                const RowAccess x = rows_access(p, base, row0, col0, k, p.vec);
+                if (x.whole) {
+                    for (int j = 0; j < p.vec; ++j) move(x.at.a + j, x.at.b + j);
+                } else if (p.vec > 1 && p.straddle) {
+                    for (int j = 0; j < p.vec; ++j) {
+                        const RowAccess y = rows_access(p, base, row0, col0, k + (uint32_t)j, 1);
+                        if (y.whole) move(y.at.a, y.at.b);
+                    }
+                }
+            }
+    }
+    return (bad || written != P.elements) ? TTC_ERR_INTERNAL : TTC_OK;
+}
+
 static int emulate_map(ttc_plan_t plan, int64_t* b_from_a)
 {
     using namespace ttc;
     const Problem& P = plan->prob;
     const Candidate& C = plan->cands[plan->selected];
+    if (C.kernel_class == TTC_KERNEL_ROWS) return emulate_rows(P, C, b_from_a);
     KernelParams p = C.kp;
     set_grid(&p, launch_grid(C, 256));
     const int32_t eba = P.eb_a, ebb = P.eb_b;

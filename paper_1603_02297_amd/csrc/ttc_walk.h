@@ -31,6 +31,43 @@ TTC_HD uint32_t fdigit(uint32_t x, const FastDiv& below, const FastDiv& cnt)
     return q - fdiv(q, cnt) * cnt.div;
 }
 
+// ---- row kernel: where a logical element of B (position in the order of B's multi-index) lies ----------
+// `row_index` counts rows in B's order (all indices but the first), `col` is the position inside the row.
+struct RowPlace { int64_t a, b; };
+
+TTC_HD RowPlace rows_place(const RowsParams& p, uint32_t row_index, uint32_t col)
+{
+    RowPlace r;
+    r.a = col; r.b = col;
+    uint32_t rest = row_index;
+#pragma unroll
+    for (int d = 1; d < kMaxDim; ++d) {             // unused indices: extent 1, stride 0
+        const uint32_t q = fdiv(rest, p.size_div[d]);
+        const uint32_t j = rest - q * p.size_div[d].div;
+        r.a += (int64_t)j * p.stride_a[d];
+        r.b += (int64_t)j * p.stride_b[d];
+        rest = q;
+    }
+    return r;
+}
+
+// One access of the row kernel: `k` is the offset of its first element inside the workgroup's chunk, which
+// starts at logical element `base` = row `row0`, column `col0`; `v` elements wide.  whole: all v elements lie
+// in one row and inside the tensor.  (col0 + k stays far below 2^31: rows are shorter than 2^30 elements and
+// a chunk holds at most 2^20.)
+struct RowAccess { RowPlace at; bool whole; };
+
+TTC_HD RowAccess rows_access(const RowsParams& p, int64_t base, uint32_t row0, uint32_t col0, uint32_t k, int v)
+{
+    const uint32_t x = col0 + k;
+    const uint32_t rl = fdiv(x, p.row_div);
+    const uint32_t c = x - rl * p.row;
+    RowAccess r;
+    r.at = rows_place(p, row0 + rl, c);
+    r.whole = (base + (int64_t)k + v <= p.elements) && (c + (uint32_t)v <= p.row);
+    return r;
+}
+
 // ---- which tiles a workgroup walks ---------------------------------------------------------
 // Consecutive workgroup ids land on consecutive XCDs (8 of them, each with its own L2).  Every
 // XCD owns one contiguous range of tile ids; its workgroups take the tiles of that range round

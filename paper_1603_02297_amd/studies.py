@@ -1,7 +1,8 @@
-"""Two measurement studies on the GPU, modelled on the paper's evaluation (Sections 4 and 6).
+"""Measurement studies on the GPU, modelled on the paper's evaluation (Sections 4 and 6), and the fit of the ranking model.
 
     python -m paper_1603_02297_amd.studies search  [--out FILE]     search-space reduction
     python -m paper_1603_02297_amd.studies sweep   [--out FILE]     57-case benchmark, classes, ablations
+    python -m paper_1603_02297_amd.studies fit DUMP [DUMP ...]      weights of the ranking model from --dump files (no GPU)
 
 search: how close the first 1 / 10 / 100 / 200 candidates of the ranked list come to the best
 of all candidates (the paper reports 94.58 / 97.35 / 99.10 % for 1 / 10 / 100 on its CPUs).
@@ -14,7 +15,11 @@ shrinking), fp32, about 200 MiB per tensor.  The paper's own list is not publish
 so the permutations are drawn here from a fixed seed.  Reported per class (stride-1 / inverse /
 general), with the gain of each search dimension (tile shape, vector width, tile order, LDS
 buffering, launch shape) measured as in the paper's Figure 6: best candidate overall over the
-best candidate with that dimension held at its default.
+best candidate with that dimension held at its default; and the gain of the pads in the LDS
+tile: the best configuration laid out again without pads (TTC_LDS_PAD=0) and timed.
+
+Results are checked elsewhere: tests/test_gpu_sweep_shapes.py runs these very shapes (same generator,
+host-drawn seeded values) against the CPU oracle; nothing in this package touches the oracle.
 
 Everything is timed with HIP events through the library's own helpers; tensors hold uniform
 random values; buffer pairs rotate so that the last-level cache cannot hold the working set.
@@ -180,6 +185,32 @@ def study_search(out, dump=None):
 
 
 # ---- study 2: the 57-case benchmark, classes and ablations ------------------------------------------
+def unpadded_ms(dtype, sizes, perm, alpha, beta, best_info, a_ptrs, b_ptrs, stream, tmp):
+    """Time of the configuration `best_info` names when its LDS tile is laid out without pads, or None."""
+    import os
+    if best_info["kernel_class"] == ttc.TTC_KERNEL_DIRECT:
+        return None
+    plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+    ttc.ttc_plan_select_candidate(plan, best_info["candidate_index"])
+    ttc.ttc_plan_set_streaming(plan, best_info["nt_a"], best_info["nt_b"])
+    ttc.ttc_plan_set_tile_mapping(plan, best_info["xcd_remap"])
+    open(tmp, "w").close()
+    ttc.ttc_plan_cache_store(plan, tmp)
+    ttc.ttc_plan_destroy(plan)
+    os.environ["TTC_LDS_PAD"] = "0"
+    try:
+        plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+        if not ttc.ttc_plan_cache_lookup(plan, tmp):
+            ttc.ttc_plan_destroy(plan)
+            return None
+        info = ttc.ttc_plan_get_info(plan)
+        ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
+        ttc.ttc_plan_destroy(plan)
+    finally:
+        del os.environ["TTC_LDS_PAD"]
+    return ms, info
+
+
 def ablations(rows):
     """Gain of searching each dimension: best time with the dimension at its default / best time overall."""
     ms = np.array([r[1] for r in rows])
@@ -203,8 +234,10 @@ def ablations(rows):
 def study_sweep(out, limit=None, dump=None):
     import torch
     stream = torch.cuda.current_stream().cuda_stream
+    import tempfile
     bufs = Buffers()
     results = []
+    tmp_store = tempfile.NamedTemporaryFile(prefix="ttc_sweep_", suffix=".txt", delete=False).name
     cases = [(perm, cls, cfg) for perm, cls in benchmark_permutations() for cfg in (0, 1, 2)]
     if limit:
         cases = cases[:limit]
@@ -217,9 +250,14 @@ def study_sweep(out, limit=None, dump=None):
         rows = retime_best(plan, time_candidates(plan, a_ptrs, b_ptrs, stream), a_ptrs, b_ptrs, stream)
         ttc.ttc_plan_select_candidate(plan, 0)
         heur_ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
-        ttc.ttc_plan_destroy(plan)
         ms = np.array([r[1] for r in rows])
         k = int(ms.argmin())
+        ttc.ttc_plan_select_candidate(plan, rows[k][0]["candidate_index"])
+        ttc.ttc_plan_set_streaming(plan, rows[k][0]["nt_a"], rows[k][0]["nt_b"])
+        ttc.ttc_plan_set_tile_mapping(plan, rows[k][0]["xcd_remap"])
+        best_again = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)     # timed next to its unpadded twin
+        ttc.ttc_plan_destroy(plan)
+        nopad = unpadded_ms(wl.F32, sizes, perm, 1.0, 0.0, rows[k][0], a_ptrs, b_ptrs, stream, tmp_store)
         nbytes = rows[0][0]["bytes_moved"]
         if dump is not None:
             name = f"sweep-{len(perm)}d-{cls}-cfg{cfg}-p{''.join(map(str, perm))}"
@@ -227,6 +265,9 @@ def study_sweep(out, limit=None, dump=None):
         res = {"perm": perm, "class": cls, "cfg": cfg, "sizes": sizes, "copy": copy,
                "best": nbytes / ms[k] / 1e6, "heur": nbytes / heur_ms / 1e6, "info": rows[k][0],
                "abl": ablations(rows), "cands": len(rows)}
+        res["abl"]["LDS pads"] = (nopad[0] / best_again) if nopad else float("nan")
+        res["conflict"] = (rows[k][0]["lds_conflict_a"], rows[k][0]["lds_conflict_b"],
+                           nopad[1]["lds_conflict_a"] if nopad else 0, nopad[1]["lds_conflict_b"] if nopad else 0)
         results.append(res)
         log(f"{len(perm)}-D {cls:9s} cfg{cfg} {sizes} p{perm}: best {res['best']:.0f} GB/s = "
             f"{100 * res['best'] / copy:.1f}% of copy, heuristic {res['heur']:.0f}")
@@ -252,26 +293,177 @@ def study_sweep(out, limit=None, dump=None):
     print("dimension       default held                                   mean gain  max gain", file=out)
     held = {"tile shape": "tile of the heuristic's first candidate", "vector width": "one element per lane",
             "tile order": "tiles numbered in B's index order", "LDS buffering": "two tile buffers",
-            "launch shape": "256 threads, 16 workgroups per CU"}
+            "launch shape": "256 threads, 16 workgroups per CU",
+            "LDS pads": "the best configuration with an unpadded LDS tile"}
     for name in held:
         g = [r["abl"][name] - 1.0 for r in results if r["abl"][name] == r["abl"][name]]
         if g:
             print(f"{name:14s}  {held[name]:45s}  {100 * statistics.mean(g):+8.1f}%  {100 * max(g):+7.1f}%", file=out)
 
 
+# ---- study 3: fitting the ranking model ------------------------------------------------------------
+FREE_SIGN = {"alA*A<256", "alA*A<1K", "tile>16K", "tile>32K", "t128", "t512", "wg4", "wg8", "ordA", "ordMix", "direct",
+             "nbuf1", "nt", "conf", "partB", "b*nbuf1", "b*t128"}
+
+
+def fit_features(r):
+    """Features of one timed candidate (a row of a --dump file: ttc_plan_get_info plus its time).  They mirror the
+    terms of heuristic_cost() in csrc/ttc_plan.cpp: contiguous run and per-instruction piece per side (octaves below
+    1 KB / 256 B / 64 B), how much of a 128-byte line a run shares with its neighbours, extra line and 64-byte write
+    requests, tile size, occupancy, idle lanes, vector width, remainder tiles, launch shape, tile order, streaming."""
+    eba, ebb = wl.ELEM_BYTES[r["dtype"]], wl.ELEM_BYTES_B[r["dtype"]]
+    n, sizes, tile = r["ndim"], r["sizes"], r["tile"]
+    vol = float(np.prod(tile[:n]))
+    tb = vol * eba
+    direct = r["kernel_class"] == ttc.TTC_KERNEL_DIRECT
+    ra, rb, sa, sb, aa, ab = (r[k] for k in ("run_bytes_a", "run_bytes_b", "seg_bytes_a", "seg_bytes_b", "align_a", "align_b"))
+
+    def idle(dt, dl, vec, nd):
+        it = 1
+        for t_, l_ in zip(dt[:nd], dl[:nd]):
+            it *= -(-t_ // l_)
+        return it * 64 * vec / vol - 1.0
+
+    la = idle(r["digit_tile_a"], r["digit_lane_a"], r["vec_a"], r["digits_a"])
+    lb = 0.0 if direct else idle(r["digit_tile_b"], r["digit_lane_b"], r["vec_b"], r["digits_b"])
+    wv = r["threads"] // 64
+    waves = min(32, (160 * 1024 // max(r["lds_bytes"], 1)) * wv) if not direct else 32
+    wgs = min(16, 160 * 1024 // max(r["lds_bytes"], 1))
+    pad = 1.0
+    for k in range(n):
+        pad *= (-(-sizes[k] // tile[k]) * tile[k]) / sizes[k]
+    vb = r["vec_b"] if not direct else r["vec_a"]
+    lg = lambda x: float(np.log2(x))
+    order, perm = r["tile_order"][:n], r["perm"][:n]
+    okind = 0 if order == perm else (1 if order == list(range(n)) else 2)
+    f = {
+        "A<1K": max(0, lg(1024 / ra)), "B<1K": max(0, lg(1024 / rb)), "A<256": max(0, lg(256 / ra)), "B<256": max(0, lg(256 / rb)),
+        "A<64": max(0, lg(64 / ra)), "B<64": max(0, lg(64 / rb)),
+        "Aun": (1 - aa / 128) * 128 / ra, "Bun": (1 - ab / 128) * 128 / rb,
+        "sA<256": max(0, lg(256 / sa)), "sB<256": max(0, lg(256 / sb)), "sA<64": max(0, lg(64 / sa)), "sB<64": max(0, lg(64 / sb)),
+        "tile<8K": max(0, lg(8192 / tb)), "tile>16K": max(0, lg(tb / 16384)), "tile>32K": max(0, lg(tb / 32768)),
+        "occ": max(0, 16 - waves) / 16, "occ8": max(0, 8 - waves) / 8, "wgs<4": max(0, 4 - wgs) / 4, "laneA": la, "laneB": lb,
+        "conf": 0 if direct else (r["lds_conflict_a"] + r["lds_conflict_b"] - 4),
+        "vbytesA<16": float(r["vec_a"] * eba < 16), "vbytesB<16": float(vb * ebb < 16),
+        "vbytesA<8": float(r["vec_a"] * eba < 8), "vbytesB<8": float(vb * ebb < 8),
+        "partA": float(r["partial_a"]), "partB": float(r["partial_b"]), "pad": pad - 1,
+        "t128": float(r["threads"] == 128), "t512": float(r["threads"] == 512),
+        "wg4": float(r["wg_per_cu"] == 4), "wg8": float(r["wg_per_cu"] == 8),
+        "ordA": float(okind == 1), "ordMix": float(okind == 2), "direct": float(direct),
+        "few": max(0, (2048 - r["num_tiles"]) / 2048), "nbuf1": float((not direct) and r["lds_buffers"] == 1),
+        "dirun": float(direct) * ((1 - aa / 128) * 128 / sa + (1 - ab / 128) * 128 / sb),
+    }
+    beta = float(r["epilogue"] == ttc.TTC_EPI_AXPBY)
+    req_a = ((ra + 128 - min(aa, 128)) / 128) * 128 / ra - 1
+    req_b = ((rb + 64 - min(ab, 64)) / 64) * 64 / rb - 1
+    f.update({"reqA": req_a, "reqB": req_b, "b*B<256": beta * f["B<256"], "b*Bun": beta * f["Bun"], "b*reqB": beta * req_b,
+              "oA*Bun": f["ordA"] * f["Bun"], "oA*reqB": f["ordA"] * req_b, "oM*Bun": f["ordMix"] * f["Bun"],
+              "alB*B<1K": float(ab >= 128) * max(0, lg(1024 / rb)), "alB*B<2K": float(ab >= 128) * max(0, lg(2048 / rb)),
+              "alA*A<256": float(aa >= 128) * max(0, lg(256 / ra)), "alA*A<1K": float(aa >= 128) * max(0, lg(1024 / ra)),
+              "nt": float(r["nt_a"] + r["nt_b"]) / 2, "b*nbuf1": beta * f["nbuf1"], "b*t128": beta * f["t128"]})
+    return f
+
+
+def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
+    """Weights of heuristic_cost() from per-candidate timings (the --dump files of `search` and `sweep`).
+
+    Model: log(time / best time of the problem) = sum_k w_k * feature_k + one free intercept per problem.
+    Objective: least squares, each row weighted by exp(-sharpness * log-slowdown) so that the fast candidates, whose
+    order matters, count most; a ridge term keeps collinear features apart.  Constraints: every weight that prices
+    a loss (short runs, shared lines, idle lanes, ...) is >= 0; only the preferences in FREE_SIGN may take either
+    sign.  Checked by cross-validation over whole problems: how close the first 1 / 10 / 100 / 200 candidates of the
+    predicted order come to the best candidate of problems the fit has not seen.  Row kernels and workgroup shapes
+    the model has no term for are left out of the fit.  The printed weights are rounded by hand into the source,
+    where guard rails outside the measured range (runs under 64 bytes, small problems) are added."""
+    import gzip
+    from scipy.optimize import lsq_linear
+    data = []
+    for path in dumps:
+        with (gzip.open(path, "rt") if path.endswith(".gz") else open(path)) as fh:
+            for line in fh:
+                d = json.loads(line)
+                d["rows"] = [r for r in d["rows"] if r["kernel_class"] != ttc.TTC_KERNEL_ROWS]
+                if d["rows"]:
+                    data.append(d)
+    names, X, y, grp = None, [], [], []
+    for d in data:
+        best = min(r["ms"] for r in d["rows"])
+        for r in d["rows"]:
+            f = fit_features(r)
+            names = names or list(f)
+            X.append([f[k] for k in names])
+            y.append(np.log(r["ms"] / best))
+            grp.append(d["problem"])
+    X, y = np.array(X), np.array(y)
+    cases = sorted(set(grp))
+    index = {c: i for i, c in enumerate(cases)}
+    G = np.zeros((len(grp), len(cases)))
+    G[np.arange(len(grp)), [index[g] for g in grp]] = 1
+    wts = np.exp(-sharpness * y)
+    lo = np.array([(-np.inf if k in FREE_SIGN else 0.0) for k in names] + [-np.inf] * len(cases))
+    hi = np.full(len(lo), np.inf)
+    full = np.hstack([X, G]) * wts[:, None]
+
+    def solve(Am, ym):
+        keep = np.abs(Am).sum(0) > 0
+        x = np.zeros(Am.shape[1])
+        nk = int(keep.sum())
+        aug = np.vstack([Am[:, keep], ridge * np.eye(nk)])
+        x[keep] = lsq_linear(aug, np.concatenate([ym, np.zeros(nk)]), bounds=(lo[keep], hi[keep]), method="trf",
+                             lsq_solver="exact").x
+        return x
+
+    coef = solve(full, y * wts)
+    print(f"# {len(data)} problems, {len(y)} timed candidates, {len(names)} features", file=out)
+    print("feature        weight", file=out)
+    for k, c in zip(names, coef):
+        print(f"{k:12s}  {c:+.4f}", file=out)
+    starts = np.cumsum([0] + [len(d["rows"]) for d in data])
+    caps = (1, 10, 100, 200)
+    q = [None] * len(data)
+    for fold in range(folds):
+        m = np.ones(len(y), bool)
+        held = [j for j in range(len(data)) if j % folds == fold]
+        for j in held:
+            m[starts[j]:starts[j + 1]] = False
+        cf = solve(full[m], (y * wts)[m])
+        for j in held:
+            pr = X[starts[j]:starts[j + 1]] @ cf[:len(names)]
+            ms = np.array([r["ms"] for r in data[j]["rows"]])
+            order = np.argsort(pr, kind="stable")
+            q[j] = [ms.min() / ms[order[:k]].min() for k in caps] + [ms.min() / ms[:k].min() for k in caps]
+    q = np.array(q)
+    print("", file=out)
+    print("cross-validation over whole problems: best time / best time among the first k candidates", file=out)
+    print("                        " + "  ".join(f"first {k:>3}" for k in caps), file=out)
+    print("refitted order, mean    " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, :4].mean(0)), file=out)
+    print("refitted order, minimum " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, :4].min(0)), file=out)
+    print("order in the dump, mean " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, 4:].mean(0)), file=out)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("study", choices=("search", "sweep"))
+    ap.add_argument("study", choices=("search", "sweep", "fit"))
+    ap.add_argument("dumps", nargs="*", help="fit: the --dump files of earlier search / sweep runs")
     ap.add_argument("--out", default="", help="write the table to this file (default: stdout)")
     ap.add_argument("--limit", type=int, default=0, help="sweep: only the first LIMIT cases")
     ap.add_argument("--dump", default="", help="also write every candidate's configuration and time (JSON lines; .gz compresses)")
     args = ap.parse_args(argv)
+    out = open(args.out, "w") if args.out else sys.stdout
+    if args.study == "fit":                      # host only: no GPU, no library call
+        if not args.dumps:
+            print("studies fit: name at least one --dump file", file=sys.stderr)
+            return 2
+        print("# python -m paper_1603_02297_amd.studies fit " + " ".join(args.dumps), file=out)
+        study_fit(out, args.dumps)
+        if args.out:
+            out.close()
+        return 0
     import torch
     if not torch.cuda.is_available():
         print("studies: no GPU visible", file=sys.stderr)
         return 2
     ttc.lib()
-    out = open(args.out, "w") if args.out else sys.stdout
     t0 = time.time()
     print(f"# python -m paper_1603_02297_amd.studies {args.study}" + (f" --limit {args.limit}" if args.limit else ""), file=out)
     dump = None

@@ -4,6 +4,7 @@ Bar: bit-exact for alpha=1, beta=0 (a pure permutation); at most 1 ulp otherwise
 follow one evaluation order with the same fused multiply-adds, so 0 is what is expected).
 """
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -33,7 +34,10 @@ def ulp_distance(x: np.ndarray, y: np.ndarray) -> int:
     return int(np.abs(xi - yi).max())
 
 
-def gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate=None, tune=False):
+STORE = os.path.join(os.path.dirname(os.path.abspath(ttc.__file__)), "plans", "gfx950_suite.txt")
+
+
+def gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate=None, tune=False, store=None):
     """One ttc_execute on the GPU; returns the resulting B as a numpy array."""
     dev = torch.device("cuda:0")
     dA = torch.from_numpy(A).to(dev)
@@ -42,6 +46,8 @@ def gpu_run(dtype, sizes, perm, alpha, beta, A, B0, candidate=None, tune=False):
     try:
         if candidate is not None:       # the list depends on whether beta is 0: wrap
             ttc.ttc_plan_select_candidate(plan, candidate % ttc.ttc_plan_candidate_count(plan))
+        if store is not None:
+            assert ttc.ttc_plan_cache_lookup(plan, store), f"{store} holds no usable plan for {sizes} {perm}"
         if tune:
             scratch = torch.empty_like(dB)
             ttc.ttc_plan_tune(plan, dA.data_ptr(), scratch.data_ptr(), torch.cuda.current_stream().cuda_stream, 0)
@@ -192,12 +198,34 @@ def test_non_default_stream():
 
 @pytest.mark.parametrize("case", wl.CASES, ids=[c.name for c in wl.CASES])
 def test_benchmark_cases_full_size(case):
-    """The 15 headline cases at full size, in the launch configuration the benchmark times
-    (the tuned plan), every element compared."""
+    """The 15 headline cases at full size, every element compared: the heuristic's plan, a plan searched
+    here, and the plan of the tracked store -- the launch configuration bench.py times and profiles/ describe."""
     A, B0 = wl.case_inputs(case)
     want = oracle.transpose(case.dtype, case.sizes, case.perm, case.alpha, case.beta, A, B0.copy(), 16)
-    for tune in (False, True):
-        got, info = gpu_run(case.dtype, case.sizes, case.perm, case.alpha, case.beta, A, B0, tune=tune)
+    for how in ({}, {"tune": True}, {"store": STORE}):
+        got, info = gpu_run(case.dtype, case.sizes, case.perm, case.alpha, case.beta, A, B0, **how)
         pure = (complex(case.alpha) == 1 and complex(case.beta) == 0)
         d = ulp_distance(got, want)
-        assert d <= (0 if pure else 1), (case.name, tune, d, info)
+        assert d <= (0 if pure else 1), (case.name, how, d, info)
+
+
+# The weakest shapes of the 57-case benchmark built by the rules of the paper's Section 4.1 (about 200 MiB,
+# extents that are multiples of nothing): runs share cache lines with their neighbours and every vector is cut.
+ODD_BENCHMARK_SHAPES = [
+    ((7241, 7241), (1, 0)),
+    ((85, 85, 85, 85), (3, 2, 1, 0)),
+    ((35, 35, 35, 35, 35), (4, 3, 2, 1, 0)),
+    ((19, 19, 19, 19, 19, 19), (5, 4, 3, 2, 1, 0)),
+]
+
+
+@pytest.mark.parametrize("sizes,perm", ODD_BENCHMARK_SHAPES, ids=["x".join(map(str, s)) for s, _ in ODD_BENCHMARK_SHAPES])
+def test_odd_benchmark_shapes_full_size(sizes, perm):
+    """Inverse permutations of odd extents at benchmark size, heuristic and searched plan, bit-exact."""
+    n = int(np.prod(sizes))
+    A = wl.uniform_tensor(wl.F32, n, 5700 + len(sizes))
+    B0 = wl.uniform_tensor(wl.F32, n, 5800 + len(sizes))
+    want = oracle.transpose(wl.F32, sizes, perm, 1.0, 0.0, A, B0.copy(), 16)
+    for tune in (False, True):
+        got, info = gpu_run(wl.F32, sizes, perm, 1.0, 0.0, A, B0, tune=tune)
+        assert np.array_equal(got, want), (sizes, perm, tune, info)
