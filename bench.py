@@ -123,7 +123,7 @@ def plan_text(info, ttc) -> str:
     """The selected configuration in one short string (the fields that name it in the plan store and the profiles)."""
     cls = {ttc.TTC_KERNEL_DIRECT: "direct", ttc.TTC_KERNEL_LDS: "lds", ttc.TTC_KERNEL_ROWS: "rows"}[info["kernel_class"]]
     tile = "x".join(str(t) for t in info["tile"])
-    return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} "
+    return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} u{info['unroll']} "
             f"buf{info['lds_buffers']} lds{info['lds_bytes']} nt{info['nt_a']}{info['nt_b']} x{info['xcd_remap']} "
             f"cf{info['lds_conflict_a']}/{info['lds_conflict_b']} cand{info['candidate_index']}/{info['candidate_count']}")
 

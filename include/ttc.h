@@ -80,7 +80,8 @@ typedef struct {
     int     partial_a, partial_b;          /* 1: runs are not a multiple of the vector: the last vector of a run is moved
                                               back to end with the run and overlaps its neighbour */
     int     threads;                       /* workgroup size */
-    int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles */
+    int     wg_per_cu;                     /* workgroups launched per compute unit; each walks several tiles (row kernel: 0,
+                                              its workgroups move one chunk each) */
     int     xcd_remap;                     /* tiles -> XCDs: 0 round robin, 1 a contiguous range each, k >= 2: chunks of 2^k tiles in turn */
     int     lds_bytes;                     /* dynamic LDS per workgroup: position tables + tile buffer(s) */
     int     lds_buffers;                   /* 2: tile buffers alternate (one barrier per tile), 1: one buffer (two barriers) */
@@ -101,6 +102,7 @@ typedef struct {
                                               then all of them: candidate 0 as created, the others by heuristic cost */
     float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
     double  heuristic_cost;                /* the ranking key: modelled relative cost, smaller is better */
+    int     unroll;                        /* row kernel: vectors a lane keeps in flight (1, 2, 4 or 8); 0 for the tile kernels */
 } ttc_plan_info_t;
 
 /*

@@ -4,9 +4,9 @@
 // text per problem in a file the caller names.
 //
 // Line format (all integers, blank separated):
-//   ttc3 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
+//   ttc4 gfx950 <dtype> <beta_is_zero> <ndim> <sizes..> <perm..> <stride_a..> <stride_b..> |
 //   <kernel_class> <threads> <wg_per_cu> <lds_buffers> <vec_a> <vec_b> <tile x6> <tile_order x6>
-//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> | <nt_a> <nt_b> <tile mapping> <microseconds>
+//   <digits_a> <dtile_a x4> <dlane_a x4> <digits_b> <dtile_b x4> <dlane_b x4> <row kernel's unroll> | <nt_a> <nt_b> <tile mapping> <microseconds>
 // The left part is the key: the fused problem as the planner sees it.  The middle part names a
 // candidate by its configuration, not by its rank, so an entry survives changes of the ranking;
 // if no candidate of the current library matches, the entry is ignored.  Later lines win.
@@ -21,7 +21,7 @@
 
 namespace ttc {
 
-static const char* kMagic = "ttc3";
+static const char* kMagic = "ttc4";
 static const char* kArch = "gfx950";
 
 static std::string problem_key(const Problem& P)
@@ -48,6 +48,7 @@ static std::vector<long long> config_signature(const Candidate& c)
     v.push_back(c.digits_b);
     for (int i = 0; i < kBoxDims; ++i) v.push_back(c.dtile_b[i]);
     for (int i = 0; i < kBoxDims; ++i) v.push_back(c.dlane_b[i]);
+    v.push_back(c.rows.unroll);
     return v;
 }
 

@@ -111,15 +111,17 @@ struct RowsParams {
     int32_t  n;                      // fused number of indices; index 0 is the row
     int32_t  vec;                    // elements per lane and access
     int32_t  unroll;                 // accesses a lane keeps in flight
-    int32_t  straddle;               // 1: a vector may cross the end of a row or of the tensor (handled element by element)
+    int32_t  overlap;                // 1: rows are not a multiple of vec: the last vector of a row is moved back to end with it
     uint32_t row;                    // extent of index 0
-    uint32_t chunk;                  // elements a workgroup moves: threads * unroll * vec
+    uint32_t slots;                  // vectors per row: ceil(row / vec)
+    uint32_t chunk;                  // vectors a workgroup moves: threads * unroll
     int32_t  nt_a, nt_b;             // non-temporal accesses per side
-    FastDiv  row_div;                // x / row
+    int32_t  pad;
+    FastDiv  slot_div;               // x / slots
     FastDiv  size_div[kMaxDim];      // extent of B's index d, d = 1 .. n-1 (entry 0 unused)
     int64_t  stride_a[kMaxDim];      // element stride in A of B's index d
     int64_t  stride_b[kMaxDim];      // element stride in B of B's index d
-    int64_t  elements;
+    int64_t  vectors;                // rows * slots
     double   alpha[2];
     double   beta[2];
 };

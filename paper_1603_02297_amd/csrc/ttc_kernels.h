@@ -340,25 +340,24 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
 // ---------------------------------------------------------------------------------
 // The row kernel, for the case where the stride-1 index keeps its place and rows are contiguous in both tensors
 // (paper Section 3.1, case 1: loops around a copy of the first column).  B is walked in the order of its
-// multi-index: workgroup w moves the `chunk` elements that start at logical position w * chunk, so consecutive
+// multi-index: workgroup w moves the `chunk` vectors that start at vector w * chunk, so consecutive
 // workgroups write consecutive memory (a dense B is written front to back like a copy), and every lane gathers
 // its vectors from the rows of A.  No tiles, no LDS, no tables: a lane finds its row by one division and the
-// row's place in both tensors by one division per index.  Vectors that would cross the end of a row (rows that
-// are not a multiple of the vector) are left out of the vector pass and moved element by element afterwards.
+// row's place in both tensors by one division per index.  Where rows are not a multiple of the vector, the last
+// vector of a row is moved back to end with the row and repeats up to V-1 elements of its neighbour with the same
+// values (only where B is not read: with beta != 0 the planner picks a vector that divides the row).
 // ---------------------------------------------------------------------------------
 constexpr int kRowsThreads = 256;
-constexpr int kRowsUnroll = 4;
 
-template <typename TA, typename TB, int MODE, int V>
+template <typename TA, typename TB, int MODE, int V, int U>
 __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, const TA* __restrict__ A, TB* __restrict__ B)
 {
-    constexpr int U = kRowsUnroll;
     constexpr int32_t kScaleA = (int32_t)sizeof(TA), kScaleB = (int32_t)sizeof(TB);
     const Epilogue<TA, TB, MODE> epi(p.alpha, p.beta);
     const int64_t base = (int64_t)blockIdx.x * (int64_t)p.chunk;
-    const int64_t row0_wide = base / (int64_t)p.row;                    // wave-uniform: once per workgroup
+    const int64_t row0_wide = base / (int64_t)p.slots;                  // wave-uniform: once per workgroup
     const uint32_t row0 = (uint32_t)row0_wide;
-    const uint32_t col0 = (uint32_t)(base - row0_wide * (int64_t)p.row);
+    const uint32_t slot0 = (uint32_t)(base - row0_wide * (int64_t)p.slots);
     const unsigned char* Ab = reinterpret_cast<const unsigned char*>(A);
     unsigned char* Bb = reinterpret_cast<unsigned char*>(B);
     auto run = [&](auto stream_a, auto stream_b) {
@@ -366,21 +365,20 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
         Pack<TA, V> ra[U];
         Pack<TB, V> rb[U];
         int64_t to[U];
-        bool whole[U];
-        // a lane whose vector is not whole loads the first vector of the tensor instead (always there: rows hold at
-        // least V elements), so that no load sits in divergent control flow
+        bool valid[U];
+        // a lane past the end of the tensor loads the first vector instead and stores nothing, so that no load
+        // sits in divergent control flow
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t k = ((uint32_t)u * kRowsThreads + threadIdx.x) * V;
-            const RowAccess x = rows_access(p, base, row0, col0, k, V);
-            whole[u] = x.whole;
+            const RowAccess x = rows_access(p, base, row0, slot0, (uint32_t)u * kRowsThreads + threadIdx.x);
+            valid[u] = x.valid;
             to[u] = x.at.b * kScaleB;
-            ra[u] = load_pack<TA, V, NTA>(Ab, x.whole ? x.at.a * kScaleA : 0);
-            if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, V, NTB>(Bb, x.whole ? to[u] : 0);
+            ra[u] = load_pack<TA, V, NTA>(Ab, x.at.a * kScaleA);
+            if (MODE == TTC_EPI_AXPBY) rb[u] = load_pack<TB, V, NTB>(Bb, to[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (!whole[u]) continue;
+            if (!valid[u]) continue;
             Pack<TB, V> out;
 #pragma unroll
             for (int j = 0; j < V; ++j) {
@@ -389,19 +387,6 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
                 out.v[j] = epi(ra[u].v[j], old);
             }
             store_pack<TB, V, NTB>(Bb, to[u], out);
-        }
-        if (V > 1 && p.straddle) {
-            for (int u = 0; u < U; ++u) {
-                if (whole[u]) continue;
-                const uint32_t k = ((uint32_t)u * kRowsThreads + threadIdx.x) * V;
-                for (int j = 0; j < V; ++j) {
-                    const RowAccess x = rows_access(p, base, row0, col0, k + (uint32_t)j, 1);
-                    if (!x.whole) continue;                              // past the end of the tensor
-                    TB old = TB();
-                    if (MODE == TTC_EPI_AXPBY) old = B[x.at.b];
-                    B[x.at.b] = epi(A[x.at.a], old);
-                }
-            }
         }
     };
     if (p.nt_a) { if (p.nt_b) run(std::true_type(), std::true_type()); else run(std::true_type(), std::false_type()); }
@@ -449,31 +434,38 @@ inline hipError_t launch_one(const KernelParams& kp, const void* A, void* B, uin
     return hipLaunchKernel(fn, dim3(grid), dim3(threads), args, (size_t)lds_bytes, stream);
 }
 
-template <typename TA, typename TB, int MODE, int V>
-inline hipError_t launch_rows_one(const Candidate& c, const void* A, void* B, hipStream_t stream)
+template <typename TA, typename TB, int MODE, int V, int U>
+inline hipError_t launch_rows_unrolled(const Candidate& c, const void* A, void* B, hipStream_t stream)
 {
     RowsParams rp = c.rows;
     rp.nt_a = c.kp.nt_a;
     rp.nt_b = c.kp.nt_b;
-    if (rp.vec != V || rp.unroll != kRowsUnroll || c.threads != kRowsThreads || rp.chunk != (uint32_t)(kRowsThreads * kRowsUnroll * V) ||
-        rp.row < (uint32_t)V || rp.elements < 1) return hipErrorInvalidValue;
-    const int64_t grid = (rp.elements + rp.chunk - 1) / rp.chunk;
+    if (rp.vec != V || rp.unroll != U || c.threads != kRowsThreads || rp.chunk != (uint32_t)(kRowsThreads * U) ||
+        rp.row < (uint32_t)V || rp.slots != (rp.row + V - 1) / V || rp.vectors < 1 || (MODE == TTC_EPI_AXPBY && rp.overlap)) return hipErrorInvalidValue;
+    const int64_t grid = (rp.vectors + rp.chunk - 1) / rp.chunk;
     if (grid < 1 || grid > INT32_MAX) return hipErrorInvalidValue;
     const TA* a = static_cast<const TA*>(A);
     TB* b = static_cast<TB*>(B);
     void* args[] = {&rp, &a, &b};
-    return hipLaunchKernel(reinterpret_cast<const void*>(&rows_kernel<TA, TB, MODE, V>), dim3((uint32_t)grid), dim3(kRowsThreads), args, 0, stream);
+    return hipLaunchKernel(reinterpret_cast<const void*>(&rows_kernel<TA, TB, MODE, V, U>), dim3((uint32_t)grid), dim3(kRowsThreads), args, 0, stream);
+}
+
+template <typename TA, typename TB, int MODE, int V>
+inline hipError_t launch_rows_one(const Candidate& c, const void* A, void* B, hipStream_t stream)
+{
+    switch (c.rows.unroll) {
+    case 1: return launch_rows_unrolled<TA, TB, MODE, V, 1>(c, A, B, stream);
+    case 2: return launch_rows_unrolled<TA, TB, MODE, V, 2>(c, A, B, stream);
+    case 4: return launch_rows_unrolled<TA, TB, MODE, V, 4>(c, A, B, stream);
+    case 8: return launch_rows_unrolled<TA, TB, MODE, V, 8>(c, A, B, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // VMAXA / VMAXB: elements of each type in 16 bytes
 template <typename TA, typename TB, int MODE, int VMAXA, int VMAXB>
 inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
 {
-    KernelParams kp = c.kp;
-    const uint32_t grid = launch_grid(c, device_cus());
-    set_grid(&kp, grid);
-    { static const bool stop = std::getenv("TTC_DEBUG_STOP") != nullptr; kp.debug_stop = stop ? 1 : 0; }
-    const int va = kp.a.vec, vb = kp.b.vec;
     constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct and row kernel: one width for both sides
     if (c.kernel_class == TTC_KERNEL_ROWS) {
         const int v = c.rows.vec;
@@ -482,6 +474,21 @@ inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStre
         if (v == 4 && VD >= 4) return launch_rows_one<TA, TB, MODE, (VD >= 4 ? 4 : 1)>(c, A, B, s);
         return hipErrorInvalidValue;
     }
+    // the candidate's parameter block is launch-ready for a device of 256 compute units (every MI355X); it is
+    // copied and re-gridded only for another device, or for the set-up measurement (TTC_DEBUG_STOP in the
+    // environment: every workgroup returns after its set-up)
+    static const bool stop = std::getenv("TTC_DEBUG_STOP") != nullptr;
+    const uint32_t grid = launch_grid(c, device_cus());
+    KernelParams other;
+    const KernelParams* ready = &c.kp;
+    if (grid != c.kp.grid || stop) {
+        other = c.kp;
+        set_grid(&other, grid);
+        other.debug_stop = stop ? 1 : 0;
+        ready = &other;
+    }
+    const KernelParams& kp = *ready;
+    const int va = kp.a.vec, vb = kp.b.vec;
     if (c.kernel_class == TTC_KERNEL_DIRECT) {
         if (va == 1) return launch_one<TA, TB, MODE, 1, 1, true>(kp, A, B, grid, c.threads, c.lds_bytes, s);
         if (va == 2 && VD >= 2) return launch_one<TA, TB, MODE, (VD >= 2 ? 2 : 1), (VD >= 2 ? 2 : 1), true>(kp, A, B, grid, c.threads, c.lds_bytes, s);

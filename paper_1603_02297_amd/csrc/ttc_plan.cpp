@@ -701,26 +701,30 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
 
 // The row kernel's candidate: B walked front to back, `vec` elements per lane and access.  Needs rows that are
 // contiguous in both tensors and hold at least one vector, fewer than 2^31 rows, rows shorter than 2^30.
-static bool make_rows_candidate(const Problem& P, int vec, Candidate* out)
+static bool make_rows_candidate(const Problem& P, int vec, int unroll, Candidate* out)
 {
     if (P.perm[0] != 0 || P.stride_a[0] != 1 || P.stride_b[0] != 1) return false;
     const int64_t row = P.size[0], rows = P.elements / P.size[0];
     if (row < vec || row >= (int64_t(1) << 30) || rows >= (int64_t(1) << 31)) return false;
+    // rows that are not a multiple of the vector: their last vector overlaps its neighbour, which is only
+    // harmless where B is not read
+    if (row % vec != 0 && P.epilogue == TTC_EPI_AXPBY) return false;
     Candidate C;
     std::memset(&C, 0, sizeof(C));
     C.kernel_class = TTC_KERNEL_ROWS;
     C.threads = 256;
-    C.wg_per_cu = 0;
+    C.wg_per_cu = 0;                   // one-shot workgroups: nothing to choose
     C.lds_bytes = 0;
     RowsParams& r = C.rows;
     r.n = P.ndim;
     r.vec = vec;
-    r.unroll = 4;
+    r.unroll = unroll;
     r.row = (uint32_t)row;
-    r.chunk = (uint32_t)(C.threads * r.unroll * vec);
-    r.straddle = (row % vec != 0 || P.elements % vec != 0) ? 1 : 0;
-    r.row_div = make_fastdiv((uint32_t)row);
-    r.elements = P.elements;
+    r.slots = (uint32_t)ceil_div(row, vec);
+    r.chunk = (uint32_t)(C.threads * r.unroll);
+    r.overlap = (row % vec != 0) ? 1 : 0;
+    r.slot_div = make_fastdiv(r.slots);
+    r.vectors = rows * (int64_t)r.slots;
     for (int d = 0; d < kMaxDim; ++d) {
         r.size_div[d] = make_fastdiv(1);
         r.stride_a[d] = 0;
@@ -739,8 +743,9 @@ static bool make_rows_candidate(const Problem& P, int vec, Candidate* out)
     kp.n = P.ndim;
     kp.a.vec = vec; kp.b.vec = vec;
     kp.lds_buffers = 1;
-    const int64_t grid = ceil_div(P.elements, r.chunk);
+    const int64_t grid = ceil_div(r.vectors, r.chunk);
     if (grid > INT32_MAX / 2) return false;
+    kp.a.partial = kp.b.partial = r.overlap;
     kp.num_tiles = (uint32_t)grid;
     kp.grid = (uint32_t)grid;
     for (int k = 0; k < kMaxDim; ++k) {
@@ -863,10 +868,15 @@ static double rows_cost(const Problem& P, const Candidate& C)
     double e = -0.30;
     e += 0.60 * oct_below(row_bytes, 512.0);                            // 576-byte rows: 94 % of a copy; 340-byte rows: 62 %
     if (std::fmod(row_bytes, 128.0) != 0.0) e += 0.04;                  // rows that share lines with their neighbours
-    if (C.rows.straddle) e += 0.35;                                     // vectors cut by the row ends go element by element
+    if (C.rows.overlap) e += 0.02;                                      // the last vector of every row repeats part of its neighbour
+    const int in_flight = access * C.rows.unroll;
+    if (in_flight > 32) e += 0.03 * std::log2(in_flight / 32.0);
+    if (in_flight < 32) e += 0.01;
+    // 16-byte accesses, two in flight per lane (8 KB per workgroup): 94 % of a copy on 384^3 and 208x115x63x35 where four
+    // in flight reach 89 %; 4-byte accesses stop at 62 %
     const int access = C.rows.vec * std::max(P.eb_a, P.eb_b);
-    if (access >= 16) e += 0.015;                                       // 8-byte accesses measured a little ahead of 16-byte ones
-    else if (access < 8) e += 0.05;
+    if (access < 8) e += 0.40;
+    else if (access < 16) e += 0.02;
     // small problems: a chunk is 16 KB, and too few of them leave compute units idle (the same guard rails as for tiles)
     const double tiles_wanted = std::min(2048.0, std::max(1.0, (double)P.elements * P.eb_a / 8192.0));
     if (C.kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - C.kp.num_tiles) / 2048.0;
@@ -965,6 +975,7 @@ static double heuristic_cost(const Problem& P, const Candidate& C)
 static bool same_config(const Candidate& x, const Candidate& y)
 {
     if (x.kernel_class != y.kernel_class || x.threads != y.threads || x.wg_per_cu != y.wg_per_cu) return false;
+    if (x.rows.unroll != y.rows.unroll) return false;
     if (x.kp.a.vec != y.kp.a.vec || x.kp.b.vec != y.kp.b.vec || x.kp.lds_buffers != y.kp.lds_buffers) return false;
     for (int k = 0; k < kMaxDim; ++k) {
         if (x.tile[k] != y.tile[k]) return false;
@@ -997,7 +1008,7 @@ static uint64_t config_hash(const Candidate& c)
 {
     uint64_t h = 1469598103934665603ull;
     auto mix = [&](int64_t x) { h = (h ^ (uint64_t)x) * 1099511628211ull; };
-    mix(c.kernel_class); mix(c.threads); mix(c.wg_per_cu);
+    mix(c.kernel_class); mix(c.threads); mix(c.wg_per_cu); mix(c.rows.unroll);
     mix(c.kp.a.vec); mix(c.kp.b.vec); mix(c.kp.lds_buffers);
     for (int k = 0; k < kMaxDim; ++k) { mix(c.tile[k]); mix(c.kp.tile_below[k].div); }
     for (int i = 0; i < kBoxDims; ++i) { mix(c.dlane_a[i]); mix(c.dlane_b[i]); mix(c.dtile_a[i]); mix(c.dtile_b[i]); }
@@ -1084,8 +1095,11 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
     if (stride1_fixed) {
         const int vwide = std::max(1, 16 / eb);
         for (int v = vwide; v >= 1; v /= 2) {
-            Candidate c;
-            if (make_rows_candidate(P, v, &c)) add_candidate(P, out, c);
+            for (int unroll : {2, 4, 1, 8}) {
+                Candidate c;
+                if (make_rows_candidate(P, v, unroll, &c)) add_candidate(P, out, c);
+                if (quick) break;
+            }
         }
     }
 
@@ -1357,6 +1371,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
+    out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : 0;
     return TTC_OK;
     });
 }
@@ -1424,9 +1439,12 @@ static int emulate_rows(const ttc::Problem& P, const ttc::Candidate& C, int64_t*
     using namespace ttc;
     const RowsParams& p = C.rows;
     for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
-    if ((p.vec != 1 && p.vec != 2 && p.vec != 4) || p.unroll != 4 || C.threads != 256 ||
-        p.chunk != (uint32_t)(C.threads * p.unroll * p.vec) || p.row < (uint32_t)p.vec || p.row != (uint32_t)P.size[0] ||
-        p.elements != P.elements || P.size[0] >= (int64_t(1) << 30) || P.elements / P.size[0] >= (int64_t(1) << 31))
+    const int64_t rows = P.elements / P.size[0];
+    if ((p.vec != 1 && p.vec != 2 && p.vec != 4) || (p.unroll != 1 && p.unroll != 2 && p.unroll != 4 && p.unroll != 8) || C.threads != 256 ||
+        p.chunk != (uint32_t)(C.threads * p.unroll) || p.row < (uint32_t)p.vec || p.row != (uint32_t)P.size[0] ||
+        p.slots != (p.row + (uint32_t)p.vec - 1) / (uint32_t)p.vec || p.vectors != rows * (int64_t)p.slots ||
+        p.overlap != (P.size[0] % p.vec != 0 ? 1 : 0) || (p.overlap && P.epilogue == TTC_EPI_AXPBY) ||
+        P.size[0] >= (int64_t(1) << 30) || rows >= (int64_t(1) << 31))
         return TTC_ERR_INTERNAL;
     auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
         if (off < 0) return false;
@@ -1438,32 +1456,24 @@ static int emulate_rows(const ttc::Problem& P, const ttc::Candidate& C, int64_t*
         }
         return off == 0;
     };
-    // lanes without a whole vector load the first vector of each tensor
-    for (int j = 0; j < p.vec; ++j)
-        if (!inside(j, P.stride_a, false) || !inside(j, P.stride_b, true)) return TTC_ERR_INTERNAL;
     int64_t written = 0;
     bool bad = false;
-    auto move = [&](int64_t ea, int64_t eo) {
-        if (!inside(ea, P.stride_a, false) || !inside(eo, P.stride_b, true) || b_from_a[eo] != -1) { bad = true; return; }
-        b_from_a[eo] = ea;
-        ++written;
-    };
-    const int64_t grid = (p.elements + p.chunk - 1) / p.chunk;
+    const int64_t grid = (p.vectors + p.chunk - 1) / p.chunk;
     for (int64_t wg = 0; wg < grid && !bad; ++wg) {
         const int64_t base = wg * (int64_t)p.chunk;
-        const int64_t row0_wide = base / (int64_t)p.row;
-        const uint32_t row0 = (uint32_t)row0_wide, col0 = (uint32_t)(base - row0_wide * (int64_t)p.row);
+        const int64_t row0_wide = base / (int64_t)p.slots;
+        const uint32_t row0 = (uint32_t)row0_wide, slot0 = (uint32_t)(base - row0_wide * (int64_t)p.slots);
         for (int u = 0; u < p.unroll && !bad; ++u)
             for (uint32_t tid = 0; tid < (uint32_t)C.threads && !bad; ++tid) {
-                const uint32_t k = ((uint32_t)u * (uint32_t)C.threads + tid) * (uint32_t)p.vec;
-                const RowAccess x = rows_access(p, base, row0, col0, k, p.vec);
-                if (x.whole) {
-                    for (int j = 0; j < p.vec; ++j) move(x.at.a + j, x.at.b + j);
-                } else if (p.vec > 1 && p.straddle) {
-                    for (int j = 0; j < p.vec; ++j) {
-                        const RowAccess y = rows_access(p, base, row0, col0, k + (uint32_t)j, 1);
-                        if (y.whole) move(y.at.a, y.at.b);
-                    }
+                const RowAccess x = rows_access(p, base, row0, slot0, (uint32_t)u * (uint32_t)C.threads + tid);
+                for (int j = 0; j < p.vec; ++j) {            // loads happen for every lane: they must stay inside
+                    const int64_t ea = x.at.a + j, eo = x.at.b + j;
+                    if (!inside(ea, P.stride_a, false) || !inside(eo, P.stride_b, true)) { bad = true; break; }
+                    if (!x.valid) continue;
+                    // an overlapping vector repeats its neighbour's elements: same source
+                    if (b_from_a[eo] != -1 && (b_from_a[eo] != ea || !p.overlap)) { bad = true; break; }
+                    if (b_from_a[eo] == -1) ++written;
+                    b_from_a[eo] = ea;
                 }
             }
     }

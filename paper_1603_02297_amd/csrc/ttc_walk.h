@@ -51,20 +51,22 @@ TTC_HD RowPlace rows_place(const RowsParams& p, uint32_t row_index, uint32_t col
     return r;
 }
 
-// One access of the row kernel: `k` is the offset of its first element inside the workgroup's chunk, which
-// starts at logical element `base` = row `row0`, column `col0`; `v` elements wide.  whole: all v elements lie
-// in one row and inside the tensor.  (col0 + k stays far below 2^31: rows are shorter than 2^30 elements and
-// a chunk holds at most 2^20.)
-struct RowAccess { RowPlace at; bool whole; };
+// One access of the row kernel: `k` is the number of its vector inside the workgroup's chunk, which starts at
+// vector `base` = row `row0`, slot `slot0` (a row holds `slots` vectors; where the row is not a multiple of the
+// vector, the last one is moved back so that it ends with the row and repeats elements of its neighbour).
+// (slot0 + k stays far below 2^31: rows are shorter than 2^30 elements and a chunk holds at most 2^20 vectors.)
+struct RowAccess { RowPlace at; bool valid; };
 
-TTC_HD RowAccess rows_access(const RowsParams& p, int64_t base, uint32_t row0, uint32_t col0, uint32_t k, int v)
+TTC_HD RowAccess rows_access(const RowsParams& p, int64_t base, uint32_t row0, uint32_t slot0, uint32_t k)
 {
-    const uint32_t x = col0 + k;
-    const uint32_t rl = fdiv(x, p.row_div);
-    const uint32_t c = x - rl * p.row;
+    const uint32_t x = slot0 + k;
+    const uint32_t rl = fdiv(x, p.slot_div);
+    const uint32_t sl = x - rl * p.slots;
+    uint32_t c = sl * (uint32_t)p.vec;
+    if (c + (uint32_t)p.vec > p.row) c = p.row - (uint32_t)p.vec;      // only with overlap: the last slot of a row
     RowAccess r;
-    r.at = rows_place(p, row0 + rl, c);
-    r.whole = (base + (int64_t)k + v <= p.elements) && (c + (uint32_t)v <= p.row);
+    r.valid = (base + (int64_t)k < p.vectors);
+    r.at = rows_place(p, r.valid ? row0 + rl : 0u, r.valid ? c : 0u);  // past the end: the first vector, never stored
     return r;
 }
 

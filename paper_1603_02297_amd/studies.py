@@ -113,14 +113,14 @@ def time_candidates(plan, a_ptrs, b_ptrs, stream, warm=1, reps=4):
 
 
 def retime_best(plan, rows, a_ptrs, b_ptrs, stream, keep=8):
-    """Time the fastest few again, longer, with the streaming hints by rule, off and on, then with the other
-    tile mappings (as the library's own search does), and return rows with those entries replaced by their best."""
+    """Time the fastest few again, longer, with the streaming hints by rule, off, on and on one side only, then with
+    the other tile mappings (as the library's own search does), and return rows with those entries replaced by their best."""
     order = sorted(range(len(rows)), key=lambda i: rows[i][1])[:keep]
     rows = list(rows)
     for i in order:
         ttc.ttc_plan_select_candidate(plan, i)
         best = None
-        for sa, sb in ((-1, -1), (0, 0), (1, 1)):
+        for sa, sb in ((-1, -1), (0, 0), (1, 1), (1, 0), (0, 1)):
             ttc.ttc_plan_set_streaming(plan, sa, sb)
             ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
             if best is None or ms < best[1]:
@@ -128,6 +128,8 @@ def retime_best(plan, rows, a_ptrs, b_ptrs, stream, keep=8):
         info = best[0]
         ttc.ttc_plan_set_streaming(plan, info["nt_a"], info["nt_b"])
         for mode in (1, 3):                      # tiles dealt to the XCDs: one range each, chunks of 8 (default: chunks of 32)
+            if info["kernel_class"] == ttc.TTC_KERNEL_ROWS:
+                break                            # no tiles to deal
             ttc.ttc_plan_set_tile_mapping(plan, mode)
             ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, 2, 12)
             if ms < best[1]:

@@ -116,7 +116,7 @@ static void check_planner()
         ttc_plan_t p = ttc_plan_create(c.dtype, c.ndim, c.sizes, c.perm, nullptr, nullptr);
         const std::string bad = store + ".bad";
         std::FILE* f = std::fopen(bad.c_str(), "w");
-        if (f) { std::fputs("ttc3 gfx950 0 1 2 37 19 1 0 1 37 19 1 | 1 2 x 4 | 0 0 99 12\n", f); std::fclose(f); }
+        if (f) { std::fputs("ttc4 gfx950 0 1 2 37 19 1 0 1 37 19 1 | 1 2 x 4 | 0 0 99 12\n", f); std::fclose(f); }
         ttc_plan_info_t a, b;
         ttc_plan_get_info(p, &a);
         EXPECT(ttc_plan_cache_lookup(p, bad.c_str()) == TTC_ERR_NOT_FOUND, "damaged line accepted");
