@@ -195,14 +195,15 @@ def main() -> int:
         ck = ttc.ttc_time_ceiling(0, nbytes, a_ptrs, b_ptrs, stream, W, reps)
         cm = ttc.ttc_time_ceiling(1, nbytes, a_ptrs, b_ptrs, stream, W, reps)
         cs = ttc.ttc_time_ceiling(3, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-        copy_k, copy_m, copy_s = (2 * nbytes / t / 1e6 for t in (ck, cm, cs))
+        co = ttc.ttc_time_ceiling(4, nbytes, a_ptrs, b_ptrs, stream, W, reps)
+        copy_k, copy_m, copy_s, copy_o = (2 * nbytes / t / 1e6 for t in (ck, cm, cs, co))
         axpby = None
         if not c.beta_is_zero:
             cx = ttc.ttc_time_ceiling(2, nbytes, a_ptrs, b_ptrs, stream, W, reps)
             axpby = 3 * nbytes / cx / 1e6
             for t in B_dev:                                      # the axpby ceiling changed B
                 t.copy_(torch.from_numpy(B_host))
-        d2d = max(copy_k, copy_m, copy_s)           # the fastest known way to copy is the ceiling
+        d2d = max(copy_k, copy_m, copy_s, copy_o)   # the fastest known way to copy is the ceiling
 
         plan = ttc.ttc_plan_create(c.dtype, len(c.sizes), c.sizes, c.perm, c.alpha, c.beta)
         ms_heur = None if args.no_heuristic else ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, reps)
@@ -254,7 +255,7 @@ def main() -> int:
         }
         results.append(r)
         log(f"[gpu] {c.name}: {gbps:.0f} GB/s = {100 * r['frac_d2d_copy']:.1f}% of D2D copy ({d2d:.0f}; kernel {copy_k:.0f}, "
-            f"nt kernel {copy_s:.0f}, memcpy {copy_m:.0f}), heuristic {r['heuristic_GBps'] or 0:.0f}, max_ulp {max_ulp}, "
+            f"nt kernel {copy_s:.0f}, one-shot nt {copy_o:.0f}, memcpy {copy_m:.0f}), heuristic {r['heuristic_GBps'] or 0:.0f}, max_ulp {max_ulp}, "
             f"{source}: {r['plan']}")
         del A_dev, B_dev
         torch.cuda.empty_cache()

@@ -104,6 +104,15 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(const uint4* __restric
     copy_chunks<true>(src, dst, n);
 }
 
+// one 16-byte access per lane, one 4 KB chunk per workgroup, non-temporal: nothing persistent, the hardware deals
+// the chunks (the launch shape of the row kernel); the faster copy on the largest tensors
+__global__ __launch_bounds__(256) void copy_oneshot_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n)
+{
+    typedef uint32_t W __attribute__((ext_vector_type(4)));
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const W*>(src) + i), reinterpret_cast<W*>(dst) + i);
+}
+
 __global__ __launch_bounds__(256) void axpby_kernel(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n)
 {
     const int64_t chunk = 256 * 4;
@@ -311,7 +320,7 @@ int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src
                      void* stream, int warmup, int iters, float* ms_per_launch)
 {
     if (!src_list || !dst_list || !ms_per_launch) return TTC_ERR_NULL_POINTER;
-    if (kind < 0 || kind > 3 || bytes < 16 || (bytes % 16) != 0 || npairs < 1 || warmup < 0 || iters < 1)
+    if (kind < 0 || kind > 4 || bytes < 16 || (bytes % 16) != 0 || npairs < 1 || warmup < 0 || iters < 1)
         return TTC_ERR_INVALID_VALUE;
     for (int i = 0; i < npairs; ++i) {
         if (!src_list[i] || !dst_list[i]) return TTC_ERR_NULL_POINTER;
@@ -337,6 +346,12 @@ int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src
         if (kind == 1) return hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyDeviceToDevice, s);
         if (kind == 3) {
             hipLaunchKernelGGL(ttc::copy_stream_kernel, dim3(copy_grid), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n);
+            return hipGetLastError();
+        }
+        if (kind == 4) {
+            const int64_t g = (n + 255) / 256;
+            if (g > INT32_MAX) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(ttc::copy_oneshot_kernel, dim3((uint32_t)g), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n);
             return hipGetLastError();
         }
         hipLaunchKernelGGL(ttc::axpby_kernel, dim3(copy_grid), dim3(256), 0, s, (const float4*)src, (float4*)dst, n);

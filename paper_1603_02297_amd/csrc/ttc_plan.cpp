@@ -869,14 +869,16 @@ static double rows_cost(const Problem& P, const Candidate& C)
     e += 0.60 * oct_below(row_bytes, 512.0);                            // 576-byte rows: 94 % of a copy; 340-byte rows: 62 %
     if (std::fmod(row_bytes, 128.0) != 0.0) e += 0.04;                  // rows that share lines with their neighbours
     if (C.rows.overlap) e += 0.02;                                      // the last vector of every row repeats part of its neighbour
-    // 16-byte accesses, two in flight per lane (8 KB per workgroup): 94 % of a copy on 384^3 and 208x115x63x35 where four
-    // in flight reach 89 %; 4-byte accesses stop at 62 %
+    // Access width and bytes a lane keeps in flight (loads of B count when beta != 0), measured on 384^3, 374^3,
+    // 917x374x153, 208x115x63x35 and 72^4 fp64: 16-byte accesses with 16 to 32 bytes in flight reach 94-97 % of a
+    // copy (4 to 8 KB per workgroup); every doubling beyond costs about 4 %, 8 bytes in flight reach 70 %,
+    // 8-byte accesses trail 16-byte ones by 5 %, 4-byte accesses stop at 62 %.
     const int access = C.rows.vec * std::max(P.eb_a, P.eb_b);
     if (access < 8) e += 0.40;
-    else if (access < 16) e += 0.02;
-    const int in_flight = access * C.rows.unroll;
-    if (in_flight > 32) e += 0.03 * std::log2(in_flight / 32.0);
-    if (in_flight < 32) e += 0.01;
+    else if (access < 16) e += 0.05;
+    const double in_flight = (double)access * C.rows.unroll * (P.epilogue == TTC_EPI_AXPBY ? 2.0 : 1.0);
+    if (in_flight > 32.0) e += 0.045 * std::log2(in_flight / 32.0);
+    if (in_flight < 16.0) e += 0.30 * std::log2(16.0 / in_flight);
     // small problems: a chunk is 4 to 32 KB, and too few of them leave compute units idle (the same guard rails as for tiles)
     const double tiles_wanted = std::min(2048.0, std::max(1.0, (double)P.elements * P.eb_a / 8192.0));
     if (C.kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - C.kp.num_tiles) / 2048.0;

@@ -145,7 +145,8 @@ def d2d_copy_gbps(nbytes, a_ptrs, b_ptrs, stream):
     ck = ttc.ttc_time_ceiling(0, nbytes, a_ptrs, b_ptrs, stream, 2, 10)
     cm = ttc.ttc_time_ceiling(1, nbytes, a_ptrs, b_ptrs, stream, 2, 10)
     cs = ttc.ttc_time_ceiling(3, nbytes, a_ptrs, b_ptrs, stream, 2, 10)
-    return 2 * nbytes / min(ck, cm, cs) / 1e6
+    co = ttc.ttc_time_ceiling(4, nbytes, a_ptrs, b_ptrs, stream, 2, 10)
+    return 2 * nbytes / min(ck, cm, cs, co) / 1e6
 
 
 # ---- study 1: reduction of the search space -------------------------------------------------------
