@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--problem", type=str, default="",
                     help="time this problem instead of the suite: dtype:sizes:perm[:alpha:beta], e.g. f32:85x85x85x85:3210:1:0 "
                          "(what profiles/ uses for shapes outside the suite; not a bench line)")
-    ap.add_argument("--force-class", type=str, default="", choices=("", "direct", "lds", "rows"),
+    ap.add_argument("--force-class", type=str, default="", choices=("", "direct", "lds", "rows", "micro"),
                     help="run the best-ranked candidate of this kernel family instead of the stored or searched plan")
     ap.add_argument("--store-plans", type=str, default="",
                     help="append what the run selected for every case to this file (the format of --plan-cache)")
@@ -121,7 +121,7 @@ class CpuLeg:
 
 def plan_text(info, ttc) -> str:
     """The selected configuration in one short string (the fields that name it in the plan store and the profiles)."""
-    cls = {ttc.TTC_KERNEL_DIRECT: "direct", ttc.TTC_KERNEL_LDS: "lds", ttc.TTC_KERNEL_ROWS: "rows"}[info["kernel_class"]]
+    cls = {ttc.TTC_KERNEL_DIRECT: "direct", ttc.TTC_KERNEL_LDS: "lds", ttc.TTC_KERNEL_ROWS: "rows", ttc.TTC_KERNEL_MICRO: "micro"}[info["kernel_class"]]
     tile = "x".join(str(t) for t in info["tile"])
     return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} u{info['unroll']} "
             f"buf{info['lds_buffers']} lds{info['lds_bytes']} nt{info['nt_a']}{info['nt_b']} x{info['xcd_remap']} "
@@ -210,7 +210,7 @@ def main() -> int:
         t0 = time.perf_counter()
         source = "search"
         if args.force_class:
-            want_cls = {"direct": ttc.TTC_KERNEL_DIRECT, "lds": ttc.TTC_KERNEL_LDS, "rows": ttc.TTC_KERNEL_ROWS}[args.force_class]
+            want_cls = {"direct": ttc.TTC_KERNEL_DIRECT, "lds": ttc.TTC_KERNEL_LDS, "rows": ttc.TTC_KERNEL_ROWS, "micro": ttc.TTC_KERNEL_MICRO}[args.force_class]
             source = "first " + args.force_class
             for k in range(ttc.ttc_plan_candidate_count(plan)):
                 ttc.ttc_plan_select_candidate(plan, k)

@@ -50,7 +50,9 @@ enum {
 
 /* Kernel families (paper Section 3.1: the stride-1 index keeps its place, or not). */
 enum { TTC_KERNEL_DIRECT = 0 /* tiles, no staging: stride-1 index fixed */, TTC_KERNEL_LDS = 1 /* tile staged through LDS */,
-       TTC_KERNEL_ROWS = 2 /* stride-1 index fixed: B walked front to back, rows gathered from A */ };
+       TTC_KERNEL_ROWS = 2 /* stride-1 index fixed: B walked front to back, rows gathered from A */,
+       TTC_KERNEL_MICRO = 3 /* tile over the two stride-1 indices only: 128-bit LDS accesses, XOR-swizzled rows,
+                               register transposes of 4x4 (2x2) blocks */ };
 /* Epilogues chosen from alpha, beta. */
 enum { TTC_EPI_COPY = 0 /* alpha=1, beta=0 */, TTC_EPI_SCALE = 1 /* beta=0: B never read */, TTC_EPI_AXPBY = 2 };
 
@@ -102,7 +104,8 @@ typedef struct {
                                               then all of them: candidate 0 as created, the others by heuristic cost */
     float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
     double  heuristic_cost;                /* the ranking key: modelled relative cost, smaller is better */
-    int     unroll;                        /* row kernel: vectors a lane keeps in flight (1, 2, 4 or 8); 0 for the tile kernels */
+    int     unroll;                        /* row kernel: vectors a lane keeps in flight (1, 2, 4 or 8); micro-tile kernel: blocks a lane owns
+                                              (1 or 2); 0 for the box kernels */
 } ttc_plan_info_t;
 
 /*

@@ -17,7 +17,7 @@ TTC_OK = 0
 (TTC_ERR_INVALID_VALUE, TTC_ERR_INVALID_PERM, TTC_ERR_UNSUPPORTED_DTYPE, TTC_ERR_NULL_POINTER,
  TTC_ERR_ALIAS, TTC_ERR_OVERFLOW, TTC_ERR_HIP, TTC_ERR_ALLOC, TTC_ERR_MISALIGNED, TTC_ERR_INTERNAL,
  TTC_ERR_NOT_FOUND, TTC_ERR_IO) = range(1, 13)
-TTC_KERNEL_DIRECT, TTC_KERNEL_LDS, TTC_KERNEL_ROWS = 0, 1, 2
+TTC_KERNEL_DIRECT, TTC_KERNEL_LDS, TTC_KERNEL_ROWS, TTC_KERNEL_MICRO = 0, 1, 2, 3
 TTC_EPI_COPY, TTC_EPI_SCALE, TTC_EPI_AXPBY = 0, 1, 2
 
 EXPORTS = (

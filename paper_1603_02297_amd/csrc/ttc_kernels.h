@@ -393,6 +393,113 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
     else        { if (p.nt_b) run(std::false_type(), std::true_type()); else run(std::false_type(), std::false_type()); }
 }
 
+// ---------------------------------------------------------------------------------
+// The micro-tile kernel (the paper's w x w in-register transposition, Section 3.2, in its gfx950 form): a tile over
+// the two stride-1 indices only, every access 128 bits wide.  Lanes load 16-byte vectors along A's stride-1 index
+// and park each with one 128-bit LDS write; after the barrier a lane reads the V x V block it owns with V
+// 128-bit LDS reads (rows of the tile are XOR-swizzled at 16-byte granularity, see MicroParams: neither phase
+// has bank conflicts), transposes it in registers -- no cross-lane traffic: row i of the block is one register
+// quad, column j is element j of each -- and stores V 16-byte vectors along B's stride-1 index.
+// Planned only where both extents are multiples of V and both tensors have one element type.
+// ---------------------------------------------------------------------------------
+template <typename T, int MODE, int V, int M>
+__global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by_value, const T* __restrict__ A, T* __restrict__ B)
+{
+    static_assert(V * sizeof(T) == 16, "one 16-byte vector");
+    const KernelParams& p = *reinterpret_cast<const KernelParams*>((const void*)__builtin_amdgcn_kernarg_segment_ptr());
+    extern __shared__ __align__(16) unsigned char smem[];
+    typedef uint32_t Quad __attribute__((ext_vector_type(4)));
+    Quad* lds = reinterpret_cast<Quad*>(smem);
+    constexpr int N = M * V;                                   // vectors a lane loads, and stores, per tile
+    constexpr int32_t kScale = (int32_t)sizeof(T);
+    const MicroParams& m = p.micro;
+    const Epilogue<T, T, MODE> epi(p.alpha, p.beta);
+    const uint32_t tid = threadIdx.x, threads = blockDim.x;
+    const int64_t row_a = m.stride_a_p0 * kScale, col_b = m.stride_b_0 * kScale;      // bytes
+    const uint32_t row_chunks = 1u << m.la_log;
+    const TileSeq seq = tile_sequence(p, blockIdx.x);
+    for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
+        const MicroTile t = micro_tile(p, tile_of(seq, q));
+        const unsigned char* At = reinterpret_cast<const unsigned char*>(A + t.a);
+        unsigned char* Bt = reinterpret_cast<unsigned char*>(B + t.b);
+        auto run = [&](auto stream_a, auto stream_b) {
+            constexpr bool NTA = decltype(stream_a)::value, NTB = decltype(stream_b)::value;
+            // ---- A order: global -> LDS.  A lane outside the tensor loads the tile's first vector instead
+            // (no load in divergent control flow) and parks it in its own slot, which nobody reads.
+            union Vec { Pack<T, V> p; Quad q; };
+            Vec in[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                const MicroLoad x = micro_load(m, threads, tid, (uint32_t)k);
+                const bool ok = x.row < t.lim_b && x.col < t.lim_a;
+                in[k].p = load_pack<T, V, NTA>(At, ok ? (int64_t)x.row * row_a + (int64_t)x.col * kScale : 0);
+            }
+#pragma unroll
+            for (int k = 0; k < N; ++k) lds[micro_load(m, threads, tid, (uint32_t)k).chunk] = in[k].q;
+            __syncthreads();
+            // ---- B order: LDS -> registers (V x V block) -> epilogue -> global
+#pragma unroll
+            for (int b = 0; b < M; ++b) {
+                const MicroBlock x = micro_block(m, threads, tid, (uint32_t)b);
+                const bool ok = x.row < t.lim_b && x.col < t.lim_a;
+                const int64_t to = (int64_t)x.col * col_b + (int64_t)x.row * kScale;
+                Pack<T, V> old[V];
+                if (MODE == TTC_EPI_AXPBY) {
+#pragma unroll
+                    for (int j = 0; j < V; ++j) old[j] = load_pack<T, V, NTB>(Bt, ok ? to + j * col_b : 0);
+                }
+                Vec blk[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i) blk[i].q = lds[x.chunk + (uint32_t)i * row_chunks];
+                if (ok) {
+#pragma unroll
+                    for (int j = 0; j < V; ++j) {
+                        Pack<T, V> out;
+#pragma unroll
+                        for (int i = 0; i < V; ++i) {
+                            T b_old = T();
+                            if (MODE == TTC_EPI_AXPBY) b_old = old[j].v[i];
+                            out.v[i] = epi(blk[i].p.v[j], b_old);
+                        }
+                        store_pack<T, V, NTB>(Bt, to + j * col_b, out);
+                    }
+                }
+            }
+        };
+        if (p.nt_a) { if (p.nt_b) run(std::true_type(), std::true_type()); else run(std::true_type(), std::false_type()); }
+        else        { if (p.nt_b) run(std::false_type(), std::true_type()); else run(std::false_type(), std::false_type()); }
+        __syncthreads();                                       // the tile buffer is refilled by the next tile
+    }
+}
+
+template <typename T, int MODE, int V, int M>
+inline hipError_t launch_micro_blocks(const Candidate& c, const void* A, void* B, hipStream_t stream)
+{
+    const KernelParams& kp = c.kp;
+    const MicroParams& m = kp.micro;
+    const uint32_t grid = kp.num_tiles;                        // one tile per workgroup: the hardware deals them
+    if (m.vec != V || m.micro != M || c.threads < 64 || c.threads > 256 || (c.threads & (c.threads - 1)) ||
+        (int64_t)m.ta * m.tb != (int64_t)c.threads * V * V * M || m.ta != (V << m.la_log) || m.tb != (V << m.lb_log) ||
+        m.la_log < 3 || m.lb_log < 3 || (1 << m.la_log) > c.threads || (1 << m.lb_log) > c.threads ||
+        c.lds_bytes != m.ta * m.tb * (int)sizeof(T) || grid < 1 || grid != kp.grid) return hipErrorInvalidValue;
+    const void* fn = reinterpret_cast<const void*>(&micro_kernel<T, MODE, V, M>);
+    const T* a = static_cast<const T*>(A);
+    T* b = static_cast<T*>(B);
+    void* args[] = {const_cast<KernelParams*>(&kp), &a, &b};
+    return hipLaunchKernel(fn, dim3(grid), dim3(c.threads), args, (size_t)c.lds_bytes, stream);
+}
+
+template <typename TA, typename TB, int MODE>
+inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipStream_t stream)
+{
+    if constexpr (std::is_same<TA, TB>::value && (sizeof(TA) == 4 || sizeof(TA) == 8)) {
+        constexpr int V = 16 / (int)sizeof(TA);
+        if (c.kp.micro.micro == 1) return launch_micro_blocks<TA, MODE, V, 1>(c, A, B, stream);
+        if (c.kp.micro.micro == 2) return launch_micro_blocks<TA, MODE, V, 2>(c, A, B, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
 // Compute units of the current device (256 on MI355X), asked once per process and device.
 inline int device_cus()
 {
@@ -467,6 +574,7 @@ template <typename TA, typename TB, int MODE, int VMAXA, int VMAXB>
 inline hipError_t launch_vec(const Candidate& c, const void* A, void* B, hipStream_t s)
 {
     constexpr int VD = VMAXA < VMAXB ? VMAXA : VMAXB;      // direct and row kernel: one width for both sides
+    if (c.kernel_class == TTC_KERNEL_MICRO) return launch_micro<TA, TB, MODE>(c, A, B, s);
     if (c.kernel_class == TTC_KERNEL_ROWS) {
         const int v = c.rows.vec;
         if (v == 1) return launch_rows_one<TA, TB, MODE, 1>(c, A, B, s);

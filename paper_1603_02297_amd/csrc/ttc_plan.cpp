@@ -699,6 +699,82 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     return true;
 }
 
+// The micro-tile kernel's candidate: a tile of ta x tb elements over A's index 0 and B's stride-1 index p0.
+// Needs one element type of 4 or 8 bytes on both sides, both indices contiguous in their tensor and both extents
+// multiples of the 16-byte vector, ta / vec and tb / vec powers of two of at least 8, and ta * tb = threads * vec^2
+// * (1 or 2).
+static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, const int* tile_order, Candidate* out)
+{
+    if (P.ndim < 2 || P.perm[0] == 0 || P.kind_a != P.kind_b || (P.eb_a != 4 && P.eb_a != 8)) return false;
+    const int p0 = P.perm[0], vec = 16 / P.eb_a;
+    if (P.stride_a[0] != 1 || P.stride_b[p0] != 1) return false;
+    if (P.size[0] % vec != 0 || P.size[p0] % vec != 0 || ta % vec != 0 || tb % vec != 0) return false;
+    const int la = ta / vec, lb = tb / vec;
+    auto log2_exact = [](int x) { int l = 0; while ((1 << l) < x) ++l; return (1 << l) == x ? l : -1; };
+    const int la_log = log2_exact(la), lb_log = log2_exact(lb);
+    if (la_log < 3 || lb_log < 3 || la > threads || lb > threads) return false;
+    const int64_t blocks = (int64_t)la * lb;
+    if (blocks % threads != 0) return false;
+    const int micro = (int)(blocks / threads);
+    if (micro != 1 && micro != 2) return false;
+    Candidate C;
+    std::memset(&C, 0, sizeof(C));
+    C.kernel_class = TTC_KERNEL_MICRO;
+    C.threads = threads;
+    C.wg_per_cu = 0;                   // one tile per workgroup
+    C.lds_bytes = ta * tb * P.eb_a;
+    if (C.lds_bytes > kMaxLdsBytes) return false;
+    KernelParams& kp = C.kp;
+    kp.n = P.ndim;
+    int64_t ntiles = 1;
+    for (int k = 0; k < kMaxDim; ++k) {
+        C.tile[k] = (k == 0) ? ta : (k == p0 ? tb : 1);
+        kp.tile[k] = C.tile[k];
+        kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
+        kp.stride_b[k] = (k < P.ndim) ? P.stride_b[k] : 0;
+        kp.tile_below[k] = kp.tile_cnt[k] = make_fastdiv(1);
+    }
+    for (int i = 0; i < P.ndim; ++i) {
+        const int k = tile_order[i];
+        const int64_t cnt = ceil_div(P.size[k], C.tile[k]);
+        if (cnt > INT32_MAX / 2 || ntiles > INT32_MAX / 2) return false;
+        kp.tile_below[k] = make_fastdiv((uint32_t)ntiles);
+        kp.tile_cnt[k] = make_fastdiv((uint32_t)cnt);
+        ntiles *= cnt;
+        if (ntiles > INT32_MAX / 2) return false;
+        C.tile_order[i] = k;
+    }
+    kp.num_tiles = (uint32_t)ntiles;
+    kp.tiles_per_xcd = kp.num_tiles / 8;
+    kp.tiles_rem_xcd = kp.num_tiles % 8;
+    if (!set_tile_mapping(&kp, kDefaultTileMapping)) return false;
+    set_grid(&kp, kp.num_tiles);
+    kp.alpha[0] = P.alpha[0]; kp.alpha[1] = P.alpha[1];
+    kp.beta[0] = P.beta[0];   kp.beta[1] = P.beta[1];
+    kp.a.vec = kp.b.vec = vec;
+    kp.lds_buffers = 1;
+    kp.lds_tile_elems = ta * tb;
+    for (int j = 0; j < kBoxDims; ++j) {            // the box kernels' slots, so that shared helpers see neutral values
+        kp.slot[j].tile = 1; kp.slot[j].size = 1;
+        kp.slot[j].tile_below = kp.slot[j].tile_cnt = make_fastdiv(1);
+    }
+    MicroParams& m = kp.micro;
+    m.ta = ta; m.tb = tb; m.p0 = p0; m.vec = vec;
+    m.la_log = la_log; m.lb_log = lb_log; m.micro = micro;
+    m.vec_log = (vec == 4) ? 2 : 1;
+    m.size_a0 = P.size[0]; m.size_p0 = P.size[p0];
+    m.stride_a_p0 = P.stride_a[p0];
+    m.stride_b_0 = P.stride_b[0];
+    C.digits_a = C.digits_b = 2;
+    C.dtile_a[0] = ta; C.dtile_a[1] = tb; C.dlane_a[0] = std::min(ta, kWave * vec); C.dlane_a[1] = std::max(1, kWave / la);
+    C.dtile_b[0] = tb; C.dtile_b[1] = ta; C.dlane_b[0] = std::min(tb, kWave * vec); C.dlane_b[1] = std::max(1, kWave / lb) * vec;
+    C.lds_conflict_a = C.lds_conflict_b = 2;       // conflict-free by construction (the value the bank model gives such a layout)
+    C.lds_stride[0] = 1;
+    C.lds_stride[p0] = ta;
+    *out = C;
+    return true;
+}
+
 // The row kernel's candidate: B walked front to back, `vec` elements per lane and access.  Needs rows that are
 // contiguous in both tensors and hold at least one vector, fewer than 2^31 rows, rows shorter than 2^30.
 static bool make_rows_candidate(const Problem& P, int vec, int unroll, Candidate* out)
@@ -785,6 +861,7 @@ bool set_tile_mapping(KernelParams* kp, int mode)
 
 uint32_t launch_grid(const Candidate& c, int cus)
 {
+    if (c.kernel_class == TTC_KERNEL_MICRO || c.kernel_class == TTC_KERNEL_ROWS) return c.kp.num_tiles;    // one-shot workgroups
     const uint64_t want = (uint64_t)std::max(cus, 1) * (uint64_t)std::max(c.wg_per_cu, 1);
     return (uint32_t)std::min<uint64_t>(want, c.kp.num_tiles);
 }
@@ -887,9 +964,40 @@ static double rows_cost(const Problem& P, const Candidate& C)
     return std::exp(e);
 }
 
+// The micro-tile kernel against the box kernels: the same terms for what it shares with them (contiguous runs per
+// side, remainder tiles, tiles to fill the chip), none for what it does not have (tables, barriers per walk, bank
+// conflicts).
+static double micro_cost(const Problem& P, const Candidate& C)
+{
+    auto oct_below = [](double x, double ref) { return x < ref ? std::log2(ref / x) : 0.0; };
+    const MicroParams& m = C.kp.micro;
+    const double run_a = (double)m.ta * P.eb_a, run_b = (double)m.tb * P.eb_a;
+    // measured against the best box candidate (% of a copy): 384^3 (1,0,2) 96.9 vs 92.9, (2,1,0) 83.8 vs 81.0, 5184^2 fp64
+    // 99.3 vs 93.7, 7232^2 90.7 vs 88, 1024^2 58 vs 48, 8192^2 91.1 vs 91.8; 72^4 fp64 (3,2,1,0), where tiles of 16 to 128
+    // leave 72 a remainder of 8: 74 vs 82
+    double e = -0.16;
+    e += 0.03 * oct_below(run_a, 256.0) + 0.03 * oct_below(run_b, 256.0);
+    double padded = ((double)ceil_div(P.size[0], m.ta) * m.ta / (double)P.size[0]) *
+                    ((double)ceil_div(P.size[m.p0], m.tb) * m.tb / (double)P.size[m.p0]);
+    e += 0.45 * (padded - 1.0);                                          // whole workgroups idle in the remainder tiles
+    const int64_t line = 128 / P.eb_a;
+    if (P.size[0] % line != 0) e += 0.05;                                // runs of A start inside lines
+    if (P.size[m.p0] % line != 0) e += 0.05;
+    if (C.threads == 128) e += 0.005; else if (C.threads == 64) e += 0.01;
+    bool b_order = true;
+    for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
+    if (!b_order) e += 0.01;
+    const double tiles_wanted = std::min(2048.0, std::max(1.0, (double)P.elements * P.eb_a / 8192.0));
+    if (C.kp.num_tiles < tiles_wanted) e += 1.28 * (tiles_wanted - C.kp.num_tiles) / 2048.0;
+    const double cus_wanted = std::min(256.0, std::max(1.0, (double)P.elements * P.eb_a / 4096.0));
+    if (C.kp.num_tiles < cus_wanted) e += 1.5 * (cus_wanted - C.kp.num_tiles) / 256.0;
+    return std::exp(e);
+}
+
 static double heuristic_cost(const Problem& P, const Candidate& C)
 {
     if (C.kernel_class == TTC_KERNEL_ROWS) return rows_cost(P, C);
+    if (C.kernel_class == TTC_KERNEL_MICRO) return micro_cost(P, C);
     // Weights fitted to timings of every candidate of 105 problems on MI355X (the benchmark workloads, 3-D and
     // 5-D problems with odd extents, a 57-case benchmark drawn by the paper's rules, power-of-two shapes): log-linear least
     // squares weighted towards the fast candidates, penalties constrained to be penalties, a small ridge term,
@@ -1141,6 +1249,18 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
         }
     }
 
+    // -- the micro-tile kernel: a tile over the two stride-1 indices, where both extents are whole vectors
+    if (!stride1_fixed && n >= 2) {
+        const int vec = std::max(1, 16 / P.eb_a);
+        for (int threads : {256, 128, 64})
+            for (int la = 8; la <= threads; la *= 2)
+                for (int lb = 8; lb <= threads; lb *= 2)
+                    for (int o = 0; o < (quick ? 1 : 2); ++o) {
+                        Candidate c;
+                        if (make_micro_candidate(P, la * vec, lb * vec, threads, orders[o], &c)) add_candidate(P, out, c);
+                    }
+    }
+
     // -- staged candidates: a box spanning the leading indices of A and of B
     if (n >= 2) {
         const int p0 = P.perm[0];
@@ -1212,7 +1332,7 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
     if (verbose()) {
         const Candidate& c = plan->cands[0];
         std::fprintf(stderr, "ttc: plan dtype %d, %d fused indices, %s kernel, tile", P.dtype, P.ndim,
-                     c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : (c.kernel_class == TTC_KERNEL_ROWS ? "row" : "staged"));
+                     c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : (c.kernel_class == TTC_KERNEL_ROWS ? "row" : (c.kernel_class == TTC_KERNEL_MICRO ? "micro-tile" : "staged")));
         for (int k = 0; k < P.ndim; ++k) std::fprintf(stderr, " %d", c.tile[k]);
         std::fprintf(stderr, ", vectors %d/%d, %d threads, %d B LDS, cost %.4f (best of %zu quick candidates)\n",
                      c.kp.a.vec, c.kp.b.vec, c.threads, c.lds_bytes, c.score, quick.size());
@@ -1373,7 +1493,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
-    out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : 0;
+    out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : (C.kernel_class == TTC_KERNEL_MICRO ? C.kp.micro.micro : 0);
     return TTC_OK;
     });
 }
@@ -1482,12 +1602,96 @@ static int emulate_rows(const ttc::Problem& P, const ttc::Candidate& C, int64_t*
     return (bad || written != P.elements) ? TTC_ERR_INTERNAL : TTC_OK;
 }
 
+// Replay of the micro-tile kernel: every workgroup, every lane, the index code the kernel runs; every LDS slot
+// must be written before it is read, inside the tile buffer.
+static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t* b_from_a)
+{
+    using namespace ttc;
+    const KernelParams& p = C.kp;
+    const MicroParams& m = p.micro;
+    for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
+    const uint32_t threads = (uint32_t)C.threads;
+    const int vec = m.vec;
+    if ((vec != 2 && vec != 4) || vec * P.eb_a != 16 || P.eb_a != P.eb_b || (m.micro != 1 && m.micro != 2) ||
+        (threads != 64 && threads != 128 && threads != 256) || m.ta != (vec << m.la_log) || m.tb != (vec << m.lb_log) ||
+        m.la_log < 3 || m.lb_log < 3 || (int64_t)m.ta * m.tb != (int64_t)threads * vec * vec * m.micro ||
+        (1u << m.la_log) > threads || (1u << m.lb_log) > threads || (1 << m.vec_log) != vec ||
+        C.lds_bytes != m.ta * m.tb * P.eb_a || C.lds_bytes > kMaxLdsBytes || p.grid != p.num_tiles ||
+        m.p0 != P.perm[0] || m.p0 == 0 || m.size_a0 != P.size[0] || m.size_p0 != P.size[m.p0] ||
+        m.stride_a_p0 != P.stride_a[m.p0] || m.stride_b_0 != P.stride_b[0] || P.stride_a[0] != 1 || P.stride_b[m.p0] != 1 ||
+        P.size[0] % vec != 0 || P.size[m.p0] % vec != 0)
+        return TTC_ERR_INTERNAL;
+    auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
+        if (off < 0) return false;
+        for (int i = P.ndim - 1; i >= 0; --i) {
+            const int k = b_side ? P.perm[i] : i;
+            const int64_t c = off / stride[k];
+            if (c >= P.size[k]) return false;
+            off -= c * stride[k];
+        }
+        return off == 0;
+    };
+    const int64_t slots = (int64_t)m.ta * m.tb / vec;           // 16-byte slots of the tile buffer
+    std::vector<int64_t> lds((size_t)(slots * vec));
+    std::vector<char> seen(p.num_tiles, 0);
+    int64_t written = 0;
+    const int loads = m.micro * vec;
+    for (uint32_t wg = 0; wg < p.grid; ++wg) {
+        const TileSeq seq = tile_sequence(p, wg);
+        for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
+            const uint32_t tile = tile_of(seq, q);
+            if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
+            seen[tile] = 1;
+            const MicroTile t = micro_tile(p, tile);
+            if (t.lim_a < 1 || t.lim_b < 1 || t.lim_a % vec || t.lim_b % vec) return TTC_ERR_INTERNAL;
+            std::fill(lds.begin(), lds.end(), (int64_t)-1);
+            for (int j = 0; j < vec; ++j)                         // lanes outside load the tile's first vector
+                if (!inside(t.a + j, P.stride_a, false) || !inside(t.b + j, P.stride_b, true)) return TTC_ERR_INTERNAL;
+            for (uint32_t tid = 0; tid < threads; ++tid)
+                for (int k = 0; k < loads; ++k) {
+                    const MicroLoad x = micro_load(m, threads, tid, (uint32_t)k);
+                    if (x.chunk >= (uint64_t)slots) return TTC_ERR_INTERNAL;
+                    const bool ok = x.row < t.lim_b && x.col < t.lim_a;
+                    for (int j = 0; j < vec; ++j) {
+                        int64_t src = -2;                         // parked by a lane outside the tensor: must never be read
+                        if (ok) {
+                            src = t.a + (int64_t)x.row * m.stride_a_p0 + x.col + j;
+                            if (!inside(src, P.stride_a, false)) return TTC_ERR_INTERNAL;
+                        }
+                        if (lds[(size_t)x.chunk * vec + j] != -1) return TTC_ERR_INTERNAL;       // every slot has one writer
+                        lds[(size_t)x.chunk * vec + j] = src;
+                    }
+                }
+            for (uint32_t tid = 0; tid < threads; ++tid)
+                for (int b = 0; b < m.micro; ++b) {
+                    const MicroBlock x = micro_block(m, threads, tid, (uint32_t)b);
+                    if (!(x.row < t.lim_b && x.col < t.lim_a)) continue;
+                    for (int i = 0; i < vec; ++i) {
+                        const uint64_t chunk = (uint64_t)x.chunk + (uint64_t)i * (1u << m.la_log);
+                        if (chunk >= (uint64_t)slots) return TTC_ERR_INTERNAL;
+                        for (int j = 0; j < vec; ++j) {
+                            const int64_t src = lds[(size_t)chunk * vec + j];
+                            const int64_t dst = t.b + (int64_t)(x.col + j) * m.stride_b_0 + x.row + i;
+                            // what sits in the slot must be the element of the tile at (row + i, col + j)
+                            if (src != t.a + (int64_t)(x.row + i) * m.stride_a_p0 + x.col + j) return TTC_ERR_INTERNAL;
+                            if (!inside(dst, P.stride_b, true) || b_from_a[dst] != -1) return TTC_ERR_INTERNAL;
+                            b_from_a[dst] = src;
+                            ++written;
+                        }
+                    }
+                }
+        }
+    }
+    return written == P.elements ? TTC_OK : TTC_ERR_INTERNAL;
+}
+
 static int emulate_map(ttc_plan_t plan, int64_t* b_from_a)
 {
     using namespace ttc;
     const Problem& P = plan->prob;
     const Candidate& C = plan->cands[plan->selected];
     if (C.kernel_class == TTC_KERNEL_ROWS) return emulate_rows(P, C, b_from_a);
+    if (C.kernel_class == TTC_KERNEL_MICRO) return emulate_micro(P, C, b_from_a);
     KernelParams p = C.kp;
     set_grid(&p, launch_grid(C, 256));
     const int32_t eba = P.eb_a, ebb = P.eb_b;

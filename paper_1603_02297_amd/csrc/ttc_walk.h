@@ -174,6 +174,53 @@ TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
     return r;
 }
 
+// ---- micro-tile kernel -----------------------------------------------------------------------
+// Where a tile lies and how much of it is inside the tensor along its two indices (multiples of the vector:
+// the kernel is only planned for extents that are).
+struct MicroTile { int64_t a, b; uint32_t lim_a, lim_b; };
+
+TTC_HD MicroTile micro_tile(const KernelParams& p, uint32_t tile)
+{
+    const MicroParams& m = p.micro;
+    const TileBase t = tile_base(p, tile);
+    const int64_t oa = (int64_t)fdigit(tile, p.tile_below[0], p.tile_cnt[0]) * m.ta;
+    const int64_t ob = (int64_t)fdigit(tile, p.tile_below[m.p0], p.tile_cnt[m.p0]) * m.tb;
+    MicroTile r;
+    r.a = t.a; r.b = t.b;
+    r.lim_a = (uint32_t)(m.size_a0 - oa < (int64_t)m.ta ? m.size_a0 - oa : (int64_t)m.ta);
+    r.lim_b = (uint32_t)(m.size_p0 - ob < (int64_t)m.tb ? m.size_p0 - ob : (int64_t)m.tb);
+    return r;
+}
+
+// Load walk: vector k of lane `tid`.  row runs along A's index p0 (B's stride-1 index), col along A's index 0;
+// chunk is the 16-byte slot of the LDS tile the vector is parked in.
+struct MicroLoad { uint32_t row, col, chunk; };
+
+TTC_HD MicroLoad micro_load(const MicroParams& m, uint32_t threads, uint32_t tid, uint32_t k)
+{
+    const uint32_t lane_a = tid & ((1u << m.la_log) - 1u);
+    MicroLoad r;
+    r.row = (tid >> m.la_log) + k * (threads >> m.la_log);
+    r.col = lane_a << m.vec_log;
+    r.chunk = (r.row << m.la_log) + (lane_a ^ ((r.row >> m.vec_log) & 7u));
+    return r;
+}
+
+// Store walk: block b of lane `tid`: vec rows x vec columns starting at (row, col); row i of the block sits in
+// LDS slot chunk + i * (ta / vec).
+struct MicroBlock { uint32_t row, col, chunk; };
+
+TTC_HD MicroBlock micro_block(const MicroParams& m, uint32_t threads, uint32_t tid, uint32_t b)
+{
+    const uint32_t lane_r = tid & ((1u << m.lb_log) - 1u);
+    const uint32_t lane_c = (tid >> m.lb_log) + b * (threads >> m.lb_log);
+    MicroBlock r;
+    r.row = lane_r << m.vec_log;
+    r.col = lane_c << m.vec_log;
+    r.chunk = (r.row << m.la_log) + (lane_c ^ (lane_r & 7u));
+    return r;
+}
+
 // ---- lane entry ------------------------------------------------------------------------------
 // Offsets are in BYTES.  A walk has three element sizes: of the tensor it follows (g), of B in
 // the direct kernel (g2), and of the LDS tile, which holds elements of A (l).

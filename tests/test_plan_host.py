@@ -144,8 +144,10 @@ def test_case_split_on_the_benchmark_cases():
         fixed = (i["perm"][0] == 0)
         assert i["stride1_fixed"] == int(fixed)
         assert fixed == (c.perm == (0, 2, 1))
-        if not fixed:
-            assert i["kernel_class"] == ttc.TTC_KERNEL_LDS
+        if fixed:
+            assert i["kernel_class"] == ttc.TTC_KERNEL_ROWS          # 1536-byte rows: gathered whole
+        else:
+            assert i["kernel_class"] in (ttc.TTC_KERNEL_LDS, ttc.TTC_KERNEL_MICRO)     # both stage the tile through LDS
         assert i["bytes_moved"] == c.traffic_bytes
         assert i["lds_bytes"] <= 160 * 1024
         assert 0 < i["candidate_count"]
