@@ -192,15 +192,16 @@ def main() -> int:
         b_ptrs = [t.data_ptr() for t in B_dev]
         reps = K if nbytes > 64e6 else max(K, 10 * npairs)       # microsecond launches: more of them per timing
         # ceilings of the same byte size, measured the same way, next to the case
-        ck = ttc.ttc_time_ceiling(0, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-        cm = ttc.ttc_time_ceiling(1, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-        cs = ttc.ttc_time_ceiling(3, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-        co = ttc.ttc_time_ceiling(4, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-        copy_k, copy_m, copy_s, copy_o = (2 * nbytes / t / 1e6 for t in (ck, cm, cs, co))
+        cbytes = nbytes - nbytes % 16                            # the copy helpers move whole 16-byte units
+        ck = ttc.ttc_time_ceiling(0, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+        cm = ttc.ttc_time_ceiling(1, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+        cs = ttc.ttc_time_ceiling(3, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+        co = ttc.ttc_time_ceiling(4, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+        copy_k, copy_m, copy_s, copy_o = (2 * cbytes / t / 1e6 for t in (ck, cm, cs, co))
         axpby = None
         if not c.beta_is_zero:
-            cx = ttc.ttc_time_ceiling(2, nbytes, a_ptrs, b_ptrs, stream, W, reps)
-            axpby = 3 * nbytes / cx / 1e6
+            cx = ttc.ttc_time_ceiling(2, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+            axpby = 3 * cbytes / cx / 1e6
             for t in B_dev:                                      # the axpby ceiling changed B
                 t.copy_(torch.from_numpy(B_host))
         d2d = max(copy_k, copy_m, copy_s, copy_o)   # the fastest known way to copy is the ceiling

@@ -226,8 +226,27 @@ static int tune_pairs(ttc_plan_t plan, int npairs, const void* const* A_list, vo
     }
     const int reps1 = std::min(40, std::max(3, (int)std::ceil(0.2f / unit)));
     const int reps2 = std::min(200, std::max(12, (int)std::ceil(1.0f / unit)));
+    // What is timed: the `cap` best-ranked candidates; a fifth of the places goes to the best-ranked micro-tile
+    // candidates where the ranking would have left them out (the two families are ranked by separate models,
+    // each good at ordering its own family and only roughly calibrated against the other)
+    std::vector<int> chosen;
+    for (int i = 0; i < cap; ++i) chosen.push_back(i);
+    if (cap >= 10 && cap < total) {
+        std::vector<int> extra;
+        int micro_seen = 0;
+        for (int i = 0; i < total && micro_seen < cap / 5; ++i)
+            if (plan->cands[i].kernel_class == TTC_KERNEL_MICRO) {
+                ++micro_seen;
+                if (i >= cap) extra.push_back(i);
+            }
+        for (int k = cap - 1; k >= 1 && !extra.empty(); --k)
+            if (plan->cands[chosen[k]].kernel_class != TTC_KERNEL_MICRO) {
+                chosen[k] = extra.back();
+                extra.pop_back();
+            }
+    }
     std::vector<std::pair<float, int>> timed;
-    for (int i = 0; i < cap; ++i) {
+    for (int i : chosen) {
         float ms = 0.f;
         const int st1 = time_one(plan->cands[i], 1, reps1, &ms);
         if (st1 != TTC_OK) return st1;

@@ -76,16 +76,18 @@ struct Slot {
 // The micro-tile kernel: a tile spans A's stride-1 index (index 0, extent ta inside the tile) and B's stride-1 index
 // (A's index p0, extent tb) and nothing else.  Lanes load 16-byte vectors along index 0 and park them in LDS with
 // one 128-bit write; after the barrier a lane reads the vec x vec block it owns with vec 128-bit reads, transposes
-// it in registers and stores vec 16-byte vectors along B's stride-1 index.  Rows of the LDS tile are ta elements
-// long (a multiple of eight 16-byte chunks); chunk c of row r sits at chunk position c ^ ((r / vec) & 7), which
+// it in registers and stores vec 16-byte vectors along B's stride-1 index.  Rows of the LDS tile are `pitch`
+// 16-byte chunks long (a multiple of eight); chunk c of row r sits at chunk position c ^ ((r / vec) & 7), which
 // makes both the writes (lanes along c) and the reads (lanes along r in steps of vec) free of bank conflicts.
 struct MicroParams {
-    int32_t  ta, tb;                 // tile extents: along A's index 0, along A's index p0
+    int32_t  ta, tb;                 // tile extents: along A's index 0, along A's index p0 (multiples of vec)
     int32_t  p0;                     // the index of A that is B's stride-1 index
-    int32_t  vec;                    // elements in 16 bytes
-    int32_t  la_log, lb_log;         // log2 of ta / vec and of tb / vec (both at least 3)
-    int32_t  micro;                  // vec x vec blocks a lane owns = ta * tb / (threads * vec * vec): 1 or 2
-    int32_t  vec_log;                // log2 of vec
+    int32_t  vec, vec_log;           // elements in 16 bytes, and its log2
+    int32_t  la, lb;                 // ta / vec and tb / vec: vectors per row of the tile, blocks per column (each at least 8)
+    int32_t  pitch;                  // 16-byte chunks per row of the LDS tile: la rounded up to a multiple of 8
+    int32_t  loads;                  // vectors a lane loads per tile: ceil(la * tb / threads)
+    int32_t  blocks;                 // vec x vec blocks a lane owns: ceil(la * lb / threads)
+    FastDiv  la_div, lb_div;
     int64_t  size_a0, size_p0;       // extents of the two indices
     int64_t  stride_a_p0;            // element stride of index p0 in A
     int64_t  stride_b_0;             // element stride of index 0 in B

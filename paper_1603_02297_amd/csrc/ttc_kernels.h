@@ -402,7 +402,7 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
 // quad, column j is element j of each -- and stores V 16-byte vectors along B's stride-1 index.
 // Planned only where both extents are multiples of V and both tensors have one element type.
 // ---------------------------------------------------------------------------------
-template <typename T, int MODE, int V, int M>
+template <typename T, int MODE, int V>
 __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by_value, const T* __restrict__ A, T* __restrict__ B)
 {
     static_assert(V * sizeof(T) == 16, "one 16-byte vector");
@@ -410,13 +410,14 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
     extern __shared__ __align__(16) unsigned char smem[];
     typedef uint32_t Quad __attribute__((ext_vector_type(4)));
     Quad* lds = reinterpret_cast<Quad*>(smem);
-    constexpr int N = M * V;                                   // vectors a lane loads, and stores, per tile
+    constexpr int U = 4;                                       // loads a lane keeps in flight
     constexpr int32_t kScale = (int32_t)sizeof(T);
     const MicroParams& m = p.micro;
     const Epilogue<T, T, MODE> epi(p.alpha, p.beta);
     const uint32_t tid = threadIdx.x, threads = blockDim.x;
     const int64_t row_a = m.stride_a_p0 * kScale, col_b = m.stride_b_0 * kScale;      // bytes
-    const uint32_t row_chunks = 1u << m.la_log;
+    const uint32_t pitch = (uint32_t)m.pitch;
+    const uint32_t loads = (uint32_t)m.loads, blocks = (uint32_t)m.blocks;
     const TileSeq seq = tile_sequence(p, blockIdx.x);
     for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
         const MicroTile t = micro_tile(p, tile_of(seq, q));
@@ -424,33 +425,39 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
         unsigned char* Bt = reinterpret_cast<unsigned char*>(B + t.b);
         auto run = [&](auto stream_a, auto stream_b) {
             constexpr bool NTA = decltype(stream_a)::value, NTB = decltype(stream_b)::value;
-            // ---- A order: global -> LDS.  A lane outside the tensor loads the tile's first vector instead
-            // (no load in divergent control flow) and parks it in its own slot, which nobody reads.
             union Vec { Pack<T, V> p; Quad q; };
-            Vec in[N];
+            // ---- A order: global -> LDS, U vectors at a time.  A lane whose vector lies outside the tensor loads the
+            // tile's first vector instead (no load in divergent control flow); what it parks nobody reads.
+            for (uint32_t k0 = 0; k0 < loads; k0 += U) {
+                Vec in[U];
+                MicroLoad x[U];
 #pragma unroll
-            for (int k = 0; k < N; ++k) {
-                const MicroLoad x = micro_load(m, threads, tid, (uint32_t)k);
-                const bool ok = x.row < t.lim_b && x.col < t.lim_a;
-                in[k].p = load_pack<T, V, NTA>(At, ok ? (int64_t)x.row * row_a + (int64_t)x.col * kScale : 0);
+                for (int u = 0; u < U; ++u) {
+                    x[u] = micro_load(m, threads, tid, k0 + (uint32_t)u);
+                    const bool ok = x[u].valid && x[u].row < t.lim_b && x[u].col < t.lim_a;
+                    const uint32_t col = micro_back(x[u].col, t.lim_a, V);
+                    in[u].p = load_pack<T, V, NTA>(At, ok ? (int64_t)x[u].row * row_a + (int64_t)col * kScale : 0);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (x[u].valid) lds[x[u].chunk] = in[u].q;
             }
-#pragma unroll
-            for (int k = 0; k < N; ++k) lds[micro_load(m, threads, tid, (uint32_t)k).chunk] = in[k].q;
             __syncthreads();
             // ---- B order: LDS -> registers (V x V block) -> epilogue -> global
-#pragma unroll
-            for (int b = 0; b < M; ++b) {
-                const MicroBlock x = micro_block(m, threads, tid, (uint32_t)b);
-                const bool ok = x.row < t.lim_b && x.col < t.lim_a;
-                const int64_t to = (int64_t)x.col * col_b + (int64_t)x.row * kScale;
+            for (uint32_t b = 0; b < blocks; ++b) {
+                const MicroBlock x = micro_block(m, threads, tid, b);
+                const bool ok = x.valid && x.row < t.lim_b && x.col < t.lim_a;
+                const uint32_t row = ok ? micro_back(x.row, t.lim_b, V) : 0u, col = ok ? micro_back(x.col, t.lim_a, V) : 0u;
+                const uint32_t lane_c = ok ? x.lane_c : 0u;
+                const int64_t to = (int64_t)col * col_b + (int64_t)row * kScale;
                 Pack<T, V> old[V];
                 if (MODE == TTC_EPI_AXPBY) {
 #pragma unroll
-                    for (int j = 0; j < V; ++j) old[j] = load_pack<T, V, NTB>(Bt, ok ? to + j * col_b : 0);
+                    for (int j = 0; j < V; ++j) old[j] = load_pack<T, V, NTB>(Bt, to + j * col_b);
                 }
                 Vec blk[V];
 #pragma unroll
-                for (int i = 0; i < V; ++i) blk[i].q = lds[x.chunk + (uint32_t)i * row_chunks];
+                for (int i = 0; i < V; ++i) blk[i].q = lds[micro_slot(m, row + (uint32_t)i, lane_c)];
                 if (ok) {
 #pragma unroll
                     for (int j = 0; j < V; ++j) {
@@ -472,30 +479,28 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
     }
 }
 
-template <typename T, int MODE, int V, int M>
-inline hipError_t launch_micro_blocks(const Candidate& c, const void* A, void* B, hipStream_t stream)
-{
-    const KernelParams& kp = c.kp;
-    const MicroParams& m = kp.micro;
-    const uint32_t grid = kp.num_tiles;                        // one tile per workgroup: the hardware deals them
-    if (m.vec != V || m.micro != M || c.threads < 64 || c.threads > 256 || (c.threads & (c.threads - 1)) ||
-        (int64_t)m.ta * m.tb != (int64_t)c.threads * V * V * M || m.ta != (V << m.la_log) || m.tb != (V << m.lb_log) ||
-        m.la_log < 3 || m.lb_log < 3 || (1 << m.la_log) > c.threads || (1 << m.lb_log) > c.threads ||
-        c.lds_bytes != m.ta * m.tb * (int)sizeof(T) || grid < 1 || grid != kp.grid) return hipErrorInvalidValue;
-    const void* fn = reinterpret_cast<const void*>(&micro_kernel<T, MODE, V, M>);
-    const T* a = static_cast<const T*>(A);
-    T* b = static_cast<T*>(B);
-    void* args[] = {const_cast<KernelParams*>(&kp), &a, &b};
-    return hipLaunchKernel(fn, dim3(grid), dim3(c.threads), args, (size_t)c.lds_bytes, stream);
-}
-
 template <typename TA, typename TB, int MODE>
 inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipStream_t stream)
 {
     if constexpr (std::is_same<TA, TB>::value && (sizeof(TA) == 4 || sizeof(TA) == 8)) {
         constexpr int V = 16 / (int)sizeof(TA);
-        if (c.kp.micro.micro == 1) return launch_micro_blocks<TA, MODE, V, 1>(c, A, B, stream);
-        if (c.kp.micro.micro == 2) return launch_micro_blocks<TA, MODE, V, 2>(c, A, B, stream);
+        const KernelParams& kp = c.kp;
+        const MicroParams& m = kp.micro;
+        const uint32_t grid = kp.num_tiles;                    // one tile per workgroup: the hardware deals them
+        const int64_t th = c.threads;
+        if (m.vec != V || (1 << m.vec_log) != V || (th != 64 && th != 128 && th != 256) || m.la < 1 || m.lb < 1 ||
+            m.ta != m.la * V || m.tb != m.lb * V || m.pitch < m.la || (m.pitch & 7) || m.la_div.div != (uint32_t)m.la ||
+            m.lb_div.div != (uint32_t)m.lb || (int64_t)m.loads * th < (int64_t)m.la * m.tb || (int64_t)m.blocks * th < (int64_t)m.la * m.lb ||
+            (int64_t)(m.loads + 4) * th >= (int64_t(1) << 31) ||
+            c.lds_bytes != m.tb * m.pitch * 16 || c.lds_bytes > 64 * 1024 || grid < 1 || grid != kp.grid ||
+            m.size_a0 < V || m.size_p0 < V ||
+            (MODE == TTC_EPI_AXPBY && (m.size_a0 % V != 0 || m.size_p0 % V != 0)))     // doubly written elements would race with their own read
+            return hipErrorInvalidValue;
+        const void* fn = reinterpret_cast<const void*>(&micro_kernel<TA, MODE, V>);
+        const TA* a = static_cast<const TA*>(A);
+        TA* b = static_cast<TA*>(B);
+        void* args[] = {const_cast<KernelParams*>(&kp), &a, &b};
+        return hipLaunchKernel(fn, dim3(grid), dim3(c.threads), args, (size_t)c.lds_bytes, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -700,30 +700,28 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
 }
 
 // The micro-tile kernel's candidate: a tile of ta x tb elements over A's index 0 and B's stride-1 index p0.
-// Needs one element type of 4 or 8 bytes on both sides, both indices contiguous in their tensor and both extents
-// multiples of the 16-byte vector, ta / vec and tb / vec powers of two of at least 8, and ta * tb = threads * vec^2
-// * (1 or 2).
+// Needs one element type of 4 or 8 bytes on both sides, both indices contiguous in their tensor and at least one
+// 16-byte vector long, ta and tb multiples of the vector, a tile of at most 64 KB.  Extents that are not multiples
+// of the vector make some elements be written twice, which an update of B (beta != 0) cannot have.
 static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, const int* tile_order, Candidate* out)
 {
     if (P.ndim < 2 || P.perm[0] == 0 || P.kind_a != P.kind_b || (P.eb_a != 4 && P.eb_a != 8)) return false;
     const int p0 = P.perm[0], vec = 16 / P.eb_a;
     if (P.stride_a[0] != 1 || P.stride_b[p0] != 1) return false;
-    if (P.size[0] % vec != 0 || P.size[p0] % vec != 0 || ta % vec != 0 || tb % vec != 0) return false;
+    if (P.size[0] < vec || P.size[p0] < vec || ta % vec != 0 || tb % vec != 0 || ta < vec || tb < vec) return false;
+    const bool whole = P.size[0] % vec == 0 && P.size[p0] % vec == 0;
+    if (!whole && P.epilogue == TTC_EPI_AXPBY) return false;
     const int la = ta / vec, lb = tb / vec;
-    auto log2_exact = [](int x) { int l = 0; while ((1 << l) < x) ++l; return (1 << l) == x ? l : -1; };
-    const int la_log = log2_exact(la), lb_log = log2_exact(lb);
-    if (la_log < 3 || lb_log < 3 || la > threads || lb > threads) return false;
-    const int64_t blocks = (int64_t)la * lb;
-    if (blocks % threads != 0) return false;
-    const int micro = (int)(blocks / threads);
-    if (micro != 1 && micro != 2) return false;
+    const int pitch = (la + 7) / 8 * 8;
+    if ((int64_t)tb * pitch * 16 > 64 * 1024) return false;
+    const int loads = (int)ceil_div((int64_t)la * tb, threads), blocks = (int)ceil_div((int64_t)la * lb, threads);
+    if (blocks > 8) return false;
     Candidate C;
     std::memset(&C, 0, sizeof(C));
     C.kernel_class = TTC_KERNEL_MICRO;
     C.threads = threads;
     C.wg_per_cu = 0;                   // one tile per workgroup
-    C.lds_bytes = ta * tb * P.eb_a;
-    if (C.lds_bytes > kMaxLdsBytes) return false;
+    C.lds_bytes = tb * pitch * 16;
     KernelParams& kp = C.kp;
     kp.n = P.ndim;
     int64_t ntiles = 1;
@@ -760,7 +758,8 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     }
     MicroParams& m = kp.micro;
     m.ta = ta; m.tb = tb; m.p0 = p0; m.vec = vec;
-    m.la_log = la_log; m.lb_log = lb_log; m.micro = micro;
+    m.la = la; m.lb = lb; m.pitch = pitch; m.loads = loads; m.blocks = blocks;
+    m.la_div = make_fastdiv((uint32_t)la); m.lb_div = make_fastdiv((uint32_t)lb);
     m.vec_log = (vec == 4) ? 2 : 1;
     m.size_a0 = P.size[0]; m.size_p0 = P.size[p0];
     m.stride_a_p0 = P.stride_a[p0];
@@ -770,7 +769,7 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     C.dtile_b[0] = tb; C.dtile_b[1] = ta; C.dlane_b[0] = std::min(tb, kWave * vec); C.dlane_b[1] = std::max(1, kWave / lb) * vec;
     C.lds_conflict_a = C.lds_conflict_b = 2;       // conflict-free by construction (the value the bank model gives such a layout)
     C.lds_stride[0] = 1;
-    C.lds_stride[p0] = ta;
+    C.lds_stride[p0] = pitch * vec;
     *out = C;
     return true;
 }
@@ -979,7 +978,7 @@ static double micro_cost(const Problem& P, const Candidate& C)
     e += 0.03 * oct_below(run_a, 256.0) + 0.03 * oct_below(run_b, 256.0);
     double padded = ((double)ceil_div(P.size[0], m.ta) * m.ta / (double)P.size[0]) *
                     ((double)ceil_div(P.size[m.p0], m.tb) * m.tb / (double)P.size[m.p0]);
-    e += 0.45 * (padded - 1.0);                                          // whole workgroups idle in the remainder tiles
+    e += 0.12 * (padded - 1.0);                                          // idle lanes in the remainder tiles (85^4: tiles of 32 x 128, 1.7 times the tensor, run 8 % ahead of the best box)
     const int64_t line = 128 / P.eb_a;
     if (P.size[0] % line != 0) e += 0.05;                                // runs of A start inside lines
     if (P.size[m.p0] % line != 0) e += 0.05;
@@ -1249,16 +1248,32 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
         }
     }
 
-    // -- the micro-tile kernel: a tile over the two stride-1 indices, where both extents are whole vectors
+    // -- the micro-tile kernel: a tile over the two stride-1 indices.  Tile extents in vectors: powers of two, and
+    // the divisors of the extent (no remainder tiles)
     if (!stride1_fixed && n >= 2) {
         const int vec = std::max(1, 16 / P.eb_a);
-        for (int threads : {256, 128, 64})
-            for (int la = 8; la <= threads; la *= 2)
-                for (int lb = 8; lb <= threads; lb *= 2)
+        auto extents = [&](int64_t size, std::vector<int>* v) {
+            const int64_t whole = size / vec;
+            for (int l = 8; l <= 64; l *= 2) if (l <= 2 * whole) v->push_back(l);
+            if (size % vec == 0)
+                for (int l = 6; l <= 96; ++l)
+                    if (whole % l == 0 && (l & (l - 1)) != 0) v->push_back(l);
+            if (whole >= 1 && whole < 8) v->push_back((int)ceil_div(size, vec));
+        };
+        std::vector<int> las, lbs;
+        extents(P.size[0], &las);
+        extents(P.size[P.perm[0]], &lbs);
+        for (int threads : {256, 128, 64}) {
+            for (int la : las)
+                for (int lb : lbs) {
+                    const int64_t blocks = ceil_div((int64_t)la * lb, threads);
+                    if (blocks > 6 || (int64_t)la * lb * 5 < blocks * threads * 4) continue;      // lanes mostly busy
                     for (int o = 0; o < (quick ? 1 : 2); ++o) {
                         Candidate c;
                         if (make_micro_candidate(P, la * vec, lb * vec, threads, orders[o], &c)) add_candidate(P, out, c);
                     }
+                }
+        }
     }
 
     // -- staged candidates: a box spanning the leading indices of A and of B
@@ -1493,7 +1508,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
-    out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : (C.kernel_class == TTC_KERNEL_MICRO ? C.kp.micro.micro : 0);
+    out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : (C.kernel_class == TTC_KERNEL_MICRO ? C.kp.micro.blocks : 0);
     return TTC_OK;
     });
 }
@@ -1612,15 +1627,17 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
     for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
     const uint32_t threads = (uint32_t)C.threads;
     const int vec = m.vec;
-    if ((vec != 2 && vec != 4) || vec * P.eb_a != 16 || P.eb_a != P.eb_b || (m.micro != 1 && m.micro != 2) ||
-        (threads != 64 && threads != 128 && threads != 256) || m.ta != (vec << m.la_log) || m.tb != (vec << m.lb_log) ||
-        m.la_log < 3 || m.lb_log < 3 || (int64_t)m.ta * m.tb != (int64_t)threads * vec * vec * m.micro ||
-        (1u << m.la_log) > threads || (1u << m.lb_log) > threads || (1 << m.vec_log) != vec ||
-        C.lds_bytes != m.ta * m.tb * P.eb_a || C.lds_bytes > kMaxLdsBytes || p.grid != p.num_tiles ||
+    if ((vec != 2 && vec != 4) || vec * P.eb_a != 16 || P.eb_a != P.eb_b ||
+        (threads != 64 && threads != 128 && threads != 256) || m.ta != vec * m.la || m.tb != vec * m.lb ||
+        m.la < 1 || m.lb < 1 || m.pitch < m.la || (m.pitch & 7) || m.la_div.div != (uint32_t)m.la || m.lb_div.div != (uint32_t)m.lb ||
+        (int64_t)m.loads * threads < (int64_t)m.la * m.tb || (int64_t)m.blocks * threads < (int64_t)m.la * m.lb ||
+        (1 << m.vec_log) != vec || C.lds_bytes != m.tb * m.pitch * 16 || C.lds_bytes > 64 * 1024 || p.grid != p.num_tiles ||
         m.p0 != P.perm[0] || m.p0 == 0 || m.size_a0 != P.size[0] || m.size_p0 != P.size[m.p0] ||
         m.stride_a_p0 != P.stride_a[m.p0] || m.stride_b_0 != P.stride_b[0] || P.stride_a[0] != 1 || P.stride_b[m.p0] != 1 ||
-        P.size[0] % vec != 0 || P.size[m.p0] % vec != 0)
+        P.size[0] < vec || P.size[m.p0] < vec)
         return TTC_ERR_INTERNAL;
+    const bool whole = P.size[0] % vec == 0 && P.size[m.p0] % vec == 0;      // else some elements are written twice
+    if (!whole && P.epilogue == TTC_EPI_AXPBY) return TTC_ERR_INTERNAL;
     auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
         if (off < 0) return false;
         for (int i = P.ndim - 1; i >= 0; --i) {
@@ -1631,11 +1648,10 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
         }
         return off == 0;
     };
-    const int64_t slots = (int64_t)m.ta * m.tb / vec;           // 16-byte slots of the tile buffer
+    const int64_t slots = (int64_t)m.tb * m.pitch;              // 16-byte slots of the tile buffer
     std::vector<int64_t> lds((size_t)(slots * vec));
     std::vector<char> seen(p.num_tiles, 0);
     int64_t written = 0;
-    const int loads = m.micro * vec;
     for (uint32_t wg = 0; wg < p.grid; ++wg) {
         const TileSeq seq = tile_sequence(p, wg);
         for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
@@ -1643,19 +1659,24 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
             if (tile >= p.num_tiles || seen[tile]) return TTC_ERR_INTERNAL;
             seen[tile] = 1;
             const MicroTile t = micro_tile(p, tile);
-            if (t.lim_a < 1 || t.lim_b < 1 || t.lim_a % vec || t.lim_b % vec) return TTC_ERR_INTERNAL;
+            if (t.lim_a < (uint32_t)vec || t.lim_b < (uint32_t)vec || t.lim_a > (uint32_t)m.ta || t.lim_b > (uint32_t)m.tb) return TTC_ERR_INTERNAL;
+            if (whole && (t.lim_a % vec || t.lim_b % vec)) return TTC_ERR_INTERNAL;
             std::fill(lds.begin(), lds.end(), (int64_t)-1);
-            for (int j = 0; j < vec; ++j)                         // lanes outside load the tile's first vector
-                if (!inside(t.a + j, P.stride_a, false) || !inside(t.b + j, P.stride_b, true)) return TTC_ERR_INTERNAL;
+            for (int i = 0; i < vec; ++i)                         // lanes outside load the tile's first vector or block
+                for (int j = 0; j < vec; ++j)
+                    if (!inside(t.a + i * m.stride_a_p0 + j, P.stride_a, false) || !inside(t.b + j * m.stride_b_0 + i, P.stride_b, true))
+                        return TTC_ERR_INTERNAL;
             for (uint32_t tid = 0; tid < threads; ++tid)
-                for (int k = 0; k < loads; ++k) {
+                for (int k = 0; k < (m.loads + 3) / 4 * 4; ++k) { // the kernel walks its loads four at a time
                     const MicroLoad x = micro_load(m, threads, tid, (uint32_t)k);
+                    if (!x.valid) continue;
                     if (x.chunk >= (uint64_t)slots) return TTC_ERR_INTERNAL;
                     const bool ok = x.row < t.lim_b && x.col < t.lim_a;
+                    const uint32_t col = ok ? micro_back(x.col, t.lim_a, (uint32_t)vec) : 0u;
                     for (int j = 0; j < vec; ++j) {
                         int64_t src = -2;                         // parked by a lane outside the tensor: must never be read
                         if (ok) {
-                            src = t.a + (int64_t)x.row * m.stride_a_p0 + x.col + j;
+                            src = t.a + (int64_t)x.row * m.stride_a_p0 + col + j;
                             if (!inside(src, P.stride_a, false)) return TTC_ERR_INTERNAL;
                         }
                         if (lds[(size_t)x.chunk * vec + j] != -1) return TTC_ERR_INTERNAL;       // every slot has one writer
@@ -1663,20 +1684,22 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
                     }
                 }
             for (uint32_t tid = 0; tid < threads; ++tid)
-                for (int b = 0; b < m.micro; ++b) {
+                for (int b = 0; b < m.blocks; ++b) {
                     const MicroBlock x = micro_block(m, threads, tid, (uint32_t)b);
-                    if (!(x.row < t.lim_b && x.col < t.lim_a)) continue;
+                    if (!(x.valid && x.row < t.lim_b && x.col < t.lim_a)) continue;
+                    const uint32_t row = micro_back(x.row, t.lim_b, (uint32_t)vec), col = micro_back(x.col, t.lim_a, (uint32_t)vec);
                     for (int i = 0; i < vec; ++i) {
-                        const uint64_t chunk = (uint64_t)x.chunk + (uint64_t)i * (1u << m.la_log);
+                        const uint64_t chunk = micro_slot(m, row + (uint32_t)i, x.lane_c);
                         if (chunk >= (uint64_t)slots) return TTC_ERR_INTERNAL;
                         for (int j = 0; j < vec; ++j) {
                             const int64_t src = lds[(size_t)chunk * vec + j];
-                            const int64_t dst = t.b + (int64_t)(x.col + j) * m.stride_b_0 + x.row + i;
+                            const int64_t dst = t.b + (int64_t)(col + j) * m.stride_b_0 + row + i;
                             // what sits in the slot must be the element of the tile at (row + i, col + j)
-                            if (src != t.a + (int64_t)(x.row + i) * m.stride_a_p0 + x.col + j) return TTC_ERR_INTERNAL;
-                            if (!inside(dst, P.stride_b, true) || b_from_a[dst] != -1) return TTC_ERR_INTERNAL;
+                            if (src != t.a + (int64_t)(row + i) * m.stride_a_p0 + col + j) return TTC_ERR_INTERNAL;
+                            if (!inside(dst, P.stride_b, true)) return TTC_ERR_INTERNAL;
+                            if (b_from_a[dst] == -1) ++written;
+                            else if (whole || b_from_a[dst] != src) return TTC_ERR_INTERNAL;   // a second write brings the same element
                             b_from_a[dst] = src;
-                            ++written;
                         }
                     }
                 }

@@ -175,8 +175,9 @@ TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
 }
 
 // ---- micro-tile kernel -----------------------------------------------------------------------
-// Where a tile lies and how much of it is inside the tensor along its two indices (multiples of the vector:
-// the kernel is only planned for extents that are).
+// Where a tile lies and how much of it is inside the tensor along its two indices.  A remainder tile that holds
+// less than one vector along an index is moved back along it until it holds one (the elements it shares with its
+// neighbour are then written twice, with the same value), so lim_a and lim_b are at least vec.
 struct MicroTile { int64_t a, b; uint32_t lim_a, lim_b; };
 
 TTC_HD MicroTile micro_tile(const KernelParams& p, uint32_t tile)
@@ -185,39 +186,58 @@ TTC_HD MicroTile micro_tile(const KernelParams& p, uint32_t tile)
     const TileBase t = tile_base(p, tile);
     const int64_t oa = (int64_t)fdigit(tile, p.tile_below[0], p.tile_cnt[0]) * m.ta;
     const int64_t ob = (int64_t)fdigit(tile, p.tile_below[m.p0], p.tile_cnt[m.p0]) * m.tb;
+    int64_t lim_a = m.size_a0 - oa < (int64_t)m.ta ? m.size_a0 - oa : (int64_t)m.ta;
+    int64_t lim_b = m.size_p0 - ob < (int64_t)m.tb ? m.size_p0 - ob : (int64_t)m.tb;
+    const int64_t back_a = lim_a < m.vec ? m.vec - lim_a : 0, back_b = lim_b < m.vec ? m.vec - lim_b : 0;
     MicroTile r;
-    r.a = t.a; r.b = t.b;
-    r.lim_a = (uint32_t)(m.size_a0 - oa < (int64_t)m.ta ? m.size_a0 - oa : (int64_t)m.ta);
-    r.lim_b = (uint32_t)(m.size_p0 - ob < (int64_t)m.tb ? m.size_p0 - ob : (int64_t)m.tb);
+    r.a = t.a - back_a - back_b * m.stride_a_p0;
+    r.b = t.b - back_a * m.stride_b_0 - back_b;
+    r.lim_a = (uint32_t)(lim_a + back_a);
+    r.lim_b = (uint32_t)(lim_b + back_b);
     return r;
 }
 
-// Load walk: vector k of lane `tid`.  row runs along A's index p0 (B's stride-1 index), col along A's index 0;
-// chunk is the 16-byte slot of the LDS tile the vector is parked in.
-struct MicroLoad { uint32_t row, col, chunk; };
+// Where the vector (or block side) that nominally starts at x really starts in a tile holding lim (at least vec)
+// elements along that index: the last one is moved back so that it ends with the tile.  Both phases apply the same
+// rule, so the LDS slot of lane (row, lane_a) holds the same columns for its writer and its readers.
+TTC_HD uint32_t micro_back(uint32_t x, uint32_t lim, uint32_t vec) { return x + vec > lim ? lim - vec : x; }
+
+// The 16-byte LDS slot of row `row` of the tile, column group `lane_c`.
+TTC_HD uint32_t micro_slot(const MicroParams& m, uint32_t row, uint32_t lane_c)
+{
+    return row * (uint32_t)m.pitch + (lane_c ^ ((row >> m.vec_log) & 7u));
+}
+
+// Load walk: vector k of lane `tid` (vectors are numbered row by row, so consecutive lanes load consecutive
+// vectors of a row).  row runs along A's index p0 (B's stride-1 index), col along A's index 0; chunk is the
+// 16-byte slot of the LDS tile the vector is parked in.  valid: the vector is one of the tile's.
+struct MicroLoad { uint32_t row, col, chunk; bool valid; };
 
 TTC_HD MicroLoad micro_load(const MicroParams& m, uint32_t threads, uint32_t tid, uint32_t k)
 {
-    const uint32_t lane_a = tid & ((1u << m.la_log) - 1u);
+    const uint32_t g = tid + k * threads;
     MicroLoad r;
-    r.row = (tid >> m.la_log) + k * (threads >> m.la_log);
+    r.row = fdiv(g, m.la_div);
+    const uint32_t lane_a = g - r.row * (uint32_t)m.la;
     r.col = lane_a << m.vec_log;
-    r.chunk = (r.row << m.la_log) + (lane_a ^ ((r.row >> m.vec_log) & 7u));
+    r.chunk = micro_slot(m, r.row, lane_a);
+    r.valid = r.row < (uint32_t)m.tb;
     return r;
 }
 
-// Store walk: block b of lane `tid`: vec rows x vec columns starting at (row, col); row i of the block sits in
-// LDS slot chunk + i * (ta / vec).
-struct MicroBlock { uint32_t row, col, chunk; };
+// Store walk: block b of lane `tid` (blocks are numbered along B's stride-1 index first): vec rows x vec columns
+// nominally starting at (row, col).  Row r of the tile, column group lane_c, sits in LDS slot micro_slot(m, r, lane_c).
+struct MicroBlock { uint32_t row, col, lane_c; bool valid; };
 
 TTC_HD MicroBlock micro_block(const MicroParams& m, uint32_t threads, uint32_t tid, uint32_t b)
 {
-    const uint32_t lane_r = tid & ((1u << m.lb_log) - 1u);
-    const uint32_t lane_c = (tid >> m.lb_log) + b * (threads >> m.lb_log);
+    const uint32_t h = tid + b * threads;
     MicroBlock r;
+    r.lane_c = fdiv(h, m.lb_div);
+    const uint32_t lane_r = h - r.lane_c * (uint32_t)m.lb;
     r.row = lane_r << m.vec_log;
-    r.col = lane_c << m.vec_log;
-    r.chunk = (r.row << m.la_log) + (lane_c ^ (lane_r & 7u));
+    r.col = r.lane_c << m.vec_log;
+    r.valid = r.lane_c < (uint32_t)m.la;
     return r;
 }
 

@@ -191,8 +191,8 @@ def study_search(out, dump=None):
 def unpadded_ms(dtype, sizes, perm, alpha, beta, best_info, a_ptrs, b_ptrs, stream, tmp):
     """Time of the configuration `best_info` names when its LDS tile is laid out without pads, or None."""
     import os
-    if best_info["kernel_class"] == ttc.TTC_KERNEL_DIRECT:
-        return None
+    if best_info["kernel_class"] != ttc.TTC_KERNEL_LDS:
+        return None                              # no LDS tile, or (micro-tile kernel) one that is swizzled, not padded
     plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
     ttc.ttc_plan_select_candidate(plan, best_info["candidate_index"])
     ttc.ttc_plan_set_streaming(plan, best_info["nt_a"], best_info["nt_b"])
@@ -214,6 +214,9 @@ def unpadded_ms(dtype, sizes, perm, alpha, beta, best_info, a_ptrs, b_ptrs, stre
     return ms, info
 
 
+ONE_SHOT = (ttc.TTC_KERNEL_ROWS, ttc.TTC_KERNEL_MICRO)      # one tile (chunk) per workgroup: no workgroups-per-CU knob
+
+
 def ablations(rows):
     """Gain of searching each dimension: best time with the dimension at its default / best time overall."""
     ms = np.array([r[1] for r in rows])
@@ -229,8 +232,9 @@ def ablations(rows):
         "tile shape": best_where(lambda i: i["tile"] == first["tile"] and i["kernel_class"] == first["kernel_class"]),
         "vector width": best_where(lambda i: i["vec_a"] == 1 and i["vec_b"] == 1),
         "tile order": best_where(lambda i: i["tile_order"] == i["perm"]),
-        "LDS buffering": best_where(lambda i: i["kernel_class"] == ttc.TTC_KERNEL_DIRECT or i["lds_buffers"] == 2),
-        "launch shape": best_where(lambda i: i["threads"] == 256 and i["wg_per_cu"] == 16),
+        "LDS buffering": best_where(lambda i: i["kernel_class"] != ttc.TTC_KERNEL_LDS or i["lds_buffers"] == 2),
+        "launch shape": best_where(lambda i: i["threads"] == 256 and (i["wg_per_cu"] == 16 or i["kernel_class"] in ONE_SHOT)),
+        "kernel family": best_where(lambda i: i["kernel_class"] in (ttc.TTC_KERNEL_LDS, ttc.TTC_KERNEL_DIRECT)),
     }
 
 
@@ -297,7 +301,8 @@ def study_sweep(out, limit=None, dump=None):
     held = {"tile shape": "tile of the heuristic's first candidate", "vector width": "one element per lane",
             "tile order": "tiles numbered in B's index order", "LDS buffering": "two tile buffers",
             "launch shape": "256 threads, 16 workgroups per CU",
-            "LDS pads": "the best configuration with an unpadded LDS tile"}
+            "LDS pads": "the best configuration with an unpadded LDS tile",
+            "kernel family": "box kernels only (no row kernel, no micro-tile kernel)"}
     for name in held:
         g = [r["abl"][name] - 1.0 for r in results if r["abl"][name] == r["abl"][name]]
         if g:
@@ -385,7 +390,7 @@ def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
         with (gzip.open(path, "rt") if path.endswith(".gz") else open(path)) as fh:
             for line in fh:
                 d = json.loads(line)
-                d["rows"] = [r for r in d["rows"] if r["kernel_class"] != ttc.TTC_KERNEL_ROWS]
+                d["rows"] = [r for r in d["rows"] if r["kernel_class"] not in ONE_SHOT]
                 if d["rows"]:
                     data.append(d)
     names, X, y, grp = None, [], [], []

@@ -164,7 +164,8 @@ def test_candidates_are_ranked_and_have_a_scalar_fallback():
         scalar |= (i["vec_a"] == 1 and i["vec_b"] == 1)
         assert i["tile"][0] % i["vec_a"] == 0 and i["tile"][i["perm"][0]] % i["vec_b"] == 0
     assert scalar
-    assert costs[:-1] == sorted(costs[:-1])       # the appended fallback may sit out of order
+    # candidate 0 is the one the plan was created with (the best of a short list); the appended fallback may sit out of order
+    assert costs[1:-1] == sorted(costs[1:-1]) and costs[0] <= 1.25 * costs[1]
     with pytest.raises(ttc.TtcError):
         ttc.ttc_plan_select_candidate(p, n)
     ttc.ttc_plan_destroy(p)
@@ -213,6 +214,41 @@ def test_walks_all_perms_small_odd_extents(n):
 ])
 def test_walks_shapes_with_tails(dtype, sizes, perm):
     check_all_candidates(dtype, sizes, perm, max_candidates=24)
+
+
+@pytest.mark.parametrize("dtype,sizes,perm", [
+    (ttc.TTC_F32, (70, 50), (1, 0)),            # ragged on both indices: last vectors and blocks moved back
+    (ttc.TTC_F32, (133, 67), (1, 0)),           # remainder tiles of less than one vector
+    (ttc.TTC_F64, (35, 35, 35), (2, 1, 0)),
+    (ttc.TTC_F64, (72, 3, 72), (2, 1, 0)),      # tiles of 72: 36 vectors a row, no power of two
+    (ttc.TTC_F32, (96, 2, 96), (2, 0, 1)),
+])
+def test_walks_of_every_micro_tile_candidate(dtype, sizes, perm):
+    p = ttc.ttc_plan_create_ex(dtype, len(sizes), sizes, perm)
+    want = [-1] * int(np.prod(sizes))
+    for off_a, off_b in oracle.element_pairs(sizes, perm, None, None):
+        want[off_b] = off_a
+    seen = 0
+    for k in range(ttc.ttc_plan_candidate_count(p)):
+        ttc.ttc_plan_select_candidate(p, k)
+        if ttc.ttc_plan_get_info(p)["kernel_class"] != ttc.TTC_KERNEL_MICRO:
+            continue
+        seen += 1
+        assert list(ttc.ttc_debug_emulate_map(p, len(want))) == want, (sizes, perm, k, ttc.ttc_plan_get_info(p))
+    assert seen >= 8
+    ttc.ttc_plan_destroy(p)
+
+
+def test_micro_tile_kernel_is_not_planned_for_updates_of_ragged_tensors():
+    """Elements written twice (moved-back vectors) cannot be read-modify-written: beta != 0 keeps to whole vectors."""
+    for sizes, want in (((70, 50), False), ((72, 48), True)):
+        p = ttc.ttc_plan_create(ttc.TTC_F32, 2, sizes, (1, 0), 1.0, 0.5)
+        classes = set()
+        for k in range(ttc.ttc_plan_candidate_count(p)):
+            ttc.ttc_plan_select_candidate(p, k)
+            classes.add(ttc.ttc_plan_get_info(p)["kernel_class"])
+        assert (ttc.TTC_KERNEL_MICRO in classes) == want
+        ttc.ttc_plan_destroy(p)
 
 
 def test_walks_random_5d_6d():
