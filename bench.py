@@ -33,6 +33,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 LAST_LEVEL_CACHE_BYTES = 256 * 1024 * 1024
+STEADY_MS = 12.0                # untimed work before a timing, so that the GPU has left its idle state
+MAX_WARM = 400                  # ... but no more launches than this (microsecond kernels)
 DEFAULT_STORE = os.path.join(ROOT, "paper_1603_02297_amd", "plans", "gfx950_suite.txt")
 
 
@@ -53,7 +55,9 @@ def parse():
     ap.add_argument("--no-heuristic", action="store_true",
                     help="do not time the heuristic's first candidate separately (keeps a profile to one configuration)")
     ap.add_argument("--plan-cache", type=str, default=DEFAULT_STORE,
-                    help="file of stored search results: cases found there are not searched again")
+                    help="file of stored search results: cases found there are not searched again; several files, comma "
+                         "separated: every stored plan of a case is timed and the fastest kept (with --store-plans: a way "
+                         "to validate searches from several machines on one more)")
     ap.add_argument("--search", action="store_true", help="search every case in the run, whatever the store holds")
     ap.add_argument("--problem", type=str, default="",
                     help="time this problem instead of the suite: dtype:sizes:perm[:alpha:beta], e.g. f32:85x85x85x85:3210:1:0 "
@@ -193,21 +197,26 @@ def main() -> int:
         reps = K if nbytes > 64e6 else max(K, 10 * npairs)       # microsecond launches: more of them per timing
         # ceilings of the same byte size, measured the same way, next to the case
         cbytes = nbytes - nbytes % 16                            # the copy helpers move whole 16-byte units
-        ck = ttc.ttc_time_ceiling(0, cbytes, a_ptrs, b_ptrs, stream, W, reps)
-        cm = ttc.ttc_time_ceiling(1, cbytes, a_ptrs, b_ptrs, stream, W, reps)
-        cs = ttc.ttc_time_ceiling(3, cbytes, a_ptrs, b_ptrs, stream, W, reps)
-        co = ttc.ttc_time_ceiling(4, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+        # Untimed launches before every timing: W, and at least STEADY_MS of work.  Kernels made of very many small
+        # workgroups take 10 ms of launches to reach their steady rate after the GPU has idled (measured: 5500 ->
+        # 6100 GB/s over the first 50 launches of a 0.2 ms kernel, 5200 again after 0.2 s of idling; the copies do
+        # not care), and the host work between the timings of a case is long enough for that.
+        Wc = max(W, min(MAX_WARM, int(STEADY_MS / (2 * cbytes / 6.0e9) + 1)))
+        ck = ttc.ttc_time_ceiling(0, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
+        cm = ttc.ttc_time_ceiling(1, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
+        cs = ttc.ttc_time_ceiling(3, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
+        co = ttc.ttc_time_ceiling(4, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
         copy_k, copy_m, copy_s, copy_o = (2 * cbytes / t / 1e6 for t in (ck, cm, cs, co))
         axpby = None
         if not c.beta_is_zero:
-            cx = ttc.ttc_time_ceiling(2, cbytes, a_ptrs, b_ptrs, stream, W, reps)
+            cx = ttc.ttc_time_ceiling(2, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
             axpby = 3 * cbytes / cx / 1e6
             for t in B_dev:                                      # the axpby ceiling changed B
                 t.copy_(torch.from_numpy(B_host))
         d2d = max(copy_k, copy_m, copy_s, copy_o)   # the fastest known way to copy is the ceiling
 
         plan = ttc.ttc_plan_create(c.dtype, len(c.sizes), c.sizes, c.perm, c.alpha, c.beta)
-        ms_heur = None if args.no_heuristic else ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, reps)
+        ms_heur = None if args.no_heuristic else ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, Wc, reps)
         t0 = time.perf_counter()
         source = "search"
         if args.force_class:
@@ -219,6 +228,17 @@ def main() -> int:
                     break
             else:
                 raise SystemExit(f"bench.py: {c.name} has no candidate of class {args.force_class}")
+        elif not args.search and "," in args.plan_cache:
+            # several stores (searches run on different machines): time what each holds for the case, keep the fastest
+            timed = []
+            for path in args.plan_cache.split(","):
+                if path and ttc.ttc_plan_cache_lookup(plan, path):
+                    timed.append((ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, Wc, reps), path))
+                    log(f"[gpu] {c.name}: {path}: {c.traffic_bytes / timed[-1][0] / 1e6:.0f} GB/s, {plan_text(ttc.ttc_plan_get_info(plan), ttc)}")
+            if not timed:
+                raise SystemExit(f"bench.py: none of the stores holds {c.name}")
+            ttc.ttc_plan_cache_lookup(plan, min(timed)[1])
+            source = "store " + os.path.basename(min(timed)[1])
         elif not args.search and args.plan_cache and ttc.ttc_plan_cache_lookup(plan, args.plan_cache):
             source = "store"
         else:
@@ -227,7 +247,7 @@ def main() -> int:
         if args.store_plans:
             ttc.ttc_plan_cache_store(plan, args.store_plans)
         info = ttc.ttc_plan_get_info(plan)
-        ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, W, reps)       # the plan as finally selected
+        ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, Wc, reps)      # the plan as finally selected
         # the same plan once more, from a fresh B, against the oracle
         max_ulp = None
         if cpu is not None:
@@ -288,7 +308,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32/f64/c64", "data": "synthetic",
         "config": {"workload": f"{len(results)}-case suite (2-D/3-D fp32, 4-D fp64, 6-D fp32, 5-D complex64), one launch per case per step",
-                   "cases": len(results)},
+                   "cases": len(results), "untimed_ms_before_each_timing": STEADY_MS},
         "roofline": roofline,
     }
     if cpu is not None:

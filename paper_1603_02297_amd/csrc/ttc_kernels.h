@@ -489,7 +489,7 @@ inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipSt
         const uint32_t grid = kp.num_tiles;                    // one tile per workgroup: the hardware deals them
         const int64_t th = c.threads;
         if (m.vec != V || (1 << m.vec_log) != V || (th != 64 && th != 128 && th != 256) || m.la < 1 || m.lb < 1 ||
-            m.ta != m.la * V || m.tb != m.lb * V || m.pitch < m.la || (m.pitch & 7) || m.la_div.div != (uint32_t)m.la ||
+            m.ta != m.la * V || m.tb != m.lb * V || m.pitch < m.la || (m.pitch & 7) || (m.swizzle != 7u && m.swizzle != 0u) || m.la_div.div != (uint32_t)m.la ||
             m.lb_div.div != (uint32_t)m.lb || (int64_t)m.loads * th < (int64_t)m.la * m.tb || (int64_t)m.blocks * th < (int64_t)m.la * m.lb ||
             (int64_t)(m.loads + 4) * th >= (int64_t(1) << 31) ||
             c.lds_bytes != m.tb * m.pitch * 16 || c.lds_bytes > 64 * 1024 || grid < 1 || grid != kp.grid ||

@@ -759,6 +759,10 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     MicroParams& m = kp.micro;
     m.ta = ta; m.tb = tb; m.p0 = p0; m.vec = vec;
     m.la = la; m.lb = lb; m.pitch = pitch; m.loads = loads; m.blocks = blocks;
+    {   // TTC_LDS_PAD=0 in the environment: no swizzle either (the ablation of the studies)
+        const char* pad_env = std::getenv("TTC_LDS_PAD");
+        m.swizzle = (pad_env && pad_env[0] == '0') ? 0u : 7u;
+    }
     m.la_div = make_fastdiv((uint32_t)la); m.lb_div = make_fastdiv((uint32_t)lb);
     m.vec_log = (vec == 4) ? 2 : 1;
     m.size_a0 = P.size[0]; m.size_p0 = P.size[p0];
@@ -1259,6 +1263,11 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                 for (int l = 6; l <= 96; ++l)
                     if (whole % l == 0 && (l & (l - 1)) != 0) v->push_back(l);
             if (whole >= 1 && whole < 8) v->push_back((int)ceil_div(size, vec));
+            if (size % vec != 0 && whole >= 8) {               // the whole extent in one tile, or in two: no run shared between tiles
+                const int64_t all = ceil_div(size, vec);
+                if (all <= 96) v->push_back((int)all);
+                if (all >= 16 && ceil_div(all, 2) <= 96) v->push_back((int)ceil_div(all, 2));
+            }
         };
         std::vector<int> las, lbs;
         extents(P.size[0], &las);
@@ -1629,7 +1638,7 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
     const int vec = m.vec;
     if ((vec != 2 && vec != 4) || vec * P.eb_a != 16 || P.eb_a != P.eb_b ||
         (threads != 64 && threads != 128 && threads != 256) || m.ta != vec * m.la || m.tb != vec * m.lb ||
-        m.la < 1 || m.lb < 1 || m.pitch < m.la || (m.pitch & 7) || m.la_div.div != (uint32_t)m.la || m.lb_div.div != (uint32_t)m.lb ||
+        m.la < 1 || m.lb < 1 || m.pitch < m.la || (m.pitch & 7) || (m.swizzle != 7u && m.swizzle != 0u) || m.la_div.div != (uint32_t)m.la || m.lb_div.div != (uint32_t)m.lb ||
         (int64_t)m.loads * threads < (int64_t)m.la * m.tb || (int64_t)m.blocks * threads < (int64_t)m.la * m.lb ||
         (1 << m.vec_log) != vec || C.lds_bytes != m.tb * m.pitch * 16 || C.lds_bytes > 64 * 1024 || p.grid != p.num_tiles ||
         m.p0 != P.perm[0] || m.p0 == 0 || m.size_a0 != P.size[0] || m.size_p0 != P.size[m.p0] ||

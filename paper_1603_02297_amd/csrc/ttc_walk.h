@@ -205,7 +205,7 @@ TTC_HD uint32_t micro_back(uint32_t x, uint32_t lim, uint32_t vec) { return x + 
 // The 16-byte LDS slot of row `row` of the tile, column group `lane_c`.
 TTC_HD uint32_t micro_slot(const MicroParams& m, uint32_t row, uint32_t lane_c)
 {
-    return row * (uint32_t)m.pitch + (lane_c ^ ((row >> m.vec_log) & 7u));
+    return row * (uint32_t)m.pitch + (lane_c ^ ((row >> m.vec_log) & m.swizzle));
 }
 
 // Load walk: vector k of lane `tid` (vectors are numbered row by row, so consecutive lanes load consecutive

@@ -189,10 +189,10 @@ def study_search(out, dump=None):
 
 # ---- study 2: the 57-case benchmark, classes and ablations ------------------------------------------
 def unpadded_ms(dtype, sizes, perm, alpha, beta, best_info, a_ptrs, b_ptrs, stream, tmp):
-    """Time of the configuration `best_info` names when its LDS tile is laid out without pads, or None."""
+    """Time of the configuration `best_info` names when its LDS tile is laid out without pads (without the swizzle), or None."""
     import os
-    if best_info["kernel_class"] != ttc.TTC_KERNEL_LDS:
-        return None                              # no LDS tile, or (micro-tile kernel) one that is swizzled, not padded
+    if best_info["kernel_class"] not in (ttc.TTC_KERNEL_LDS, ttc.TTC_KERNEL_MICRO):
+        return None                              # no LDS tile (the micro-tile kernel's is swizzled, not padded: the swizzle goes)
     plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
     ttc.ttc_plan_select_candidate(plan, best_info["candidate_index"])
     ttc.ttc_plan_set_streaming(plan, best_info["nt_a"], best_info["nt_b"])
