@@ -339,7 +339,7 @@ __global__ __launch_bounds__(kMaxThreads) void box_kernel(const KernelParams par
 
 // ---------------------------------------------------------------------------------
 // The row kernel, for the case where the stride-1 index keeps its place and rows are contiguous in both tensors
-// (paper Section 3.1, case 1: loops around a copy of the first column).  B is walked in the order of its
+// (paper Section 3.1, case 1: the first column is copied, inside loops over the other indices).  B is walked in the order of its
 // multi-index: workgroup w moves the `chunk` vectors that start at vector w * chunk, so consecutive
 // workgroups write consecutive memory (a dense B is written front to back like a copy), and every lane gathers
 // its vectors from the rows of A.  No tiles, no LDS, no tables: a lane finds its row by one division and the

@@ -150,6 +150,30 @@ def d2d_copy_gbps(nbytes, a_ptrs, b_ptrs, stream):
 
 
 # ---- study 1: reduction of the search space -------------------------------------------------------
+def search_set(classes, cap):
+    """Ranks the library's search times when capped at `cap` candidates (the rule of ttc_plan_tune_pairs): the
+    first `cap` of the ranking, a fifth of the places going to the best-ranked micro-tile candidates where the
+    ranking would have left them out."""
+    total = len(classes)
+    cap = min(cap, total)
+    chosen = list(range(cap))
+    if 10 <= cap < total:
+        extra, seen = [], 0
+        for i, cls in enumerate(classes):
+            if seen >= cap // 5:
+                break
+            if cls == ttc.TTC_KERNEL_MICRO:
+                seen += 1
+                if i >= cap:
+                    extra.append(i)
+        k = cap - 1
+        while k >= 1 and extra:
+            if classes[chosen[k]] != ttc.TTC_KERNEL_MICRO:
+                chosen[k] = extra.pop()
+            k -= 1
+    return chosen
+
+
 def study_search(out, dump=None):
     import torch
     stream = torch.cuda.current_stream().cuda_stream
@@ -171,11 +195,13 @@ def study_search(out, dump=None):
         if dump is not None:        # every candidate's configuration and time, one JSON line per problem
             dump.write(json.dumps({"problem": name, "rows": [dict(r[0], ms=r[1]) for r in rows]}) + "\n")
         best = ms.min()
-        frac = [best / ms[:k].min() for k in caps]
+        classes = [r[0]["kernel_class"] for r in rows]
+        frac = [best / ms[search_set(classes, k)].min() for k in caps]
         table.append((name, len(rows), rows[0][0]["bytes_moved"] / best / 1e6, frac))
         log(f"{name}: {len(rows)} candidates, best {table[-1][2]:.0f} GB/s, " +
             ", ".join(f"first {k}: {100 * f:.1f}%" for k, f in zip(caps, frac)))
     w = max(len(t[0]) for t in table)
+    print("best time among the candidates a search capped at 1 / 10 / 100 / 200 would time, relative to the best of all", file=out)
     print(f"{'problem':<{w}}  cands  best GB/s  " + "  ".join(f"first {k:>3}" for k in caps), file=out)
     for name, n, gbps, frac in table:
         print(f"{name:<{w}}  {n:5d}  {gbps:9.0f}  " + "  ".join(f"{100 * f:8.2f}%" for f in frac), file=out)

@@ -229,3 +229,42 @@ def test_odd_benchmark_shapes_full_size(sizes, perm):
     for tune in (False, True):
         got, info = gpu_run(wl.F32, sizes, perm, 1.0, 0.0, A, B0, tune=tune)
         assert np.array_equal(got, want), (sizes, perm, tune, info)
+
+
+# ---- every candidate of the one-shot kernel families on ragged shapes -----------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,sizes,perm,alpha,beta", [
+    (wl.F32, (70, 50), (1, 0), 1.0, 0.0),              # moved-back vectors and blocks on both indices
+    (wl.F32, (133, 67), (1, 0), 1.5, 0.0),             # remainder tiles narrower than a vector
+    (wl.F64, (35, 35, 35), (2, 1, 0), 1.0, 0.0),
+    (wl.F64, (72, 5, 72), (2, 1, 0), 0.75, 1.25),      # tiles of 72 (36 vectors a row), B read as well
+    (wl.C64, (24, 7, 40), (2, 0, 1), 0.5 + 0.5j, 1.0 + 0.0j),
+    (wl.F32, (96, 20, 31), (0, 2, 1), 1.5, 0.0),       # stride-1 index fixed: the row kernel's candidates
+    (wl.F32, (85, 9, 13), (0, 2, 1), 2.0, 0.0),        # rows that are no multiple of the vector
+])
+def test_every_candidate_of_the_one_shot_families(dtype, sizes, perm, alpha, beta):
+    n = int(np.prod(sizes))
+    A = wl.uniform_tensor(dtype, n, 4100)
+    B0 = wl.uniform_tensor(dtype, n, 4200)
+    want = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy(), 4)
+    pure = (complex(alpha) == 1 and complex(beta) == 0)
+    dev = torch.device("cuda:0")
+    dA, dB0 = torch.from_numpy(A).to(dev), torch.from_numpy(B0).to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+    try:
+        ran = 0
+        for k in range(ttc.ttc_plan_candidate_count(plan)):
+            ttc.ttc_plan_select_candidate(plan, k)
+            info = ttc.ttc_plan_get_info(plan)
+            if info["kernel_class"] not in (ttc.TTC_KERNEL_MICRO, ttc.TTC_KERNEL_ROWS):
+                continue
+            dB = dB0.clone()
+            ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), stream)
+            torch.cuda.synchronize()
+            d = ulp_distance(dB.cpu().numpy(), want)
+            assert d <= (0 if pure else 1), (sizes, perm, k, d, info)
+            ran += 1
+        assert ran >= 4, (sizes, perm, ran)
+    finally:
+        ttc.ttc_plan_destroy(plan)
