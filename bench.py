@@ -127,7 +127,7 @@ def plan_text(info, ttc) -> str:
     """The selected configuration in one short string (the fields that name it in the plan store and the profiles)."""
     cls = {ttc.TTC_KERNEL_DIRECT: "direct", ttc.TTC_KERNEL_LDS: "lds", ttc.TTC_KERNEL_ROWS: "rows", ttc.TTC_KERNEL_MICRO: "micro"}[info["kernel_class"]]
     tile = "x".join(str(t) for t in info["tile"])
-    return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} u{info['unroll']} "
+    return (f"{cls} t{tile} v{info['vec_a']}/{info['vec_b']} th{info['threads']} wg{info['wg_per_cu']} u{info['unroll']} m{info['merged']} "
             f"buf{info['lds_buffers']} lds{info['lds_bytes']} nt{info['nt_a']}{info['nt_b']} x{info['xcd_remap']} "
             f"cf{info['lds_conflict_a']}/{info['lds_conflict_b']} cand{info['candidate_index']}/{info['candidate_count']}")
 
@@ -209,7 +209,8 @@ def main() -> int:
         copy_k, copy_m, copy_s, copy_o = (2 * cbytes / t / 1e6 for t in (ck, cm, cs, co))
         axpby = None
         if not c.beta_is_zero:
-            cx = ttc.ttc_time_ceiling(2, cbytes, a_ptrs, b_ptrs, stream, Wc, reps)
+            cx = min(ttc.ttc_time_ceiling(2, cbytes, a_ptrs, b_ptrs, stream, Wc, reps),
+                     ttc.ttc_time_ceiling(5, cbytes, a_ptrs, b_ptrs, stream, Wc, reps))      # plain persistent, non-temporal one-shot
             axpby = 3 * cbytes / cx / 1e6
             for t in B_dev:                                      # the axpby ceiling changed B
                 t.copy_(torch.from_numpy(B_host))

@@ -105,7 +105,9 @@ typedef struct {
     float   tuned_ms;                      /* time of the selected candidate in the last ttc_plan_tune, else 0 */
     double  heuristic_cost;                /* the ranking key: modelled relative cost, smaller is better */
     int     unroll;                        /* row kernel: vectors a lane keeps in flight (1, 2, 4 or 8); micro-tile kernel: blocks a lane owns
-                                              (1 or 2); 0 for the box kernels */
+                                              (1 to 6); 0 for the box kernels */
+    int     merged;                        /* micro-tile kernel: bit 0: the tile's column index is A's indices 0 and 1 taken as one,
+                                              bit 1: its row index is B's first two indices taken as one; else 0 */
 } ttc_plan_info_t;
 
 /*

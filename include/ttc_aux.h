@@ -28,7 +28,8 @@ int ttc_time_execute(ttc_plan_t plan, int npairs, const void* const* A_list, voi
  * paper's Section 4).  kind 0: dst <- src with a 128-bit-per-lane copy kernel (1 read, 1
  * write); kind 1: hipMemcpyAsync device-to-device; kind 2: dst <- 0.75*src + 1.25*dst as
  * fp32 (2 reads, 1 write); kind 3: the copy kernel of kind 0 with non-temporal loads and stores; kind 4: a non-temporal copy of one
- * 16-byte access per lane and one 4 KB chunk per one-shot workgroup.  `bytes` must be a multiple of 16 and the pointers 16-byte
+ * 16-byte access per lane and one 4 KB chunk per one-shot workgroup; kind 5: the update of kind 2 in the launch shape of kind 4,
+ * non-temporal.  `bytes` must be a multiple of 16 and the pointers 16-byte
  * aligned.  Buffer pairs rotate as in ttc_time_execute.  SYNCHRONISES.
  */
 int ttc_time_ceiling(int kind, int64_t bytes, int npairs, const void* const* src_list,

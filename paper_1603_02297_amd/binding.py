@@ -49,7 +49,7 @@ class ttc_plan_info_t(ctypes.Structure):
         ("span_a", ctypes.c_int64), ("span_b", ctypes.c_int64),
         ("stride_a", ctypes.c_int64 * TTC_MAX_DIM), ("stride_b", ctypes.c_int64 * TTC_MAX_DIM),
         ("candidate_index", ctypes.c_int), ("candidate_count", ctypes.c_int), ("tuned_ms", ctypes.c_float), ("heuristic_cost", ctypes.c_double),
-        ("unroll", ctypes.c_int),
+        ("unroll", ctypes.c_int), ("merged", ctypes.c_int),
     ]
 
     def as_dict(self) -> dict:

@@ -73,15 +73,19 @@ struct Slot {
     FastDiv  tile_below, tile_cnt;   // tile id -> tile coordinate along this index
 };
 
-// The micro-tile kernel: a tile spans A's stride-1 index (index 0, extent ta inside the tile) and B's stride-1 index
-// (A's index p0, extent tb) and nothing else.  Lanes load 16-byte vectors along index 0 and park them in LDS with
+// The micro-tile kernel: a tile spans ta columns and tb rows and nothing else.  The column index is A's stride-1
+// index (index 0), or A's indices 0 and 1 taken as one index where rows are short (together they are one contiguous
+// run of A, and a column's place in B follows from its two parts); the row index is B's stride-1 index (A's index
+// p0), or B's first two indices taken as one.  Lanes load 16-byte vectors along the columns and park them in LDS with
 // one 128-bit write; after the barrier a lane reads the vec x vec block it owns with vec 128-bit reads, transposes
-// it in registers and stores vec 16-byte vectors along B's stride-1 index.  Rows of the LDS tile are `pitch`
+// it in registers and stores vec 16-byte vectors along the rows.  Rows of the LDS tile are `pitch`
 // 16-byte chunks long (a multiple of eight); chunk c of row r sits at chunk position c ^ ((r / vec) & 7), which
 // makes both the writes (lanes along c) and the reads (lanes along r in steps of vec) free of bank conflicts.
 struct MicroParams {
-    int32_t  ta, tb;                 // tile extents: along A's index 0, along A's index p0 (multiples of vec)
+    int32_t  ta, tb;                 // tile extents along the column index and along the row index (multiples of vec)
     int32_t  p0;                     // the index of A that is B's stride-1 index
+    int32_t  merged_a, merged_b;     // 1: the column index is A's indices 0 and 1 taken as one (contiguous in A), the row
+                                     // index B's first two indices taken as one (contiguous in B); 0: one index each
     int32_t  vec, vec_log;           // elements in 16 bytes, and its log2
     int32_t  la, lb;                 // ta / vec and tb / vec: vectors per row of the tile, blocks per column (each at least 8)
     int32_t  pitch;                  // 16-byte chunks per row of the LDS tile: la rounded up to a multiple of 8
@@ -89,9 +93,12 @@ struct MicroParams {
     int32_t  loads;                  // vectors a lane loads per tile: ceil(la * tb / threads)
     int32_t  blocks;                 // vec x vec blocks a lane owns: ceil(la * lb / threads)
     FastDiv  la_div, lb_div;
-    int64_t  size_a0, size_p0;       // extents of the two indices
-    int64_t  stride_a_p0;            // element stride of index p0 in A
-    int64_t  stride_b_0;             // element stride of index 0 in B
+    int64_t  size_a0, size_p0;       // extents of the column index and of the row index (the product where two are merged)
+    // A column x sits at element x of A's run and at (x % in) * stride_in + (x / in) * stride_out in B, where `in`
+    // is the extent of A's index 0; a row likewise with the tensors exchanged.  Not merged: x / in is always 0.
+    FastDiv  col_in_div, row_in_div;
+    int64_t  col_b_in, col_b_out;    // element strides in B of the column index's inner and outer part
+    int64_t  row_a_in, row_a_out;    // element strides in A of the row index's inner and outer part
 };
 
 // Everything a kernel launch needs; passed by value as the kernel argument.

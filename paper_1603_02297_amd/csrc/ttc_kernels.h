@@ -415,7 +415,6 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
     const MicroParams& m = p.micro;
     const Epilogue<T, T, MODE> epi(p.alpha, p.beta);
     const uint32_t tid = threadIdx.x, threads = blockDim.x;
-    const int64_t row_a = m.stride_a_p0 * kScale, col_b = m.stride_b_0 * kScale;      // bytes
     const uint32_t pitch = (uint32_t)m.pitch;
     const uint32_t loads = (uint32_t)m.loads, blocks = (uint32_t)m.blocks;
     const TileSeq seq = tile_sequence(p, blockIdx.x);
@@ -435,8 +434,8 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
                 for (int u = 0; u < U; ++u) {
                     x[u] = micro_load(m, threads, tid, k0 + (uint32_t)u);
                     const bool ok = x[u].valid && x[u].row < t.lim_b && x[u].col < t.lim_a;
-                    const uint32_t col = micro_back(x[u].col, t.lim_a, V);
-                    in[u].p = load_pack<T, V, NTA>(At, ok ? (int64_t)x[u].row * row_a + (int64_t)col * kScale : 0);
+                    const uint32_t col = ok ? micro_back(x[u].col, t.lim_a, V) : 0u;
+                    in[u].p = load_pack<T, V, NTA>(At, (micro_row_a(m, t.row0 + (ok ? x[u].row : 0u)) + (int64_t)col) * kScale);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
@@ -449,16 +448,32 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
                 const bool ok = x.valid && x.row < t.lim_b && x.col < t.lim_a;
                 const uint32_t row = ok ? micro_back(x.row, t.lim_b, V) : 0u, col = ok ? micro_back(x.col, t.lim_a, V) : 0u;
                 const uint32_t lane_c = ok ? x.lane_c : 0u;
-                const int64_t to = (int64_t)col * col_b + (int64_t)row * kScale;
+                int64_t to[V];                                  // byte offsets of the block's V columns in B
+#pragma unroll
+                for (int j = 0; j < V; ++j) to[j] = (micro_col_b(m, t.col0 + col + (uint32_t)j) + (int64_t)row) * kScale;
                 Pack<T, V> old[V];
                 if (MODE == TTC_EPI_AXPBY) {
 #pragma unroll
-                    for (int j = 0; j < V; ++j) old[j] = load_pack<T, V, NTB>(Bt, to + j * col_b);
+                    for (int j = 0; j < V; ++j) old[j] = load_pack<T, V, NTB>(Bt, to[j]);
                 }
                 Vec blk[V];
 #pragma unroll
                 for (int i = 0; i < V; ++i) blk[i].q = lds[micro_slot(m, row + (uint32_t)i, lane_c)];
-                if (ok) {
+                // Where B is read as well as written an element must be updated once: a block that was moved back, or
+                // lies in a tile that was, updates only what is its own (from its nominal place on, and not the
+                // neighbouring tile's elements), element by element.  Such blocks exist at the tensor's edge only.
+                const bool edge = MODE == TTC_EPI_AXPBY && ok && (row != x.row || col != x.col || x.row < t.own_b || x.col < t.own_a);
+                if (MODE == TTC_EPI_AXPBY && edge) {
+                    const uint32_t first_row = x.row > t.own_b ? x.row : t.own_b, first_col = x.col > t.own_a ? x.col : t.own_a;
+#pragma unroll
+                    for (int j = 0; j < V; ++j)
+#pragma unroll
+                        for (int i = 0; i < V; ++i)
+                            if (col + (uint32_t)j >= first_col && row + (uint32_t)i >= first_row) {
+                                T* pb = reinterpret_cast<T*>(Bt + to[j]) + i;
+                                *pb = epi(blk[i].p.v[j], *pb);
+                            }
+                } else if (ok) {
 #pragma unroll
                     for (int j = 0; j < V; ++j) {
                         Pack<T, V> out;
@@ -468,7 +483,7 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
                             if (MODE == TTC_EPI_AXPBY) b_old = old[j].v[i];
                             out.v[i] = epi(blk[i].p.v[j], b_old);
                         }
-                        store_pack<T, V, NTB>(Bt, to + j * col_b, out);
+                        store_pack<T, V, NTB>(Bt, to[j], out);
                     }
                 }
             }
@@ -493,8 +508,8 @@ inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipSt
             m.lb_div.div != (uint32_t)m.lb || (int64_t)m.loads * th < (int64_t)m.la * m.tb || (int64_t)m.blocks * th < (int64_t)m.la * m.lb ||
             (int64_t)(m.loads + 4) * th >= (int64_t(1) << 31) ||
             c.lds_bytes != m.tb * m.pitch * 16 || c.lds_bytes > 64 * 1024 || grid < 1 || grid != kp.grid ||
-            m.size_a0 < V || m.size_p0 < V ||
-            (MODE == TTC_EPI_AXPBY && (m.size_a0 % V != 0 || m.size_p0 % V != 0)))     // doubly written elements would race with their own read
+            m.size_a0 < V || m.size_p0 < V || m.size_a0 >= (int64_t(1) << 31) || m.size_p0 >= (int64_t(1) << 31) ||
+            m.col_in_div.div < 1 || m.row_in_div.div < 1)
             return hipErrorInvalidValue;
         const void* fn = reinterpret_cast<const void*>(&micro_kernel<TA, MODE, V>);
         const TA* a = static_cast<const TA*>(A);

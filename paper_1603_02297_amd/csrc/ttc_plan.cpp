@@ -699,18 +699,25 @@ static bool make_candidate(const Problem& P, const int* t_in, int vec_limit, boo
     return true;
 }
 
-// The micro-tile kernel's candidate: a tile of ta x tb elements over A's index 0 and B's stride-1 index p0.
-// Needs one element type of 4 or 8 bytes on both sides, both indices contiguous in their tensor and at least one
-// 16-byte vector long, ta and tb multiples of the vector, a tile of at most 64 KB.  Extents that are not multiples
-// of the vector make some elements be written twice, which an update of B (beta != 0) cannot have.
-static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, const int* tile_order, Candidate* out)
+// The micro-tile kernel's candidate: a tile of ta columns x tb rows.  The column index is A's index 0, or A's
+// indices 0 and 1 taken as one (merge_a: together they are one contiguous run of A); the row index is B's
+// stride-1 index p0, or B's first two indices taken as one (merge_b).  Needs one element type of 4 or 8 bytes on
+// both sides, indices contiguous in their tensor, four different indices where both sides merge, both (merged)
+// extents at least one 16-byte vector, ta and tb multiples of the vector, a tile of at most 64 KB.  Extents that
+// are not multiples of the vector make some elements be moved twice; where B is updated (beta != 0) the kernel
+// writes such an element once, from the block that owns it.
+static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, const int* tile_order, bool merge_a, bool merge_b,
+                                 Candidate* out)
 {
     if (P.ndim < 2 || P.perm[0] == 0 || P.kind_a != P.kind_b || (P.eb_a != 4 && P.eb_a != 8)) return false;
     const int p0 = P.perm[0], vec = 16 / P.eb_a;
+    const int a1 = 1, p1 = P.ndim >= 2 ? P.perm[1] : -1;         // the second index of A and of B
     if (P.stride_a[0] != 1 || P.stride_b[p0] != 1) return false;
-    if (P.size[0] < vec || P.size[p0] < vec || ta % vec != 0 || tb % vec != 0 || ta < vec || tb < vec) return false;
-    const bool whole = P.size[0] % vec == 0 && P.size[p0] % vec == 0;
-    if (!whole && P.epilogue == TTC_EPI_AXPBY) return false;
+    if (merge_a && (P.ndim < 3 || a1 == p0 || P.stride_a[a1] != P.size[0] || (merge_b && a1 == p1))) return false;
+    if (merge_b && (P.ndim < 3 || p1 == 0 || P.stride_b[p1] != P.size[p0] || (merge_a && p1 == a1))) return false;
+    const int64_t cols = merge_a ? P.size[0] * P.size[a1] : P.size[0], rows = merge_b ? P.size[p0] * P.size[p1] : P.size[p0];
+    if (cols >= (int64_t(1) << 31) || rows >= (int64_t(1) << 31)) return false;
+    if (cols < vec || rows < vec || ta % vec != 0 || tb % vec != 0 || ta < vec || tb < vec) return false;
     const int la = ta / vec, lb = tb / vec;
     const int pitch = (la + 7) / 8 * 8;
     if ((int64_t)tb * pitch * 16 > 64 * 1024) return false;
@@ -725,16 +732,26 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     KernelParams& kp = C.kp;
     kp.n = P.ndim;
     int64_t ntiles = 1;
+    // what the tile decode sees: the (merged) column index in the place of index 0, the row index in the place of
+    // p0, an index merged into one of them as a single tile that contributes nothing, every other index one
+    // element per tile.  The decode adds the column's place in A and the row's place in B (stride 1); where the
+    // column lies in B and the row in A depends on more than a stride and is left to the kernel.
+    int64_t extent[kMaxDim];
     for (int k = 0; k < kMaxDim; ++k) {
-        C.tile[k] = (k == 0) ? ta : (k == p0 ? tb : 1);
-        kp.tile[k] = C.tile[k];
+        extent[k] = (k < P.ndim) ? P.size[k] : 1;
+        C.tile[k] = 1;
         kp.stride_a[k] = (k < P.ndim) ? P.stride_a[k] : 0;
         kp.stride_b[k] = (k < P.ndim) ? P.stride_b[k] : 0;
         kp.tile_below[k] = kp.tile_cnt[k] = make_fastdiv(1);
     }
+    extent[0] = cols; C.tile[0] = ta; kp.stride_a[0] = 1; kp.stride_b[0] = 0;
+    extent[p0] = rows; C.tile[p0] = tb; kp.stride_a[p0] = 0; kp.stride_b[p0] = 1;
+    if (merge_a) { extent[a1] = 1; kp.stride_a[a1] = kp.stride_b[a1] = 0; }
+    if (merge_b) { extent[p1] = 1; kp.stride_a[p1] = kp.stride_b[p1] = 0; }
+    for (int k = 0; k < kMaxDim; ++k) kp.tile[k] = C.tile[k];
     for (int i = 0; i < P.ndim; ++i) {
         const int k = tile_order[i];
-        const int64_t cnt = ceil_div(P.size[k], C.tile[k]);
+        const int64_t cnt = ceil_div(extent[k], C.tile[k]);
         if (cnt > INT32_MAX / 2 || ntiles > INT32_MAX / 2) return false;
         kp.tile_below[k] = make_fastdiv((uint32_t)ntiles);
         kp.tile_cnt[k] = make_fastdiv((uint32_t)cnt);
@@ -758,6 +775,7 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     }
     MicroParams& m = kp.micro;
     m.ta = ta; m.tb = tb; m.p0 = p0; m.vec = vec;
+    m.merged_a = merge_a ? 1 : 0; m.merged_b = merge_b ? 1 : 0;
     m.la = la; m.lb = lb; m.pitch = pitch; m.loads = loads; m.blocks = blocks;
     {   // TTC_LDS_PAD=0 in the environment: no swizzle either (the ablation of the studies)
         const char* pad_env = std::getenv("TTC_LDS_PAD");
@@ -765,12 +783,18 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     }
     m.la_div = make_fastdiv((uint32_t)la); m.lb_div = make_fastdiv((uint32_t)lb);
     m.vec_log = (vec == 4) ? 2 : 1;
-    m.size_a0 = P.size[0]; m.size_p0 = P.size[p0];
-    m.stride_a_p0 = P.stride_a[p0];
-    m.stride_b_0 = P.stride_b[0];
+    m.size_a0 = cols; m.size_p0 = rows;
+    m.col_in_div = make_fastdiv((uint32_t)P.size[0]);
+    m.row_in_div = make_fastdiv((uint32_t)P.size[p0]);
+    m.col_b_in = P.stride_b[0];  m.col_b_out = merge_a ? P.stride_b[a1] : 0;
+    m.row_a_in = P.stride_a[p0]; m.row_a_out = merge_b ? P.stride_a[p1] : 0;
+    // the tile per index of A, as the plan reports it: a merged index takes what the tile spans of it
+    if (merge_a) { C.tile[0] = (int)std::min<int64_t>(ta, P.size[0]); C.tile[a1] = (int)std::min<int64_t>(ceil_div(ta, P.size[0]), P.size[a1]); }
+    if (merge_b) { C.tile[p0] = (int)std::min<int64_t>(tb, P.size[p0]); C.tile[p1] = (int)std::min<int64_t>(ceil_div(tb, P.size[p0]), P.size[p1]); }
     C.digits_a = C.digits_b = 2;
     C.dtile_a[0] = ta; C.dtile_a[1] = tb; C.dlane_a[0] = std::min(ta, kWave * vec); C.dlane_a[1] = std::max(1, kWave / la);
     C.dtile_b[0] = tb; C.dtile_b[1] = ta; C.dlane_b[0] = std::min(tb, kWave * vec); C.dlane_b[1] = std::max(1, kWave / lb) * vec;
+    C.dlane_a[2] = m.merged_a; C.dlane_b[2] = m.merged_b;       // part of what names the configuration
     C.lds_conflict_a = C.lds_conflict_b = 2;       // conflict-free by construction (the value the bank model gives such a layout)
     C.lds_stride[0] = 1;
     C.lds_stride[p0] = pitch * vec;
@@ -980,12 +1004,12 @@ static double micro_cost(const Problem& P, const Candidate& C)
     // leave 72 a remainder of 8: 74 vs 82
     double e = -0.16;
     e += 0.03 * oct_below(run_a, 256.0) + 0.03 * oct_below(run_b, 256.0);
-    double padded = ((double)ceil_div(P.size[0], m.ta) * m.ta / (double)P.size[0]) *
-                    ((double)ceil_div(P.size[m.p0], m.tb) * m.tb / (double)P.size[m.p0]);
+    double padded = ((double)ceil_div(m.size_a0, m.ta) * m.ta / (double)m.size_a0) *
+                    ((double)ceil_div(m.size_p0, m.tb) * m.tb / (double)m.size_p0);
     e += 0.12 * (padded - 1.0);                                          // idle lanes in the remainder tiles (85^4: tiles of 32 x 128, 1.7 times the tensor, run 8 % ahead of the best box)
     const int64_t line = 128 / P.eb_a;
-    if (P.size[0] % line != 0) e += 0.05;                                // runs of A start inside lines
-    if (P.size[m.p0] % line != 0) e += 0.05;
+    if (m.size_a0 % line != 0 || m.ta % line != 0) e += 0.05;            // runs of A start inside lines
+    if (m.size_p0 % line != 0 || m.tb % line != 0) e += 0.05;
     if (C.threads == 128) e += 0.005; else if (C.threads == 64) e += 0.01;
     bool b_order = true;
     for (int i = 0; i < P.ndim; ++i) if (C.tile_order[i] != P.perm[i]) b_order = false;
@@ -1269,20 +1293,32 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                 if (all >= 16 && ceil_div(all, 2) <= 96) v->push_back((int)ceil_div(all, 2));
             }
         };
-        std::vector<int> las, lbs;
-        extents(P.size[0], &las);
-        extents(P.size[P.perm[0]], &lbs);
-        for (int threads : {256, 128, 64}) {
-            for (int la : las)
-                for (int lb : lbs) {
-                    const int64_t blocks = ceil_div((int64_t)la * lb, threads);
-                    if (blocks > 6 || (int64_t)la * lb * 5 < blocks * threads * 4) continue;      // lanes mostly busy
-                    for (int o = 0; o < (quick ? 1 : 2); ++o) {       // the mixed orders time the same (384^3, 72^4 reversals)
-                        Candidate c;
-                        if (make_micro_candidate(P, la * vec, lb * vec, threads, orders[o], &c)) add_candidate(P, out, c);
-                    }
-                }
-        }
+        // the column index: A's index 0, or (short rows) indices 0 and 1 as one; the row index likewise on B's side
+        const int p0 = P.perm[0], p1 = P.perm[1];
+        for (int merge_a = 0; merge_a < 2; ++merge_a)
+            for (int merge_b = 0; merge_b < 2; ++merge_b) {
+                if (merge_a && (n < 3 || P.size[0] * P.eb_a > 1024 || p0 == 1 || (quick && P.size[0] * P.eb_a >= 256))) continue;
+                if (merge_b && (n < 3 || P.size[p0] * P.eb_a > 1024 || p1 == 0 || (quick && P.size[p0] * P.eb_a >= 256))) continue;
+                if (merge_a && merge_b && p1 == 1) continue;
+                const int64_t cols = merge_a ? P.size[0] * P.size[1] : P.size[0], rows = merge_b ? P.size[p0] * P.size[p1] : P.size[p0];
+                std::vector<int> las, lbs;
+                extents(cols, &las);
+                extents(rows, &lbs);
+                // whole rows of the inner index: tiles that end where a run of the other tensor ends
+                if (merge_a) for (int64_t k = 1; k * P.size[0] <= 96 * vec && k <= P.size[1]; ++k) if (k * P.size[0] % vec == 0) las.push_back((int)(k * P.size[0] / vec));
+                if (merge_b) for (int64_t k = 1; k * P.size[p0] <= 96 * vec && k <= P.size[p1]; ++k) if (k * P.size[p0] % vec == 0) lbs.push_back((int)(k * P.size[p0] / vec));
+                for (int threads : {256, 128, 64})
+                    for (int la : las)
+                        for (int lb : lbs) {
+                            const int64_t blocks = ceil_div((int64_t)la * lb, threads);
+                            if (blocks > 6 || (int64_t)la * lb * 5 < blocks * threads * 4) continue;      // lanes mostly busy
+                            for (int o = 0; o < (quick ? 1 : 2); ++o) {       // the mixed orders time the same (384^3, 72^4 reversals)
+                                Candidate c;
+                                if (make_micro_candidate(P, la * vec, lb * vec, threads, orders[o], merge_a != 0, merge_b != 0, &c))
+                                    add_candidate(P, out, c);
+                            }
+                        }
+            }
     }
 
     // -- staged candidates: a box spanning the leading indices of A and of B
@@ -1517,6 +1553,7 @@ int ttc_plan_get_info(ttc_plan_t plan, ttc_plan_info_t* out)
     out->candidate_count = (int)plan->cands.size();
     out->tuned_ms = C.tuned_ms;
     out->heuristic_cost = C.score;
+    out->merged = C.kernel_class == TTC_KERNEL_MICRO ? (C.kp.micro.merged_a | (C.kp.micro.merged_b << 1)) : 0;
     out->unroll = C.kernel_class == TTC_KERNEL_ROWS ? C.rows.unroll : (C.kernel_class == TTC_KERNEL_MICRO ? C.kp.micro.blocks : 0);
     return TTC_OK;
     });
@@ -1641,12 +1678,20 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
         m.la < 1 || m.lb < 1 || m.pitch < m.la || (m.pitch & 7) || (m.swizzle != 7u && m.swizzle != 0u) || m.la_div.div != (uint32_t)m.la || m.lb_div.div != (uint32_t)m.lb ||
         (int64_t)m.loads * threads < (int64_t)m.la * m.tb || (int64_t)m.blocks * threads < (int64_t)m.la * m.lb ||
         (1 << m.vec_log) != vec || C.lds_bytes != m.tb * m.pitch * 16 || C.lds_bytes > 64 * 1024 || p.grid != p.num_tiles ||
-        m.p0 != P.perm[0] || m.p0 == 0 || m.size_a0 != P.size[0] || m.size_p0 != P.size[m.p0] ||
-        m.stride_a_p0 != P.stride_a[m.p0] || m.stride_b_0 != P.stride_b[0] || P.stride_a[0] != 1 || P.stride_b[m.p0] != 1 ||
-        P.size[0] < vec || P.size[m.p0] < vec)
+        m.p0 != P.perm[0] || m.p0 == 0 || P.ndim < 2 || P.stride_a[0] != 1 || P.stride_b[m.p0] != 1 ||
+        (m.merged_a != 0 && m.merged_a != 1) || (m.merged_b != 0 && m.merged_b != 1))
         return TTC_ERR_INTERNAL;
-    const bool whole = P.size[0] % vec == 0 && P.size[m.p0] % vec == 0;      // else some elements are written twice
-    if (!whole && P.epilogue == TTC_EPI_AXPBY) return TTC_ERR_INTERNAL;
+    const int a1 = 1, p1 = P.perm[1];
+    if (m.merged_a && (P.ndim < 3 || a1 == m.p0 || P.stride_a[a1] != P.size[0] || (m.merged_b && a1 == p1))) return TTC_ERR_INTERNAL;
+    if (m.merged_b && (P.ndim < 3 || p1 == 0 || P.stride_b[p1] != P.size[m.p0] || (m.merged_a && p1 == a1))) return TTC_ERR_INTERNAL;
+    const int64_t cols = m.merged_a ? P.size[0] * P.size[a1] : P.size[0], rows = m.merged_b ? P.size[m.p0] * P.size[p1] : P.size[m.p0];
+    if (m.size_a0 != cols || m.size_p0 != rows || cols < vec || rows < vec || cols >= (int64_t(1) << 31) || rows >= (int64_t(1) << 31) ||
+        m.col_in_div.div != (uint32_t)P.size[0] || m.row_in_div.div != (uint32_t)P.size[m.p0] ||
+        m.col_b_in != P.stride_b[0] || m.col_b_out != (m.merged_a ? P.stride_b[a1] : 0) ||
+        m.row_a_in != P.stride_a[m.p0] || m.row_a_out != (m.merged_b ? P.stride_a[p1] : 0))
+        return TTC_ERR_INTERNAL;
+    const bool whole = cols % vec == 0 && rows % vec == 0;                   // else some elements are written twice ...
+    const bool update = P.epilogue == TTC_EPI_AXPBY;                         // ... unless B is read as well: then blocks write only their own
     auto inside = [&](int64_t off, const int64_t* stride, bool b_side) {
         if (off < 0) return false;
         for (int i = P.ndim - 1; i >= 0; --i) {
@@ -1673,7 +1718,8 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
             std::fill(lds.begin(), lds.end(), (int64_t)-1);
             for (int i = 0; i < vec; ++i)                         // lanes outside load the tile's first vector or block
                 for (int j = 0; j < vec; ++j)
-                    if (!inside(t.a + i * m.stride_a_p0 + j, P.stride_a, false) || !inside(t.b + j * m.stride_b_0 + i, P.stride_b, true))
+                    if (!inside(t.a + micro_row_a(m, t.row0 + (uint32_t)i) + j, P.stride_a, false) ||
+                        !inside(t.b + micro_col_b(m, t.col0 + (uint32_t)j) + i, P.stride_b, true))
                         return TTC_ERR_INTERNAL;
             for (uint32_t tid = 0; tid < threads; ++tid)
                 for (int k = 0; k < (m.loads + 3) / 4 * 4; ++k) { // the kernel walks its loads four at a time
@@ -1685,7 +1731,7 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
                     for (int j = 0; j < vec; ++j) {
                         int64_t src = -2;                         // parked by a lane outside the tensor: must never be read
                         if (ok) {
-                            src = t.a + (int64_t)x.row * m.stride_a_p0 + col + j;
+                            src = t.a + micro_row_a(m, t.row0 + x.row) + col + j;
                             if (!inside(src, P.stride_a, false)) return TTC_ERR_INTERNAL;
                         }
                         if (lds[(size_t)x.chunk * vec + j] != -1) return TTC_ERR_INTERNAL;       // every slot has one writer
@@ -1697,17 +1743,20 @@ static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t
                     const MicroBlock x = micro_block(m, threads, tid, (uint32_t)b);
                     if (!(x.valid && x.row < t.lim_b && x.col < t.lim_a)) continue;
                     const uint32_t row = micro_back(x.row, t.lim_b, (uint32_t)vec), col = micro_back(x.col, t.lim_a, (uint32_t)vec);
+                    const bool edge = update && (row != x.row || col != x.col || x.row < t.own_b || x.col < t.own_a);
+                    const uint32_t first_row = std::max(x.row, t.own_b), first_col = std::max(x.col, t.own_a);
                     for (int i = 0; i < vec; ++i) {
                         const uint64_t chunk = micro_slot(m, row + (uint32_t)i, x.lane_c);
                         if (chunk >= (uint64_t)slots) return TTC_ERR_INTERNAL;
                         for (int j = 0; j < vec; ++j) {
                             const int64_t src = lds[(size_t)chunk * vec + j];
-                            const int64_t dst = t.b + (int64_t)(col + j) * m.stride_b_0 + row + i;
+                            const int64_t dst = t.b + micro_col_b(m, t.col0 + col + (uint32_t)j) + row + i;
                             // what sits in the slot must be the element of the tile at (row + i, col + j)
-                            if (src != t.a + (int64_t)(row + i) * m.stride_a_p0 + col + j) return TTC_ERR_INTERNAL;
+                            if (src != t.a + micro_row_a(m, t.row0 + row + (uint32_t)i) + col + j) return TTC_ERR_INTERNAL;
                             if (!inside(dst, P.stride_b, true)) return TTC_ERR_INTERNAL;
+                            if (edge && !(col + (uint32_t)j >= first_col && row + (uint32_t)i >= first_row)) continue;   // not this block's to update
                             if (b_from_a[dst] == -1) ++written;
-                            else if (whole || b_from_a[dst] != src) return TTC_ERR_INTERNAL;   // a second write brings the same element
+                            else if (whole || update || b_from_a[dst] != src) return TTC_ERR_INTERNAL;   // a second write brings the same element
                             b_from_a[dst] = src;
                         }
                     }

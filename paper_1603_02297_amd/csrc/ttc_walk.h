@@ -178,23 +178,44 @@ TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
 // Where a tile lies and how much of it is inside the tensor along its two indices.  A remainder tile that holds
 // less than one vector along an index is moved back along it until it holds one (the elements it shares with its
 // neighbour are then written twice, with the same value), so lim_a and lim_b are at least vec.
-struct MicroTile { int64_t a, b; uint32_t lim_a, lim_b; };
+// a, b: element offsets in A and B of everything but the tile's two indices, plus (a) the first column's place in A's
+// run and (b) the first row's place in B's run; col0, row0: the tile's first column and row (where a column lies in
+// B and a row in A follows from those, see micro_col_b / micro_row_a).
+// own_a, own_b: the first column and row that are this tile's own (not 0 where the tile was moved back over its neighbour).
+struct MicroTile { int64_t a, b; uint32_t col0, row0, lim_a, lim_b, own_a, own_b; };
 
 TTC_HD MicroTile micro_tile(const KernelParams& p, uint32_t tile)
 {
     const MicroParams& m = p.micro;
-    const TileBase t = tile_base(p, tile);
+    const TileBase t = tile_base(p, tile);      // the plan's strides leave out what depends on the column in B and on the row in A
     const int64_t oa = (int64_t)fdigit(tile, p.tile_below[0], p.tile_cnt[0]) * m.ta;
     const int64_t ob = (int64_t)fdigit(tile, p.tile_below[m.p0], p.tile_cnt[m.p0]) * m.tb;
     int64_t lim_a = m.size_a0 - oa < (int64_t)m.ta ? m.size_a0 - oa : (int64_t)m.ta;
     int64_t lim_b = m.size_p0 - ob < (int64_t)m.tb ? m.size_p0 - ob : (int64_t)m.tb;
     const int64_t back_a = lim_a < m.vec ? m.vec - lim_a : 0, back_b = lim_b < m.vec ? m.vec - lim_b : 0;
     MicroTile r;
-    r.a = t.a - back_a - back_b * m.stride_a_p0;
-    r.b = t.b - back_a * m.stride_b_0 - back_b;
+    r.a = t.a - back_a;
+    r.b = t.b - back_b;
+    r.col0 = (uint32_t)(oa - back_a);
+    r.row0 = (uint32_t)(ob - back_b);
+    r.own_a = (uint32_t)back_a;
+    r.own_b = (uint32_t)back_b;
     r.lim_a = (uint32_t)(lim_a + back_a);
     r.lim_b = (uint32_t)(lim_b + back_b);
     return r;
+}
+
+// Element offset in B of column x (of the whole tensor), and in A of row y.
+TTC_HD int64_t micro_col_b(const MicroParams& m, uint32_t x)
+{
+    const uint32_t out = fdiv(x, m.col_in_div);
+    return (int64_t)(x - out * m.col_in_div.div) * m.col_b_in + (int64_t)out * m.col_b_out;
+}
+
+TTC_HD int64_t micro_row_a(const MicroParams& m, uint32_t y)
+{
+    const uint32_t out = fdiv(y, m.row_in_div);
+    return (int64_t)(y - out * m.row_in_div.div) * m.row_a_in + (int64_t)out * m.row_a_out;
 }
 
 // Where the vector (or block side) that nominally starts at x really starts in a tile holding lim (at least vec)

@@ -103,12 +103,19 @@ class Buffers:
 
 
 def time_candidates(plan, a_ptrs, b_ptrs, stream, warm=1, reps=4):
-    """(info, ms) of every candidate of the plan, in rank order."""
+    """(info, ms) of every candidate of the plan, in rank order (ms: the better of the rule's streaming hints and both sides streamed)."""
     rows = []
     for k in range(ttc.ttc_plan_candidate_count(plan)):
         ttc.ttc_plan_select_candidate(plan, k)
         ms = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, warm, reps)
-        rows.append((ttc.ttc_plan_get_info(plan), ms))
+        info = ttc.ttc_plan_get_info(plan)
+        if not (info["nt_a"] == 1 and info["nt_b"] == 1):     # like the library's search: the better of the rule's hints and both sides streamed
+            ttc.ttc_plan_set_streaming(plan, 1, 1)
+            ms_nt = ttc.ttc_time_execute(plan, a_ptrs, b_ptrs, stream, warm, reps)
+            if ms_nt < ms:
+                ms, info = ms_nt, ttc.ttc_plan_get_info(plan)
+            ttc.ttc_plan_set_streaming(plan, -1, -1)
+        rows.append((info, ms))
     return rows
 
 
@@ -150,28 +157,38 @@ def d2d_copy_gbps(nbytes, a_ptrs, b_ptrs, stream):
 
 
 # ---- study 1: reduction of the search space -------------------------------------------------------
-def search_set(classes, cap):
+def search_set(families, cap):
     """Ranks the library's search times when capped at `cap` candidates (the rule of ttc_plan_tune_pairs): the
-    first `cap` of the ranking, a fifth of the places going to the best-ranked micro-tile candidates where the
-    ranking would have left them out."""
-    total = len(classes)
+    first `cap` of the ranking, a fifth of the places going to the best-ranked micro-tile candidates over single
+    indices and another fifth to those over merged indices where the ranking would have left them out.
+    families: per candidate in rank order, 0 = other kernels, 1 = micro-tile, 2 = micro-tile over merged indices."""
+    total = len(families)
     cap = min(cap, total)
     chosen = list(range(cap))
     if 10 <= cap < total:
-        extra, seen = [], 0
-        for i, cls in enumerate(classes):
-            if seen >= cap // 5:
-                break
-            if cls == ttc.TTC_KERNEL_MICRO:
-                seen += 1
-                if i >= cap:
-                    extra.append(i)
+        extra = []
+        for fam in (1, 2):
+            seen = 0
+            for i, f in enumerate(families):
+                if seen >= cap // 5:
+                    break
+                if f == fam:
+                    seen += 1
+                    if i >= cap:
+                        extra.append(i)
         k = cap - 1
         while k >= 1 and extra:
-            if classes[chosen[k]] != ttc.TTC_KERNEL_MICRO:
+            if families[chosen[k]] == 0:
                 chosen[k] = extra.pop()
             k -= 1
     return chosen
+
+
+def micro_family(info):
+    """0: not the micro-tile kernel; 1: its tile is over single indices; 2: two indices taken as one on a side."""
+    if info["kernel_class"] != ttc.TTC_KERNEL_MICRO:
+        return 0
+    return 2 if info["merged"] else 1
 
 
 def study_search(out, dump=None):
@@ -195,8 +212,8 @@ def study_search(out, dump=None):
         if dump is not None:        # every candidate's configuration and time, one JSON line per problem
             dump.write(json.dumps({"problem": name, "rows": [dict(r[0], ms=r[1]) for r in rows]}) + "\n")
         best = ms.min()
-        classes = [r[0]["kernel_class"] for r in rows]
-        frac = [best / ms[search_set(classes, k)].min() for k in caps]
+        families = [micro_family(r[0]) for r in rows]
+        frac = [best / ms[search_set(families, k)].min() for k in caps]
         table.append((name, len(rows), rows[0][0]["bytes_moved"] / best / 1e6, frac))
         log(f"{name}: {len(rows)} candidates, best {table[-1][2]:.0f} GB/s, " +
             ", ".join(f"first {k}: {100 * f:.1f}%" for k, f in zip(caps, frac)))

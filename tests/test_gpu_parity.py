@@ -236,9 +236,15 @@ def test_odd_benchmark_shapes_full_size(sizes, perm):
 @pytest.mark.parametrize("dtype,sizes,perm,alpha,beta", [
     (wl.F32, (70, 50), (1, 0), 1.0, 0.0),              # moved-back vectors and blocks on both indices
     (wl.F32, (133, 67), (1, 0), 1.5, 0.0),             # remainder tiles narrower than a vector
+    (wl.F32, (133, 67), (1, 0), 0.75, 1.25),           # ... with B read as well: every element updated once
+    (wl.F64, (35, 35, 35), (2, 1, 0), 2.0, -1.0),
     (wl.F64, (35, 35, 35), (2, 1, 0), 1.0, 0.0),
     (wl.F64, (72, 5, 72), (2, 1, 0), 0.75, 1.25),      # tiles of 72 (36 vectors a row), B read as well
     (wl.C64, (24, 7, 40), (2, 0, 1), 0.5 + 0.5j, 1.0 + 0.0j),
+    (wl.F32, (12, 10, 7, 9, 11), (4, 3, 2, 1, 0), 1.0, 0.0),     # two indices taken as one on both sides, ragged
+    (wl.F32, (12, 10, 7, 9, 11), (4, 3, 2, 1, 0), 0.75, 1.25),
+    (wl.F32, (24, 20, 5, 22, 16), (4, 3, 2, 1, 0), 2.0, -1.0),   # ... whole vectors, B read as well
+    (wl.F64, (6, 7, 5, 9), (3, 1, 0, 2), 1.5, 0.0),              # ... on one side only
     (wl.F32, (96, 20, 31), (0, 2, 1), 1.5, 0.0),       # stride-1 index fixed: the row kernel's candidates
     (wl.F32, (85, 9, 13), (0, 2, 1), 2.0, 0.0),        # rows that are no multiple of the vector
 ])

@@ -222,6 +222,9 @@ def test_walks_shapes_with_tails(dtype, sizes, perm):
     (ttc.TTC_F64, (35, 35, 35), (2, 1, 0)),
     (ttc.TTC_F64, (72, 3, 72), (2, 1, 0)),      # tiles of 72: 36 vectors a row, no power of two
     (ttc.TTC_F32, (96, 2, 96), (2, 0, 1)),
+    (ttc.TTC_F32, (12, 5, 7, 9), (3, 2, 1, 0)),         # short leading extents: two indices taken as one, on both sides
+    (ttc.TTC_F64, (6, 7, 5, 9), (3, 1, 0, 2)),          # ... on one side only (B's second index is A's second index)
+    (ttc.TTC_C64, (8, 5, 4, 10), (3, 1, 2, 0)),
 ])
 def test_walks_of_every_micro_tile_candidate(dtype, sizes, perm):
     p = ttc.ttc_plan_create_ex(dtype, len(sizes), sizes, perm)
@@ -239,15 +242,22 @@ def test_walks_of_every_micro_tile_candidate(dtype, sizes, perm):
     ttc.ttc_plan_destroy(p)
 
 
-def test_micro_tile_kernel_is_not_planned_for_updates_of_ragged_tensors():
-    """Elements written twice (moved-back vectors) cannot be read-modify-written: beta != 0 keeps to whole vectors."""
-    for sizes, want in (((70, 50), False), ((72, 48), True)):
-        p = ttc.ttc_plan_create(ttc.TTC_F32, 2, sizes, (1, 0), 1.0, 0.5)
-        classes = set()
+def test_micro_tile_kernel_updates_every_element_of_a_ragged_tensor_once():
+    """beta != 0: moved-back vectors and blocks must not update an element twice; the replay then insists on one
+    write per element (without an update of B a second write with the same source is allowed)."""
+    for sizes, perm in (((70, 50), (1, 0)), ((133, 67), (1, 0)), ((12, 5, 7, 9), (3, 2, 1, 0))):
+        want = [-1] * int(np.prod(sizes))
+        for off_a, off_b in oracle.element_pairs(sizes, perm, None, None):
+            want[off_b] = off_a
+        p = ttc.ttc_plan_create(ttc.TTC_F32, len(sizes), sizes, perm, 1.0, 0.5)
+        seen = 0
         for k in range(ttc.ttc_plan_candidate_count(p)):
             ttc.ttc_plan_select_candidate(p, k)
-            classes.add(ttc.ttc_plan_get_info(p)["kernel_class"])
-        assert (ttc.TTC_KERNEL_MICRO in classes) == want
+            if ttc.ttc_plan_get_info(p)["kernel_class"] != ttc.TTC_KERNEL_MICRO:
+                continue
+            seen += 1
+            assert list(ttc.ttc_debug_emulate_map(p, len(want))) == want, (sizes, perm, k, ttc.ttc_plan_get_info(p))
+        assert seen >= 8
         ttc.ttc_plan_destroy(p)
 
 
