@@ -291,7 +291,8 @@ def main() -> int:
     dom = next((r for r in results if r["case"].startswith("cfg2-f32-p210")), results[0])
     roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom["case"], dom["plan"]),
-                "kernel": "box_kernel", "case": dom["case"], "plan": dom["plan"],
+                "kernel": {"micro": "micro_kernel", "rows": "rows_kernel"}.get(dom["plan"].split(" ")[0], "box_kernel"),
+                "case": dom["case"], "plan": dom["plan"],
                 "algorithmic_bytes_per_launch": dom["traffic_bytes"], "avg_launch_ms": dom["ms"],
                 "median_frac_of_d2d_copy": round(median_frac, 4),
                 "worst_case_vs_copy": worst["case"], "worst_frac_of_d2d_copy": worst["frac_d2d_copy"],

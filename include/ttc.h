@@ -189,11 +189,14 @@ int ttc_plan_set_tile_mapping(ttc_plan_t plan, int mode);
 /*
  * Search (paper Section 3: candidates are timed and the fastest becomes the solution;
  * Table 1 --maxImplementations).  Times at most max_candidates candidates, in heuristic
- * rank order, on the caller's buffers and stream (HIP events, a few launches each, more
+ * rank order (up to two fifths of the places are kept for the best-ranked candidates of
+ * the micro-tile kernel, over single and over merged indices, whose ranking is a model
+ * of its own), on the caller's buffers and stream (HIP events, a few launches each, more
  * of them if a launch takes only microseconds, after about 3 ms of untimed launches that
- * bring an idle GPU up to its clocks) and selects the fastest; the best few are timed
- * again, also with the non-temporal hints switched the other way and with the other
- * tile mappings.  max_candidates: 0 = environment TTC_MAX_CANDIDATES or 200,
+ * bring an idle GPU up to its clocks), each with the non-temporal hints of the rule and
+ * with both sides streamed, and selects the fastest; the best few are timed again, with
+ * every setting of the hints and with the other tile mappings.
+ * max_candidates: 0 = environment TTC_MAX_CANDIDATES or 200,
  * 1 = keep the heuristic choice without timing, -1 = all candidates.
  * A_scratch / B_scratch are DEVICE buffers of prod(sizes) elements; B_scratch is
  * overwritten.  SYNCHRONISES the stream.

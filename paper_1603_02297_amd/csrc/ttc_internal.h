@@ -129,7 +129,7 @@ struct KernelParams {
     Side     b;                      // store walk (B order); unused by the direct kernel
     double   alpha[2];               // re, im (im = 0 for real types)
     double   beta[2];
-    int32_t  debug_stop;             // measurement aid: 1 = every workgroup returns after its set-up
+    int32_t  debug_stop;             // measurement aid: 1 = every workgroup returns after its set-up (micro-tile kernel: 2 = after its loads)
     int32_t  pad_end;
     MicroParams micro;               // micro-tile kernel only
 };

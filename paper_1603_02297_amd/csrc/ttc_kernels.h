@@ -420,6 +420,7 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
     const TileSeq seq = tile_sequence(p, blockIdx.x);
     for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
         const MicroTile t = micro_tile(p, tile_of(seq, q));
+        if (p.debug_stop == 1) return;                        // measurement aid: launch, parameters and tile decode only
         const unsigned char* At = reinterpret_cast<const unsigned char*>(A + t.a);
         unsigned char* Bt = reinterpret_cast<unsigned char*>(B + t.b);
         auto run = [&](auto stream_a, auto stream_b) {
@@ -442,6 +443,7 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
                     if (x[u].valid) lds[x[u].chunk] = in[u].q;
             }
             __syncthreads();
+            if (p.debug_stop == 2) return;                     // measurement aid: ... and the loads of A into LDS
             // ---- B order: LDS -> registers (V x V block) -> epilogue -> global
             for (uint32_t b = 0; b < blocks; ++b) {
                 const MicroBlock x = micro_block(m, threads, tid, b);
@@ -514,7 +516,12 @@ inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipSt
         const void* fn = reinterpret_cast<const void*>(&micro_kernel<TA, MODE, V>);
         const TA* a = static_cast<const TA*>(A);
         TA* b = static_cast<TA*>(B);
-        void* args[] = {const_cast<KernelParams*>(&kp), &a, &b};
+        // TTC_DEBUG_STOP=1 or 2 in the environment: workgroups return early (how the parts of a launch were timed)
+        static const int stop = std::getenv("TTC_DEBUG_STOP") ? std::atoi(std::getenv("TTC_DEBUG_STOP")) : 0;
+        KernelParams stopped;
+        const KernelParams* ready = &kp;
+        if (stop) { stopped = kp; stopped.debug_stop = stop; ready = &stopped; }
+        void* args[] = {const_cast<KernelParams*>(ready), &a, &b};
         return hipLaunchKernel(fn, dim3(grid), dim3(c.threads), args, (size_t)c.lds_bytes, stream);
     }
     return hipErrorInvalidValue;
