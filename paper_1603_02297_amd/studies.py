@@ -415,8 +415,45 @@ def fit_features(r):
     return f
 
 
-def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
-    """Weights of heuristic_cost() from per-candidate timings (the --dump files of `search` and `sweep`).
+FREE_SIGN_MICRO = {"A>1K", "B>1K", "t128", "t64", "ordNotB", "blocks", "lds", "mergeA", "mergeB", "beta"}
+
+
+def fit_micro_features(r):
+    """Features of one timed micro-tile candidate; they mirror the terms of micro_cost() in csrc/ttc_plan.cpp: run
+    length per side (octaves below 128 / 256 / 512 bytes, above 1 KB), remainder tiles, runs that start inside
+    cache lines, workgroup size, tile order, blocks per lane, LDS per workgroup, merged indices and tiles that cut
+    the inner index of a merged pair, idle lanes."""
+    eb = wl.ELEM_BYTES[r["dtype"]]
+    n, sizes, perm = r["ndim"], r["sizes"], r["perm"]
+    p0 = perm[0]
+    ta, tb = r["digit_tile_a"][0], r["digit_tile_a"][1]
+    ma, mb = r["merged"] & 1, (r["merged"] >> 1) & 1
+    cols = sizes[0] * (sizes[1] if ma else 1)
+    rows = sizes[p0] * (sizes[perm[1]] if mb else 1)
+    ra, rb = ta * eb, tb * eb
+    below = lambda v, ref: max(0.0, float(np.log2(ref / v)))
+    above = lambda v, ref: max(0.0, float(np.log2(v / ref)))
+    line = 128 // eb
+    un_a = float(cols % line != 0 or ta % line != 0)
+    un_b = float(rows % line != 0 or tb % line != 0)
+    vec = 16 // eb
+    blocks, th = max(1, r["unroll"]), r["threads"]
+    return {
+        "A<128": below(ra, 128), "A<256": below(ra, 256), "A<512": below(ra, 512), "A>1K": above(ra, 1024),
+        "B<128": below(rb, 128), "B<256": below(rb, 256), "B<512": below(rb, 512), "B>1K": above(rb, 1024),
+        "pad": (-(-cols // ta) * ta / cols) * (-(-rows // tb) * tb / rows) - 1.0,
+        "unA*A<512": un_a * below(ra, 512), "unB*B<512": un_b * below(rb, 512),
+        "t128": float(th == 128), "t64": float(th == 64), "ordNotB": float(r["tile_order"][:n] != perm[:n]),
+        "blocks": float(np.log2(blocks)), "lds": r["lds_bytes"] / 65536.0,
+        "mergeA": float(ma), "mergeB": float(mb),
+        "cutA": float(ma and ta % sizes[0] != 0), "cutB": float(mb and tb % sizes[p0] != 0),
+        "idle": 1.0 - (ta // vec) * (tb // vec) / (blocks * th),
+    }
+
+
+def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8, family="box"):
+    """Weights of heuristic_cost() (family "box") or micro_cost() (family "micro") from per-candidate timings (the
+    --dump files of `search` and `sweep`).
 
     Model: log(time / best time of the problem) = sum_k w_k * feature_k + one free intercept per problem.
     Objective: least squares, each row weighted by exp(-sharpness * log-slowdown) so that the fast candidates, whose
@@ -433,14 +470,18 @@ def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
         with (gzip.open(path, "rt") if path.endswith(".gz") else open(path)) as fh:
             for line in fh:
                 d = json.loads(line)
-                d["rows"] = [r for r in d["rows"] if r["kernel_class"] not in ONE_SHOT]
-                if d["rows"]:
+                if family == "micro":
+                    d["rows"] = [r for r in d["rows"] if r["kernel_class"] == ttc.TTC_KERNEL_MICRO]
+                else:
+                    d["rows"] = [r for r in d["rows"] if r["kernel_class"] not in ONE_SHOT]
+                if len(d["rows"]) >= 4:
                     data.append(d)
+    features, free_sign = (fit_micro_features, FREE_SIGN_MICRO) if family == "micro" else (fit_features, FREE_SIGN)
     names, X, y, grp = None, [], [], []
     for d in data:
         best = min(r["ms"] for r in d["rows"])
         for r in d["rows"]:
-            f = fit_features(r)
+            f = features(r)
             names = names or list(f)
             X.append([f[k] for k in names])
             y.append(np.log(r["ms"] / best))
@@ -451,7 +492,7 @@ def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
     G = np.zeros((len(grp), len(cases)))
     G[np.arange(len(grp)), [index[g] for g in grp]] = 1
     wts = np.exp(-sharpness * y)
-    lo = np.array([(-np.inf if k in FREE_SIGN else 0.0) for k in names] + [-np.inf] * len(cases))
+    lo = np.array([(-np.inf if k in free_sign else 0.0) for k in names] + [-np.inf] * len(cases))
     hi = np.full(len(lo), np.inf)
     full = np.hstack([X, G]) * wts[:, None]
 
@@ -490,6 +531,7 @@ def study_fit(out, dumps, ridge=0.05, sharpness=3.0, folds=8):
     print("refitted order, mean    " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, :4].mean(0)), file=out)
     print("refitted order, minimum " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, :4].min(0)), file=out)
     print("order in the dump, mean " + "  ".join(f"{100 * v:8.2f}%" for v in q[:, 4:].mean(0)), file=out)
+    print("(within the family: the candidates of the other kernel families are left out of both orders)", file=out)
 
 
 def main(argv=None):
@@ -498,6 +540,7 @@ def main(argv=None):
     ap.add_argument("dumps", nargs="*", help="fit: the --dump files of earlier search / sweep runs")
     ap.add_argument("--out", default="", help="write the table to this file (default: stdout)")
     ap.add_argument("--limit", type=int, default=0, help="sweep: only the first LIMIT cases")
+    ap.add_argument("--family", choices=("box", "micro"), default="box", help="fit: the box kernels' model or the micro-tile kernel's")
     ap.add_argument("--dump", default="", help="also write every candidate's configuration and time (JSON lines; .gz compresses)")
     args = ap.parse_args(argv)
     out = open(args.out, "w") if args.out else sys.stdout
@@ -505,8 +548,8 @@ def main(argv=None):
         if not args.dumps:
             print("studies fit: name at least one --dump file", file=sys.stderr)
             return 2
-        print("# python -m paper_1603_02297_amd.studies fit " + " ".join(args.dumps), file=out)
-        study_fit(out, args.dumps)
+        print("# python -m paper_1603_02297_amd.studies fit " + " ".join(args.dumps) + f" --family {args.family}", file=out)
+        study_fit(out, args.dumps, family=args.family)
         if args.out:
             out.close()
         return 0
