@@ -51,8 +51,9 @@ enum {
 /* Kernel families (paper Section 3.1: the stride-1 index keeps its place, or not). */
 enum { TTC_KERNEL_DIRECT = 0 /* tiles, no staging: stride-1 index fixed */, TTC_KERNEL_LDS = 1 /* tile staged through LDS */,
        TTC_KERNEL_ROWS = 2 /* stride-1 index fixed: B walked front to back, rows gathered from A */,
-       TTC_KERNEL_MICRO = 3 /* tile over the two stride-1 indices only: 128-bit LDS accesses, XOR-swizzled rows,
-                               register transposes of 4x4 (2x2) blocks */ };
+       TTC_KERNEL_MICRO = 3 /* tile over the two stride-1 indices only (each possibly merged with the index next to it in
+                               its tensor): 128-bit LDS accesses, XOR-swizzled rows, register transposes of 4x4 (2x2)
+                               blocks; one precision of 4- or 8-byte elements */ };
 /* Epilogues chosen from alpha, beta. */
 enum { TTC_EPI_COPY = 0 /* alpha=1, beta=0 */, TTC_EPI_SCALE = 1 /* beta=0: B never read */, TTC_EPI_AXPBY = 2 };
 

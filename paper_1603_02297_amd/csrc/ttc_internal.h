@@ -87,7 +87,7 @@ struct MicroParams {
     int32_t  merged_a, merged_b;     // 1: the column index is A's indices 0 and 1 taken as one (contiguous in A), the row
                                      // index B's first two indices taken as one (contiguous in B); 0: one index each
     int32_t  vec, vec_log;           // elements in 16 bytes, and its log2
-    int32_t  la, lb;                 // ta / vec and tb / vec: vectors per row of the tile, blocks per column (each at least 8)
+    int32_t  la, lb;                 // ta / vec and tb / vec: vectors per row of the tile, blocks per column
     int32_t  pitch;                  // 16-byte chunks per row of the LDS tile: la rounded up to a multiple of 8
     uint32_t swizzle;                // 7: chunk c of row r sits at c ^ ((r / vec) & 7); 0: rows laid out plainly (measurement aid)
     int32_t  loads;                  // vectors a lane loads per tile: ceil(la * tb / threads)

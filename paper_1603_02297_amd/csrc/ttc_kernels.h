@@ -395,12 +395,14 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
 
 // ---------------------------------------------------------------------------------
 // The micro-tile kernel (the paper's w x w in-register transposition, Section 3.2, in its gfx950 form): a tile over
-// the two stride-1 indices only, every access 128 bits wide.  Lanes load 16-byte vectors along A's stride-1 index
-// and park each with one 128-bit LDS write; after the barrier a lane reads the V x V block it owns with V
-// 128-bit LDS reads (rows of the tile are XOR-swizzled at 16-byte granularity, see MicroParams: neither phase
-// has bank conflicts), transposes it in registers -- no cross-lane traffic: row i of the block is one register
-// quad, column j is element j of each -- and stores V 16-byte vectors along B's stride-1 index.
-// Planned only where both extents are multiples of V and both tensors have one element type.
+// the two stride-1 indices only (each possibly merged with the index next to it in its tensor, see MicroParams),
+// every access 128 bits wide.  Lanes load 16-byte vectors along A's stride-1 index and park each with one 128-bit
+// LDS write; after the barrier a lane reads the V x V block it owns with V 128-bit LDS reads (rows of the tile are
+// XOR-swizzled at 16-byte granularity: neither phase has bank conflicts), transposes it in registers -- no
+// cross-lane traffic: row i of the block is one register quad, column j is element j of each -- and stores V
+// 16-byte vectors along B's stride-1 index.  Extents need not be multiples of V: the last vector of a row and the
+// last block of a column are moved back to end with the tensor (micro_back), and where B is updated as well a
+// moved block writes only what is its own.  Both tensors have one element type of 4 or 8 bytes.
 // ---------------------------------------------------------------------------------
 template <typename T, int MODE, int V>
 __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by_value, const T* __restrict__ A, T* __restrict__ B)
@@ -410,12 +412,11 @@ __global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by
     extern __shared__ __align__(16) unsigned char smem[];
     typedef uint32_t Quad __attribute__((ext_vector_type(4)));
     Quad* lds = reinterpret_cast<Quad*>(smem);
-    constexpr int U = 4;                                       // loads a lane keeps in flight
+    constexpr int U = 4;                                       // loads a lane keeps in flight (eight: 0-5 % slower on the suite)
     constexpr int32_t kScale = (int32_t)sizeof(T);
     const MicroParams& m = p.micro;
     const Epilogue<T, T, MODE> epi(p.alpha, p.beta);
     const uint32_t tid = threadIdx.x, threads = blockDim.x;
-    const uint32_t pitch = (uint32_t)m.pitch;
     const uint32_t loads = (uint32_t)m.loads, blocks = (uint32_t)m.blocks;
     const TileSeq seq = tile_sequence(p, blockIdx.x);
     for (uint32_t q = seq.first; q < seq.end; q += seq.step) {
