@@ -274,3 +274,45 @@ def test_every_candidate_of_the_one_shot_families(dtype, sizes, perm, alpha, bet
         assert ran >= 4, (sizes, perm, ran)
     finally:
         ttc.ttc_plan_destroy(plan)
+
+
+@pytest.mark.gpu
+def test_random_problems_through_the_micro_tile_families():
+    """Random 3-D to 6-D shapes with odd extents, every element type the micro-tile kernel takes, with and without
+    an update of B: the best-ranked candidates over single and over merged indices against the oracle."""
+    rng = np.random.default_rng(1603)
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    ran = {1: 0, 2: 0}
+    for trial in range(36):
+        ndim = int(rng.integers(3, 7))
+        sizes, perm = wl.random_problem(rng, ndim, 400000, 26)
+        dtype = (wl.F32, wl.F64, wl.C64)[trial % 3]
+        alpha, beta = SCALARS[dtype][trial % len(SCALARS[dtype])]
+        n = int(np.prod(sizes))
+        A = wl.uniform_tensor(dtype, n, 5000 + trial)
+        B0 = wl.uniform_tensor(dtype, n, 6000 + trial)
+        want = oracle.transpose(dtype, sizes, perm, alpha, beta, A, B0.copy(), 4)
+        pure = (complex(alpha) == 1 and complex(beta) == 0)
+        dA, dB0 = torch.from_numpy(A).to(dev), torch.from_numpy(B0).to(dev)
+        plan = ttc.ttc_plan_create(dtype, len(sizes), sizes, perm, alpha, beta)
+        try:
+            taken = {1: 0, 2: 0}
+            for k in range(ttc.ttc_plan_candidate_count(plan)):
+                ttc.ttc_plan_select_candidate(plan, k)
+                info = ttc.ttc_plan_get_info(plan)
+                if info["kernel_class"] != ttc.TTC_KERNEL_MICRO:
+                    continue
+                fam = 2 if info["merged"] else 1
+                if taken[fam] >= 3:
+                    continue
+                taken[fam] += 1
+                dB = dB0.clone()
+                ttc.ttc_execute(plan, dA.data_ptr(), dB.data_ptr(), stream)
+                torch.cuda.synchronize()
+                d = ulp_distance(dB.cpu().numpy(), want)
+                assert d <= (0 if pure else 1), (sizes, perm, alpha, beta, k, d, info)
+                ran[fam] += 1
+        finally:
+            ttc.ttc_plan_destroy(plan)
+    assert ran[1] >= 20 and ran[2] >= 20, ran
