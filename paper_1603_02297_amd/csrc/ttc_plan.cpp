@@ -749,6 +749,9 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     if (merge_a) { extent[a1] = 1; kp.stride_a[a1] = kp.stride_b[a1] = 0; }
     if (merge_b) { extent[p1] = 1; kp.stride_a[p1] = kp.stride_b[p1] = 0; }
     for (int k = 0; k < kMaxDim; ++k) kp.tile[k] = C.tile[k];
+    uint32_t ordered = 0;                        // the order has to name every index of the problem once
+    for (int i = 0; i < P.ndim; ++i) if (tile_order[i] >= 0 && tile_order[i] < P.ndim) ordered |= 1u << tile_order[i];
+    if (ordered != (1u << P.ndim) - 1u) return false;
     for (int i = 0; i < P.ndim; ++i) {
         const int k = tile_order[i];
         const int64_t cnt = ceil_div(extent[k], C.tile[k]);
@@ -1331,7 +1334,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                         for (int lb : lbs) {
                             const int64_t blocks = ceil_div((int64_t)la * lb, threads);
                             if (blocks > 6 || (int64_t)la * lb * 5 < blocks * threads * 4) continue;      // lanes mostly busy
-                            for (int o = 0; o < (quick ? 1 : 2); ++o) {       // the mixed orders time the same (384^3, 72^4 reversals)
+                            for (int o = 0; o < (quick ? 1 : 2); ++o) {       // the mixed orders, and the indices outside the tile first, time the same (384^3, 72^4, 6-D reversals)
                                 Candidate c;
                                 if (make_micro_candidate(P, la * vec, lb * vec, threads, orders[o], merge_a != 0, merge_b != 0, &c))
                                     add_candidate(P, out, c);
