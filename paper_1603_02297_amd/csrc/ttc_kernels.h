@@ -405,10 +405,10 @@ __global__ __launch_bounds__(kRowsThreads) void rows_kernel(const RowsParams p, 
 // moved block writes only what is its own.  Both tensors have one element type of 4 or 8 bytes.
 // ---------------------------------------------------------------------------------
 template <typename T, int MODE, int V>
-__global__ __launch_bounds__(256) void micro_kernel(const KernelParams params_by_value, const T* __restrict__ A, T* __restrict__ B)
+__global__ __launch_bounds__(256) void micro_kernel(const MicroArgs args_by_value, const T* __restrict__ A, T* __restrict__ B)
 {
     static_assert(V * sizeof(T) == 16, "one 16-byte vector");
-    const KernelParams& p = *reinterpret_cast<const KernelParams*>((const void*)__builtin_amdgcn_kernarg_segment_ptr());
+    const MicroArgs& p = *reinterpret_cast<const MicroArgs*>((const void*)__builtin_amdgcn_kernarg_segment_ptr());
     extern __shared__ __align__(16) unsigned char smem[];
     typedef uint32_t Quad __attribute__((ext_vector_type(4)));
     Quad* lds = reinterpret_cast<Quad*>(smem);
@@ -519,10 +519,9 @@ inline hipError_t launch_micro(const Candidate& c, const void* A, void* B, hipSt
         TA* b = static_cast<TA*>(B);
         // TTC_DEBUG_STOP=1 or 2 in the environment: workgroups return early (how the parts of a launch were timed)
         static const int stop = std::getenv("TTC_DEBUG_STOP") ? std::atoi(std::getenv("TTC_DEBUG_STOP")) : 0;
-        KernelParams stopped;
-        const KernelParams* ready = &kp;
-        if (stop) { stopped = kp; stopped.debug_stop = stop; ready = &stopped; }
-        void* args[] = {const_cast<KernelParams*>(ready), &a, &b};
+        MicroArgs ready = micro_args(c);
+        ready.debug_stop = stop;
+        void* args[] = {&ready, &a, &b};
         return hipLaunchKernel(fn, dim3(grid), dim3(c.threads), args, (size_t)c.lds_bytes, stream);
     }
     return hipErrorInvalidValue;

@@ -805,6 +805,38 @@ static bool make_micro_candidate(const Problem& P, int ta, int tb, int threads, 
     return true;
 }
 
+// The micro-tile kernel's argument block from a candidate as it stands (tile mapping, streaming hints and grid are
+// the plan's current ones).
+MicroArgs micro_args(const Candidate& c)
+{
+    const KernelParams& kp = c.kp;
+    MicroArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.xcd_remap = kp.xcd_remap;
+    a.num_tiles = kp.num_tiles; a.tiles_per_xcd = kp.tiles_per_xcd; a.tiles_rem_xcd = kp.tiles_rem_xcd;
+    a.grid = kp.grid; a.grid_per_xcd = kp.grid_per_xcd; a.grid_rem_xcd = kp.grid_rem_xcd;
+    for (int x = 0; x < 8; ++x) a.xcd_tiles[x] = kp.xcd_tiles[x];
+    a.nt_a = kp.nt_a; a.nt_b = kp.nt_b;
+    a.debug_stop = 0;
+    a.col_pos = a.row_pos = -1;
+    for (int i = 0; i < kMaxDim; ++i) {
+        a.cnt[i] = make_fastdiv(1);
+        a.step_a[i] = a.step_b[i] = 0;
+    }
+    for (int i = 0; i < kp.n && i < kMaxDim; ++i) {
+        const int k = c.tile_order[i];
+        a.cnt[i] = kp.tile_cnt[k];
+        a.step_a[i] = (int64_t)kp.tile[k] * kp.stride_a[k];
+        a.step_b[i] = (int64_t)kp.tile[k] * kp.stride_b[k];
+        if (k == 0) a.col_pos = i;
+        if (k == kp.micro.p0) a.row_pos = i;
+    }
+    a.alpha[0] = kp.alpha[0]; a.alpha[1] = kp.alpha[1];
+    a.beta[0] = kp.beta[0];   a.beta[1] = kp.beta[1];
+    a.micro = kp.micro;
+    return a;
+}
+
 // The row kernel's candidate: B walked front to back, `vec` elements per lane and access.  Needs rows that are
 // contiguous in both tensors and hold at least one vector, fewer than 2^31 rows, rows shorter than 2^30.
 static bool make_rows_candidate(const Problem& P, int vec, int unroll, Candidate* out)
@@ -1691,11 +1723,12 @@ static int emulate_rows(const ttc::Problem& P, const ttc::Candidate& C, int64_t*
 static int emulate_micro(const ttc::Problem& P, const ttc::Candidate& C, int64_t* b_from_a)
 {
     using namespace ttc;
-    const KernelParams& p = C.kp;
+    const MicroArgs p = micro_args(C);          // what the launch hands to the kernel
     const MicroParams& m = p.micro;
     for (int64_t i = 0; i < P.span_b; ++i) b_from_a[i] = -1;
     const uint32_t threads = (uint32_t)C.threads;
     const int vec = m.vec;
+    if (p.col_pos < 0 || p.row_pos < 0 || p.col_pos == p.row_pos) return TTC_ERR_INTERNAL;
     if ((vec != 2 && vec != 4) || vec * P.eb_a != 16 || P.eb_a != P.eb_b ||
         (threads != 64 && threads != 128 && threads != 256) || m.ta != vec * m.la || m.tb != vec * m.lb ||
         m.la < 1 || m.lb < 1 || m.pitch < m.la || (m.pitch & 7) || (m.swizzle != 7u && m.swizzle != 0u) || m.la_div.div != (uint32_t)m.la || m.lb_div.div != (uint32_t)m.lb ||

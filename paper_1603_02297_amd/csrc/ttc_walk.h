@@ -81,7 +81,8 @@ TTC_HD RowAccess rows_access(const RowsParams& p, int64_t base, uint32_t row0, u
 // XCDs in turn (neighbours inside a chunk share an L2 and the window still advances as one).
 struct TileSeq { uint32_t first, end, step, base, xcd, chunk_log; };
 
-TTC_HD TileSeq tile_sequence(const KernelParams& p, uint32_t wg)
+template <typename Params>       // KernelParams, or the micro-tile kernel's MicroArgs
+TTC_HD TileSeq tile_sequence(const Params& p, uint32_t wg)
 {
     TileSeq s;
     s.base = 0; s.xcd = 0; s.chunk_log = 0;
@@ -184,12 +185,24 @@ TTC_HD SideLim side_lim(const Side& s, const TileLim& t)
 // own_a, own_b: the first column and row that are this tile's own (not 0 where the tile was moved back over its neighbour).
 struct MicroTile { int64_t a, b; uint32_t col0, row0, lim_a, lim_b, own_a, own_b; };
 
-TTC_HD MicroTile micro_tile(const KernelParams& p, uint32_t tile)
+TTC_HD MicroTile micro_tile(const MicroArgs& p, uint32_t tile)
 {
     const MicroParams& m = p.micro;
-    const TileBase t = tile_base(p, tile);      // the plan's strides leave out what depends on the column in B and on the row in A
-    const int64_t oa = (int64_t)fdigit(tile, p.tile_below[0], p.tile_cnt[0]) * m.ta;
-    const int64_t ob = (int64_t)fdigit(tile, p.tile_below[m.p0], p.tile_cnt[m.p0]) * m.tb;
+    // mixed radix in tile order; straight-line over all kMaxDim places (unused ones hold one tile and no step).
+    // The steps leave out what depends on the column in B and on the row in A.
+    struct { int64_t a, b; } t = {0, 0};
+    uint32_t rest = tile, da = 0, db = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxDim; ++i) {
+        const uint32_t next = fdiv(rest, p.cnt[i]);
+        const uint32_t d = rest - next * p.cnt[i].div;
+        rest = next;
+        t.a += (int64_t)d * p.step_a[i];
+        t.b += (int64_t)d * p.step_b[i];
+        if (i == p.col_pos) da = d;
+        if (i == p.row_pos) db = d;
+    }
+    const int64_t oa = (int64_t)da * m.ta, ob = (int64_t)db * m.tb;
     int64_t lim_a = m.size_a0 - oa < (int64_t)m.ta ? m.size_a0 - oa : (int64_t)m.ta;
     int64_t lim_b = m.size_p0 - ob < (int64_t)m.tb ? m.size_p0 - ob : (int64_t)m.tb;
     const int64_t back_a = lim_a < m.vec ? m.vec - lim_a : 0, back_b = lim_b < m.vec ? m.vec - lim_b : 0;
