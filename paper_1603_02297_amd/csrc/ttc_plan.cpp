@@ -1449,8 +1449,10 @@ int build_plan(int dtype, int ndim, const int64_t* sizes, const int* perm, const
         std::fprintf(stderr, "ttc: plan dtype %d, %d fused indices, %s kernel, tile", P.dtype, P.ndim,
                      c.kernel_class == TTC_KERNEL_DIRECT ? "direct" : (c.kernel_class == TTC_KERNEL_ROWS ? "row" : (c.kernel_class == TTC_KERNEL_MICRO ? "micro-tile" : "staged")));
         for (int k = 0; k < P.ndim; ++k) std::fprintf(stderr, " %d", c.tile[k]);
-        std::fprintf(stderr, ", vectors %d/%d, %d threads, %d B LDS, cost %.4f (best of %zu quick candidates)\n",
-                     c.kp.a.vec, c.kp.b.vec, c.threads, c.lds_bytes, c.score, quick.size());
+        size_t per_class[4] = {0, 0, 0, 0};
+        for (const Candidate& q : quick) if (q.kernel_class >= 0 && q.kernel_class < 4) ++per_class[q.kernel_class];
+        std::fprintf(stderr, ", vectors %d/%d, %d threads, %d B LDS, cost %.4f (best of %zu candidates of the short list: %zu direct, %zu staged, %zu row, %zu micro-tile)\n",
+                     c.kp.a.vec, c.kp.b.vec, c.threads, c.lds_bytes, c.score, quick.size(), per_class[0], per_class[1], per_class[2], per_class[3]);
     }
     return TTC_OK;
 }
