@@ -1318,15 +1318,13 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                     if (spanned > kBoxDims || vol * eb > 128 * 1024) continue;
                     if (vol * eb < 4096 && vol < P.elements) continue;
                     if (!shapes.first_time(t, v, 0)) continue;
-                    for (int o = 0; o < norders; ++o) {
-                        if (quick && o == 1) continue;      // A's order is never ranked ahead of B's for the same tile
+                    for (int o = 0; o < norders; ++o)
                         for (int li = 0; li < nshapes; ++li) {
                             const LaunchShape& ls = kLaunchShapes[li];
                             Candidate c;
                             if (make_candidate(P, t, v, true, ls.threads, ls.wg_per_cu, orders[o], kDefaultTileMapping, &c))
                                 add_candidate(P, out, c);
                         }
-                    }
                 }
         }
     }
@@ -1409,8 +1407,7 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                         for (int nbuf = 2; nbuf >= 1; --nbuf) {
                             if (nbuf == 1 && vol * eb < 8192) continue;     // small tiles can afford two buffers
                             for (int mg = 0; mg < (quick ? 1 : 4); ++mg)
-                                for (int o = 0; o < norders; ++o) {
-                                    if (quick && o == 1) continue;      // A's order is never ranked ahead of B's for the same tile
+                                for (int o = 0; o < norders; ++o)
                                     for (int li = 0; li < nshapes; ++li) {
                                         const LaunchShape& ls = kLaunchShapes[li];
                                         Candidate c;
@@ -1418,7 +1415,6 @@ static void enumerate(const Problem& P, std::vector<Candidate>& out_list, bool q
                                                            &c, (mg & 1) == 0, (mg & 2) == 0, &cache, nbuf))
                                             add_candidate(P, out, c);
                                     }
-                                }
                         }
                     }
         }
